@@ -1,0 +1,183 @@
+"""EGGROLL CPU oracle (test infrastructure, not product code).
+
+Thin ctypes/numpy wrapper around ``eggroll_oracle.c``.  Only ``tests/``, the smoke check and the
+benchmark's ``cpu_baseline`` leg may import this package; the product (``paper_2511_16652_amd``)
+never does.  Every function here cites the passage of the paper it follows in the C source.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "eggroll_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+NOISE_F32 = 0
+NOISE_BF16 = 1
+ACT_NONE = 0
+ACT_GELU = 1
+WHICH_A = 0
+WHICH_B = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP); returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u64, u32, i64, i32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int64, ctypes.c_int
+        dbl, vp = ctypes.c_double, ctypes.c_void_p
+        lib.oracle_threefry2x32_20.argtypes = [vp, vp, vp]
+        lib.oracle_threefry2x32_20.restype = None
+        lib.oracle_stream_key.argtypes = [u64, u32, u32, i32, vp]
+        lib.oracle_stream_key.restype = None
+        lib.oracle_raw_words.argtypes = [u64, u32, u32, i32, i64, u64, u64, vp]
+        lib.oracle_raw_words.restype = None
+        lib.oracle_noise_normal.argtypes = [u64, u32, u32, i32, i64, u64, u64, vp]
+        lib.oracle_noise_normal.restype = None
+        lib.oracle_int_from_byte.argtypes = [ctypes.c_uint, i32]
+        lib.oracle_int_from_byte.restype = i32
+        lib.oracle_noise_int.argtypes = [u64, u32, u32, i32, i64, u64, u64, i32, vp]
+        lib.oracle_noise_int.restype = None
+        lib.oracle_round_bf16.argtypes = [dbl]
+        lib.oracle_round_bf16.restype = dbl
+        lib.oracle_noise_matrix.argtypes = [u64, u32, u32, i32, i64, i64, i32, i32, vp]
+        lib.oracle_noise_matrix.restype = None
+        lib.oracle_forward.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, dbl, i32,
+                                       vp, vp, vp]
+        lib.oracle_forward.restype = i32
+        lib.oracle_update.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, vp, dbl, vp]
+        lib.oracle_update.restype = i32
+        lib.oracle_update_entry.argtypes = [u64, u32, u32, i64, i64, i32, i32, vp, dbl, i64, i64]
+        lib.oracle_update_entry.restype = dbl
+        lib.oracle_forward_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32,
+                                          vp, vp, vp]
+        lib.oracle_forward_i8.restype = None
+        lib.oracle_threads.argtypes = []
+        lib.oracle_threads.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def threads() -> int:
+    return int(_load().oracle_threads())
+
+
+def threefry2x32_20(counter, key) -> np.ndarray:
+    """One Threefry-2x32-20 block: counter[2], key[2] (uint32) -> 2 uint32."""
+    c = _c(counter, np.uint32)
+    k = _c(key, np.uint32)
+    assert c.shape == (2,) and k.shape == (2,)
+    out = np.empty(2, np.uint32)
+    _load().oracle_threefry2x32_20(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def stream_key(seed, step, layer, which) -> np.ndarray:
+    """The derived 64-bit key of one (seed, step, layer, which) stream, as 2 uint32."""
+    out = np.empty(2, np.uint32)
+    _load().oracle_stream_key(seed, step, layer, which, _ptr(out))
+    return out
+
+
+def raw_words(seed, step, layer, which, member, first_word, n) -> np.ndarray:
+    out = np.empty(int(n), np.uint32)
+    _load().oracle_raw_words(seed, step, layer, which, member, first_word, n, _ptr(out))
+    return out
+
+
+def noise_normal(seed, step, layer, which, member, first, n) -> np.ndarray:
+    """fp64 Box-Muller normals with flat indices first..first+n-1 (before storage rounding)."""
+    out = np.empty(int(n), np.float64)
+    _load().oracle_noise_normal(seed, step, layer, which, member, first, n, _ptr(out))
+    return out
+
+
+def int_from_byte(byte: int, bound: int) -> int:
+    return int(_load().oracle_int_from_byte(byte, bound))
+
+
+def noise_int(seed, step, layer, which, member, first, n, bound) -> np.ndarray:
+    out = np.empty(int(n), np.int8)
+    _load().oracle_noise_int(seed, step, layer, which, member, first, n, bound, _ptr(out))
+    return out
+
+
+def round_bf16(v: float) -> float:
+    return float(_load().oracle_round_bf16(float(v)))
+
+
+def noise_matrix(seed, step, layer, which, member, d, rank, noise_dtype) -> np.ndarray:
+    """A_i (which=0) or B_i (which=1) as stored: fp64 array [d, rank] of storage-dtype values."""
+    out = np.empty((int(d), int(rank)), np.float64)
+    _load().oracle_noise_matrix(seed, step, layer, which, member, d, rank, noise_dtype, _ptr(out))
+    return out
+
+
+def forward(seed, step, layer, member_begin, member_count, S, d_out, d_in, rank, noise_dtype,
+            sigma, act, W, X) -> np.ndarray:
+    """Explicit-W_i population forward; returns fp64 Y[member_count*S, d_out] (unrounded)."""
+    W = _c(W, np.float64)
+    X = _c(X, np.float64)
+    assert W.shape == (d_out, d_in) and X.shape == (member_count * S, d_in)
+    Y = np.empty((member_count * S, d_out), np.float64)
+    rc = _load().oracle_forward(seed, step, layer, member_begin, member_count, S, d_out, d_in,
+                                rank, noise_dtype, float(sigma), act, _ptr(W), _ptr(X), _ptr(Y))
+    if rc != 0:
+        raise MemoryError("oracle_forward")
+    return Y
+
+
+def update(seed, step, layer, member_begin, member_count, d_out, d_in, rank, noise_dtype,
+           fitness, scale) -> np.ndarray:
+    """G = scale * sum_i f_i A_i B_i^T as explicit outer products; fp64 [d_out, d_in]."""
+    f = _c(fitness, np.float64)
+    assert f.shape == (member_count,)
+    G = np.empty((d_out, d_in), np.float64)
+    rc = _load().oracle_update(seed, step, layer, member_begin, member_count, d_out, d_in, rank,
+                               noise_dtype, _ptr(f), float(scale), _ptr(G))
+    if rc != 0:
+        raise MemoryError("oracle_update")
+    return G
+
+
+def update_entry(seed, step, layer, member_begin, member_count, rank, noise_dtype, fitness, scale,
+                 j, k) -> float:
+    f = _c(fitness, np.float64)
+    return float(_load().oracle_update_entry(seed, step, layer, member_begin, member_count, rank,
+                                             noise_dtype, _ptr(f), float(scale), j, k))
+
+
+def forward_i8(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift,
+               steps, W, H_in) -> np.ndarray:
+    W = _c(W, np.int8)
+    H = _c(H_in, np.int8)
+    assert W.shape == (d, d) and H.shape == (member_count, d)
+    out = np.empty_like(H)
+    _load().oracle_forward_i8(seed, step, layer, member_begin, member_count, d, bound, corr_shift,
+                              out_shift, steps, _ptr(W), _ptr(H), _ptr(out))
+    return out

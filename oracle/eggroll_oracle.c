@@ -1,0 +1,367 @@
+/*
+ * EGGROLL CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, obviously-correct implementation of what the GPU hot path computes, written from
+ * the paper's statement of the method ("Evolution Strategies at the Hyperscale", EGGROLL):
+ *
+ *   - noise:   A_i in R^{d_out x r}, B_i in R^{d_in x r} as a pure function of
+ *              (seed, step, layer, which, member, flat index)   [Sec. 1 "counter-based deterministic
+ *              RNG ... reconstruct noise on demand"; Alg. 1 "reconstruct E_j from seeds"]
+ *   - forward: for every member i, materialise W_i = M + (sigma/sqrt(r)) A_i B_i^T as a dense fp64
+ *              matrix and multiply                               [Alg. 1 line f_i <- f(W = M + sigma E_i),
+ *              E_i = A_i B_i^T / sqrt(r); Sec. 4.1]
+ *   - update:  G = scale * sum_i f_i A_i B_i^T as N*r explicit outer products in fp64
+ *              [EGGROLL UPDATE box, Eq. (eggroll_update); the 1/(sigma N) constant of Eq. (matrix_mc)]
+ *   - int8:    the integer perturbed matmul step by step        [App. "Adding EGGROLL Perturbations"]
+ *
+ * It deliberately does NOT use the factored form u M^T + (sigma/sqrt r)(u B)A^T or the
+ * (diag(f)A)^T B contraction of Sec. 4.2: those are what the GPU path uses, and the tests check
+ * that the two agree.  Nothing here is shared with the HIP sources (no common header, table or
+ * helper).  Only tests, the smoke check and the benchmark's cpu_baseline leg may call this file.
+ *
+ * Pins (tests/test_oracle_*.py): the Threefry block function against rocRAND's host-callable
+ * Threefry-2x32-20 engine; the normal transform against N(0,1) moments / KS and the K_0 product density of the
+ * mean-field appendix; the integer map exhaustively; forward/update against brute-force numpy,
+ * closed forms and the identities of Sec. 4.2.  Parity against the authors' own JAX noise stream
+ * is unpinned: the paper does not publish its stream and it need not be matched.
+ *
+ * Build: gcc -O2 -fopenmp -fPIC -shared -o liboracle.so eggroll_oracle.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------------------------ */
+/* Threefry-2x32, 20 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as  */
+/* 1, 2, 3", SC'11) -- the counter-based generator the paper cites for noise reconstruction    */
+/* (it is the block function of the JAX PRNG the paper's code base uses).                      */
+/* ------------------------------------------------------------------------------------------ */
+
+static uint32_t rotl32(uint32_t v, unsigned s) { return (v << s) | (v >> (32u - s)); }
+
+/* rotation amounts of Threefry-2x32, indexed by round mod 8 */
+static const unsigned TF_ROT[8] = {13, 15, 26, 6, 17, 29, 16, 24};
+
+void oracle_threefry2x32_20(const uint32_t ctr[2], const uint32_t key[2], uint32_t out[2])
+{
+    uint32_t ks[3];
+    ks[0] = key[0];
+    ks[1] = key[1];
+    ks[2] = 0x1BD11BDAu ^ key[0] ^ key[1]; /* Threefish key-schedule parity word, 32-bit form */
+    uint32_t x0 = ctr[0] + ks[0];
+    uint32_t x1 = ctr[1] + ks[1];
+    for (int round = 0; round < 20; ++round) {
+        x0 += x1;
+        x1 = rotl32(x1, TF_ROT[round % 8]);
+        x1 ^= x0;
+        if ((round & 3) == 3) { /* key injection after every fourth round */
+            const uint32_t s = (uint32_t)(round / 4 + 1);
+            x0 += ks[s % 3u];
+            x1 += ks[(s + 1u) % 3u] + s;
+        }
+    }
+    out[0] = x0;
+    out[1] = x1;
+}
+
+/*
+ * Stream addressing (this build's contract; the paper only requires "known random seeds").
+ *   stream key  = Threefry(key = (seed low 32, seed high 32), counter = (step, layer | which<<31))
+ *                 which: A = 0, B = 1; layer < 2^31
+ *   block b of member i = Threefry(key = stream key, counter = (b, i)),  0 <= i < 2^32
+ * One block yields output words 2b and 2b+1 of that member's vector.
+ */
+static void stream_key(uint64_t seed, uint32_t step, uint32_t layer, int which, uint32_t out[2])
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const uint32_t ctr[2] = {step, (layer & 0x7FFFFFFFu) | ((uint32_t)(which & 1) << 31)};
+    oracle_threefry2x32_20(ctr, key, out);
+}
+
+static void noise_block(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
+                        uint32_t block, uint32_t out[2])
+{
+    uint32_t sk[2];
+    stream_key(seed, step, layer, which, sk);
+    const uint32_t ctr[2] = {block, (uint32_t)((uint64_t)member)};
+    oracle_threefry2x32_20(ctr, sk, out);
+}
+
+void oracle_stream_key(uint64_t seed, uint32_t step, uint32_t layer, int which, uint32_t out[2])
+{
+    stream_key(seed, step, layer, which, out);
+}
+
+/* raw words first_word .. first_word+n-1 of one member's stream */
+void oracle_raw_words(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
+                      uint64_t first_word, uint64_t n, uint32_t* out)
+{
+    for (uint64_t w = 0; w < n; ++w) {
+        const uint64_t word = first_word + w;
+        uint32_t blk[2];
+        noise_block(seed, step, layer, which, member, (uint32_t)(word >> 1), blk);
+        out[w] = blk[word & 1u];
+    }
+}
+
+/*
+ * Standard normals, one 32-bit word per value.  The paper leaves the transform open (Assumption 1
+ * asks only for iid, zero-mean, symmetric, unit-variance entries; the configs ask for Gaussians).
+ * Reading used here: the top 23 bits of a word give u = (k + 1/2) 2^-23 in (0,1); words (2p, 2p+1)
+ * form a Box-Muller pair: rho = sqrt(-2 ln u1); z_2p = rho cos(2 pi u2), z_2p+1 = rho sin(2 pi u2).
+ * Value with flat index n (= d*rank + l) is z_n.  Evaluated in fp64.
+ */
+static double word_to_unit(uint32_t w) { return ((double)(w >> 9) + 0.5) * (1.0 / 8388608.0); }
+
+void oracle_noise_normal(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
+                         uint64_t first, uint64_t n, double* out)
+{
+    static const double TWO_PI = 6.283185307179586476925286766559;
+    for (uint64_t v = 0; v < n; ++v) {
+        const uint64_t idx = first + v;
+        uint32_t blk[2];
+        noise_block(seed, step, layer, which, member, (uint32_t)(idx >> 1), blk);
+        const double u1 = word_to_unit(blk[0]);
+        const double u2 = word_to_unit(blk[1]);
+        const double rho = sqrt(-2.0 * log(u1));
+        out[v] = (idx & 1u) ? rho * sin(TWO_PI * u2) : rho * cos(TWO_PI * u2);
+    }
+}
+
+/*
+ * Bounded integers on {-b..b} from the BYTES of the same stream: value n uses word n>>2, byte n&3
+ * (little end first).  With m = 2b+1 and q = floor(256/m): byte < q*m -> floor(byte/q) - b, else 0.
+ * Exactly symmetric and zero-mean (Assumption 1), no floating point (App. "Adding EGGROLL
+ * Perturbations" keeps float arithmetic off the accelerator).  b = 0 gives all zeros.
+ */
+int oracle_int_from_byte(unsigned byte, int bound)
+{
+    const int m = 2 * bound + 1;
+    const int q = 256 / m;
+    return ((int)byte < q * m) ? (int)byte / q - bound : 0;
+}
+
+void oracle_noise_int(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
+                      uint64_t first, uint64_t n, int bound, int8_t* out)
+{
+    for (uint64_t v = 0; v < n; ++v) {
+        const uint64_t idx = first + v;
+        uint32_t blk[2];
+        noise_block(seed, step, layer, which, member, (uint32_t)(idx >> 3), blk);
+        const uint32_t word = blk[(idx >> 2) & 1u];
+        out[v] = (int8_t)oracle_int_from_byte((word >> (8u * (unsigned)(idx & 3u))) & 0xFFu, bound);
+    }
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* storage roundings (round-to-nearest-even), so the oracle sees exactly the values the method */
+/* stores: fp32 noise in fp32 mode; fp32 then bfloat16 in bf16 mode.                            */
+/* ------------------------------------------------------------------------------------------ */
+double oracle_round_f32(double v) { return (double)(float)v; }
+
+double oracle_round_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    if ((bits & 0x7F800000u) == 0x7F800000u) return (double)f; /* inf / nan pass through */
+    const uint32_t lsb = (bits >> 16) & 1u;
+    bits += 0x7FFFu + lsb;
+    bits &= 0xFFFF0000u;
+    memcpy(&f, &bits, 4);
+    return (double)f;
+}
+
+static double round_storage(double v, int noise_dtype) /* 0 = fp32, 1 = bf16 */
+{
+    return noise_dtype == 1 ? oracle_round_bf16(v) : oracle_round_f32(v);
+}
+
+/* A_i (which = 0, d = d_out) or B_i (which = 1, d = d_in) as stored: out[d*rank], index d*rank+l */
+void oracle_noise_matrix(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
+                         int64_t d, int rank, int noise_dtype, double* out)
+{
+    const uint64_t n = (uint64_t)d * (uint64_t)rank;
+    oracle_noise_normal(seed, step, layer, which, member, 0, n, out);
+    for (uint64_t v = 0; v < n; ++v) out[v] = round_storage(out[v], noise_dtype);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* forward: explicit W_i per member                                                            */
+/* ------------------------------------------------------------------------------------------ */
+static double gelu_exact(double x) { return 0.5 * x * (1.0 + erf(x * 0.70710678118654752440)); }
+
+/*
+ * Y[row, j] = act( sum_k W_i[j,k] X[row,k] ),  W_i = W + (sigma/sqrt(rank)) A_i B_i^T,
+ * rows of X are member-major: member(row) = member_begin + row / S.
+ * W[d_out*d_in], X[count*S*d_in], Y[count*S*d_out] all fp64 holding storage-dtype values.
+ * Returns 0, or -1 if memory for the per-thread W_i could not be obtained.
+ */
+int oracle_forward(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                   int64_t member_count, int S, int d_out, int d_in, int rank, int noise_dtype,
+                   double sigma, int act, const double* W, const double* X, double* Y)
+{
+    const double c = sigma / sqrt((double)rank);
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* Wi = (double*)malloc(sizeof(double) * (size_t)d_out * (size_t)d_in);
+        double* A = (double*)malloc(sizeof(double) * (size_t)d_out * (size_t)rank);
+        double* B = (double*)malloc(sizeof(double) * (size_t)d_in * (size_t)rank);
+        if (!Wi || !A || !B) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t m = 0; m < member_count; ++m) {
+                const int64_t member = member_begin + m;
+                oracle_noise_matrix(seed, step, layer, 0, member, d_out, rank, noise_dtype, A);
+                oracle_noise_matrix(seed, step, layer, 1, member, d_in, rank, noise_dtype, B);
+                for (int j = 0; j < d_out; ++j) {
+                    for (int k = 0; k < d_in; ++k) {
+                        double e = 0.0;
+                        for (int l = 0; l < rank; ++l)
+                            e += A[(size_t)j * rank + l] * B[(size_t)k * rank + l];
+                        Wi[(size_t)j * d_in + k] = W[(size_t)j * d_in + k] + c * e;
+                    }
+                }
+                for (int s = 0; s < S; ++s) {
+                    const double* x = X + ((size_t)m * S + s) * (size_t)d_in;
+                    double* y = Y + ((size_t)m * S + s) * (size_t)d_out;
+                    for (int j = 0; j < d_out; ++j) {
+                        double acc = 0.0;
+                        const double* w = Wi + (size_t)j * d_in;
+                        for (int k = 0; k < d_in; ++k) acc += w[k] * x[k];
+                        y[j] = act == 1 ? gelu_exact(acc) : acc;
+                    }
+                }
+            }
+        }
+        free(Wi); free(A); free(B);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* update: explicit sum of N*r outer products                                                  */
+/* ------------------------------------------------------------------------------------------ */
+/*
+ * G[j,k] = scale * sum_i fitness[i] * sum_l A_i[j,l] B_i[k,l]      (members member_begin .. +count)
+ * Row blocks of G are owned by threads; every thread walks the members in increasing order, so
+ * the summation order of each entry is fixed.
+ */
+int oracle_update(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                  int64_t member_count, int d_out, int d_in, int rank, int noise_dtype,
+                  const double* fitness, double scale, double* G)
+{
+    /* materialise all factors once (N*(d_out+d_in)*r doubles) */
+    const size_t na = (size_t)d_out * rank, nb = (size_t)d_in * rank;
+    double* A = (double*)malloc(sizeof(double) * na * (size_t)member_count);
+    double* B = (double*)malloc(sizeof(double) * nb * (size_t)member_count);
+    if (!A || !B) { free(A); free(B); return -1; }
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < member_count; ++m) {
+        oracle_noise_matrix(seed, step, layer, 0, member_begin + m, d_out, rank, noise_dtype, A + na * (size_t)m);
+        oracle_noise_matrix(seed, step, layer, 1, member_begin + m, d_in, rank, noise_dtype, B + nb * (size_t)m);
+    }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d_out; ++j) {
+        double* g = G + (size_t)j * d_in;
+        for (int k = 0; k < d_in; ++k) g[k] = 0.0;
+        for (int64_t m = 0; m < member_count; ++m) {
+            const double* a = A + na * (size_t)m + (size_t)j * rank;
+            const double* b = B + nb * (size_t)m;
+            for (int l = 0; l < rank; ++l) {
+                const double fa = fitness[m] * a[l];
+                for (int k = 0; k < d_in; ++k) g[k] += fa * b[(size_t)k * rank + l];
+            }
+        }
+        for (int k = 0; k < d_in; ++k) g[k] *= scale;
+    }
+    free(A); free(B);
+    return 0;
+}
+
+/* one entry of G, by random access into the noise stream (for sampled checks at full size) */
+double oracle_update_entry(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                           int64_t member_count, int rank, int noise_dtype, const double* fitness,
+                           double scale, int64_t j, int64_t k)
+{
+    double acc = 0.0;
+    double a[8], b[8];
+    for (int64_t m = 0; m < member_count; ++m) {
+        oracle_noise_normal(seed, step, layer, 0, member_begin + m, (uint64_t)j * rank, (uint64_t)rank, a);
+        oracle_noise_normal(seed, step, layer, 1, member_begin + m, (uint64_t)k * rank, (uint64_t)rank, b);
+        double e = 0.0;
+        for (int l = 0; l < rank; ++l) e += round_storage(a[l], noise_dtype) * round_storage(b[l], noise_dtype);
+        acc += fitness[m] * e;
+    }
+    return scale * acc;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* integer perturbed matmul, repeated as a recurrence                                          */
+/* ------------------------------------------------------------------------------------------ */
+static int32_t shr_floor(int64_t v, int s) /* arithmetic shift: floor(v / 2^s) */
+{
+    if (s <= 0) return (int32_t)v;
+    return (int32_t)(v >= 0 ? (v >> s) : -((-v + ((int64_t)1 << s) - 1) >> s));
+}
+
+/*
+ * For each member row h (int8[d]) and `steps` times:
+ *     acc_j  = sum_k h_k W[j,k]                     (int32)
+ *     dot    = sum_k h_k B_i[k]                     (int32)            "u . B"
+ *     corr_j = (dot * int32(A_i[j])) >> corr_shift  (arithmetic)       "(u.B) I32(A) >> (4+sigma_hat)"
+ *     h'_j   = clamp((acc_j + corr_j) >> out_shift, -127, 127)         "I8(. / (16 sqrt n))"
+ * rank 1, square W (d x d), noise on {-bound..bound}.  H_in/H_out: [count][d].
+ */
+void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                       int64_t member_count, int d, int bound, int corr_shift, int out_shift,
+                       int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
+{
+#pragma omp parallel
+    {
+        int8_t* A = (int8_t*)malloc((size_t)d);
+        int8_t* B = (int8_t*)malloc((size_t)d);
+        int32_t* h = (int32_t*)malloc(sizeof(int32_t) * (size_t)d);
+        int32_t* hn = (int32_t*)malloc(sizeof(int32_t) * (size_t)d);
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t m = 0; m < member_count; ++m) {
+            const int64_t member = member_begin + m;
+            oracle_noise_int(seed, step, layer, 0, member, 0, (uint64_t)d, bound, A);
+            oracle_noise_int(seed, step, layer, 1, member, 0, (uint64_t)d, bound, B);
+            for (int k = 0; k < d; ++k) h[k] = H_in[(size_t)m * d + k];
+            for (int t = 0; t < steps; ++t) {
+                int32_t dot = 0;
+                for (int k = 0; k < d; ++k) dot += h[k] * (int32_t)B[k];
+                for (int j = 0; j < d; ++j) {
+                    int32_t acc = 0;
+                    const int8_t* w = W + (size_t)j * d;
+                    for (int k = 0; k < d; ++k) acc += h[k] * (int32_t)w[k];
+                    const int32_t corr = shr_floor((int64_t)dot * (int64_t)A[j], corr_shift);
+                    int32_t v = shr_floor((int64_t)acc + (int64_t)corr, out_shift);
+                    if (v > 127) v = 127;
+                    if (v < -127) v = -127;
+                    hn[j] = v;
+                }
+                for (int k = 0; k < d; ++k) h[k] = hn[k];
+            }
+            for (int k = 0; k < d; ++k) H_out[(size_t)m * d + k] = (int8_t)h[k];
+        }
+        free(A); free(B); free(h); free(hn);
+    }
+}
+
+int oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

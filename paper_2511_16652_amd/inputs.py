@@ -1,0 +1,112 @@
+"""Seeded synthetic inputs for the EGGROLL hot path (shared by tests, oracle runs and bench.py).
+
+This module holds NO arithmetic of the method itself: it only draws weights, activations, targets
+and raw fitness scores with the shapes and value distributions of the workloads, and rounds them
+to their storage dtype so that the CPU oracle and the GPU path read identical values.
+All draws come from ``numpy.random.default_rng(data_seed)``.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round a float array to the nearest bfloat16 (ties to even); result stays float32."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    bits = (bits + 0x7FFF + lsb) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(f.shape)
+
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of an array that already holds bfloat16-representable float32 values."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    return (f.view(np.uint32) >> 16).astype(np.uint16).reshape(f.shape)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16
+    return u.view(np.float32).reshape(b.shape)
+
+
+@dataclass
+class LinearWorkload:
+    """One perturbed linear layer: the shapes of the float configurations."""
+    name: str
+    dtype: str            # "f32" or "bf16": storage type of W, X, Y and of the noise
+    d_out: int
+    d_in: int
+    N: int                # population size
+    S: int                # rows (tokens) per member
+    rank: int
+    sigma: float
+    data_seed: int
+    noise_seed: int = 0
+    step: int = 0
+    layer: int = 0
+    W: np.ndarray = field(default=None, repr=False)
+    X: np.ndarray = field(default=None, repr=False)
+    target: np.ndarray = field(default=None, repr=False)
+    raw_fitness: np.ndarray = field(default=None, repr=False)
+
+
+def make_linear(name, dtype, d_out, d_in, N, S, rank, sigma, data_seed, layer=0) -> LinearWorkload:
+    """W ~ N(0, 1/d_in), X ~ N(0, 1), target ~ N(0, 1), raw fitness ~ N(0, 1)."""
+    rng = np.random.default_rng(data_seed)
+    W = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    X = rng.standard_normal((N * S, d_in)).astype(np.float32)
+    target = rng.standard_normal(d_out).astype(np.float32)
+    raw = rng.standard_normal(N).astype(np.float64)
+    if dtype == "bf16":
+        W, X = round_to_bf16(W), round_to_bf16(X)
+    return LinearWorkload(name, dtype, d_out, d_in, N, S, rank, sigma, data_seed, 0, 0, layer,
+                          W, X, target, raw)
+
+
+def config1() -> LinearWorkload:
+    """fp32 256x256 layer, N = 64, r = 1, sigma = 0.01, one input per member."""
+    return make_linear("cfg1_f32_256", "f32", 256, 256, 64, 1, 1, 0.01, 1001)
+
+
+def config2(N: int = 4096, d: int = 4096) -> LinearWorkload:
+    """bf16 4096x4096 layer, N = 4096, r = 1, sigma = 1e-3, one token per member."""
+    return make_linear("cfg2_bf16_%d_N%d" % (d, N), "bf16", d, d, N, 1, 1, 1e-3, 1002)
+
+
+def centered(f: np.ndarray) -> np.ndarray:
+    """Raw scores shifted to zero mean (the caller-side shaping of the synthetic fitness)."""
+    f = np.asarray(f, dtype=np.float64)
+    return f - f.mean()
+
+
+@dataclass
+class Int8Workload:
+    """The integer recurrent cell: one square int8 matrix applied `steps` times."""
+    name: str
+    d: int
+    N: int
+    bound: int
+    corr_shift: int
+    out_shift: int
+    steps: int
+    data_seed: int
+    noise_seed: int = 0
+    step: int = 0
+    layer: int = 0
+    W: np.ndarray = field(default=None, repr=False)
+    H0: np.ndarray = field(default=None, repr=False)
+
+
+def make_int8(name, d, N, steps, data_seed, bound=8, corr_shift=4, out_shift=8) -> Int8Workload:
+    """W and h_0 uniform integers on [-127, 127]."""
+    rng = np.random.default_rng(data_seed)
+    W = rng.integers(-127, 128, size=(d, d), dtype=np.int64).astype(np.int8)
+    H0 = rng.integers(-127, 128, size=(N, d), dtype=np.int64).astype(np.int8)
+    return Int8Workload(name, d, N, bound, corr_shift, out_shift, steps, data_seed, 0, 0, 0, W, H0)
+
+
+def config3(N: int = 8192, d: int = 1024, steps: int = 64) -> Int8Workload:
+    return make_int8("cfg3_i8_%d_N%d_T%d" % (d, N, steps), d, N, steps, 1003)
