@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the EGGROLL hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: noise regeneration, projection,
+shared GEMM with the fused low-rank correction (perturbed forward), then the fitness-weighted update
+G = scale * sum_i f_i A_i B_i^T computed as one MFMA contraction over K = N*r.  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3|p0] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def timed(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def linear_workload(args):
+    """bf16/fp32 linear layer: perturbed forward + update."""
+    import numpy as np
+    import torch
+
+    from paper_2511_16652_amd import binding as eb
+    from paper_2511_16652_amd import inputs, roofline
+
+    if args.workload == "cfg1":
+        wl = inputs.config1()
+    elif args.workload == "p0":   # the paper's own speed benchmark shape: bf16 8192x8192, batch 1024
+        wl = inputs.make_linear("p0_bf16_8192_N1024", "bf16", 8192, 8192, 1024, 1, 1, 1e-3, 1100)
+    else:
+        wl = inputs.config2()
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    code = eb.EGG_BF16 if wl.dtype == "bf16" else eb.EGG_F32
+    R = wl.N * wl.S
+    ctx = eb.Context(0)
+    W = torch.from_numpy(wl.W).to(tdt).cuda()
+    X = torch.from_numpy(wl.X).to(tdt).cuda()
+    Y = torch.empty((R, wl.d_out), dtype=tdt, device="cuda")
+    A = torch.empty((wl.N, wl.d_out, wl.rank), dtype=tdt, device="cuda")
+    B = torch.empty((wl.N, wl.d_in, wl.rank), dtype=tdt, device="cuda")
+    G = torch.empty((wl.d_out, wl.d_in), dtype=torch.float32, device="cuda")
+    fit = torch.from_numpy(inputs.centered(wl.raw_fitness).astype(np.float32)).cuda()
+    key = eb.make_key(wl.noise_seed, wl.step, wl.layer)
+    shape = eb.make_shape(0, wl.N, wl.S, wl.d_out, wl.d_in, wl.rank)
+    scale = eb.eggroll_default_scale(wl.N, wl.sigma, wl.rank)
+
+    def forward():
+        ctx.eggroll_perturbed_forward(key, shape, wl.sigma, eb.EGG_ACT_NONE, W, X, Y, A, B)
+
+    def forward_nocache():
+        ctx.eggroll_perturbed_forward(key, shape, wl.sigma, eb.EGG_ACT_NONE, W, X, Y, None, None)
+
+    def unperturbed():
+        ctx.eggroll_perturbed_forward(key, shape, 0.0, eb.EGG_ACT_NONE, W, X, Y, None, None)
+
+    def update():
+        ctx.eggroll_update(key, shape, code, fit, scale, 0, G, None, 0.0, A, B)
+
+    def step():
+        forward()
+        update()
+
+    def torch_mm():
+        torch.matmul(X, W.t(), out=Y)
+
+    t_step = timed(step, args.steps, args.warmup)
+    t_fwd = timed(forward, args.steps, args.warmup)
+    t_fwd_nc = timed(forward_nocache, args.steps, args.warmup)
+    t_unp = timed(unperturbed, args.steps, args.warmup)
+    t_upd = timed(update, args.steps, args.warmup)
+    t_mm = timed(torch_mm, args.steps, args.warmup)
+
+    # per-kernel durations of the same step, HIP events on the library's stream
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in prof.items()}
+
+    gemm_name = max((k for k in kernels if k.startswith("forward_gemm")), key=lambda k: kernels[k]["avg_us"])
+    fl = roofline.forward_flops(R, wl.d_in, wl.d_out, wl.rank)
+    peak = roofline.MFMA_PEAK_TFLOPS["bf16" if wl.dtype == "bf16" else "f32"]
+    achieved = fl / (kernels[gemm_name]["avg_us"] * 1e-6) / 1e12
+    upd_name = max((k for k in kernels if k.startswith("update_gemm")), key=lambda k: kernels[k]["avg_us"])
+    upd_tflops = roofline.update_flops(wl.N, wl.d_in, wl.d_out, wl.rank) / (kernels[upd_name]["avg_us"] * 1e-6) / 1e12
+
+    out = {
+        "metric": "population tokens/sec (perturbed forward + update), 1 GPU",
+        "value": R / t_step,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "d_out": wl.d_out, "d_in": wl.d_in, "population": wl.N,
+                   "rows_per_member": wl.S, "rank": wl.rank, "sigma": wl.sigma},
+        "pct_of_unperturbed": {
+            "forward_vs_own_sigma0": 100.0 * t_unp / t_fwd_nc,
+            "forward_with_caches_vs_own_sigma0": 100.0 * t_unp / t_fwd,
+            "forward_vs_torch_matmul": 100.0 * t_mm / t_fwd_nc,
+            "quoted": 100.0 * min(t_unp, t_mm) / t_fwd_nc,
+        },
+        "tokens_per_s": {"forward_only": R / t_fwd_nc, "forward_with_caches": R / t_fwd, "update_only": R / t_upd,
+                         "unperturbed_own": R / t_unp, "unperturbed_torch_matmul": R / t_mm},
+        "ms": {"forward": 1e3 * t_fwd_nc, "forward_with_caches": 1e3 * t_fwd, "unperturbed": 1e3 * t_unp,
+               "update": 1e3 * t_upd, "torch_matmul": 1e3 * t_mm},
+        "roofline": {"bound": "mfma", "kernel": gemm_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None},
+        "update_roofline": {"bound": "mfma", "kernel": upd_name, "achieved": upd_tflops, "peak": peak,
+                            "unit": "TFLOP/s", "frac": upd_tflops / peak},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_linear(wl)
+    ctx.close()
+    return out
+
+
+def cpu_baseline_linear(wl):
+    """The oracle as it stands (explicit W_i per member, explicit outer products), timed on a bounded
+    sample of the same workload on the host cores."""
+    import numpy as np
+
+    import oracle
+    from paper_2511_16652_amd import inputs
+
+    nd = oracle.NOISE_BF16 if wl.dtype == "bf16" else oracle.NOISE_F32
+    per_member = 3.0 * wl.d_out * wl.d_in * wl.rank  # rough flop-equivalents, only used to size the sample
+    m = int(max(8, min(wl.N, 2e11 / per_member / 8)))
+    m = min(wl.N, max(oracle.threads(), m - m % oracle.threads()))
+    f = inputs.centered(wl.raw_fitness[:m])
+    t0 = time.perf_counter()
+    oracle.forward(wl.noise_seed, wl.step, wl.layer, 0, m, wl.S, wl.d_out, wl.d_in, wl.rank, nd, wl.sigma, 0,
+                   wl.W, wl.X[:m * wl.S])
+    t1 = time.perf_counter()
+    oracle.update(wl.noise_seed, wl.step, wl.layer, 0, m, wl.d_out, wl.d_in, wl.rank, nd, f, 1.0)
+    t2 = time.perf_counter()
+    return {"value": m * wl.S / (t2 - t0), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "%d of %d members, forward (%.2f s) + update (%.2f s); cost is linear in members" % (
+                m, wl.N, t1 - t0, t2 - t1)}
+
+
+def int8_workload(args):
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_16652_amd import binding as eb
+    from paper_2511_16652_amd import inputs, roofline
+
+    wl = inputs.config3()
+    ctx = eb.Context(0)
+    W = torch.from_numpy(wl.W).cuda()
+    H = torch.from_numpy(wl.H0).cuda()
+    out_t = torch.empty_like(H)
+    key = eb.make_key(0, 0, 0)
+    shape = eb.make_shape(0, wl.N, 1, wl.d, wl.d, 1)
+
+    def step():
+        ctx.eggroll_perturbed_forward_i8(key, shape, wl.bound, wl.corr_shift, wl.out_shift, wl.steps, W, H, out_t)
+
+    t_step = timed(step, args.steps, args.warmup)
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in prof.items()}
+    ops = 2.0 * wl.N * wl.d * wl.d
+    achieved = ops / (kernels["forward_gemm_i8"]["avg_us"] * 1e-6) / 1e12
+    res = {
+        "metric": "population tokens/sec (integer perturbed recurrence), 1 GPU",
+        "value": wl.N * wl.steps / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * t_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": wl.name, "d": wl.d, "population": wl.N, "time_steps": wl.steps, "bound": wl.bound},
+        "roofline": {"bound": "mfma", "kernel": "forward_gemm_i8", "achieved": achieved,
+                     "peak": roofline.MFMA_PEAK_TFLOPS["i8"], "unit": "TOP/s",
+                     "frac": achieved / roofline.MFMA_PEAK_TFLOPS["i8"], "traffic": None},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        m = 64 * max(1, oracle.threads() // 8)
+        t0 = time.perf_counter()
+        oracle.forward_i8(0, 0, 0, 0, m, wl.d, wl.bound, wl.corr_shift, wl.out_shift, wl.steps, wl.W, wl.H0[:m])
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": m * wl.steps / dt, "unit": "tokens/s", "cores": oracle.threads(),
+                               "kind": "oracle", "sample": "%d of %d members, all %d time steps (%.2f s)" % (m, wl.N, wl.steps, dt)}
+    ctx.close()
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (the hot path of one MI355X); --gpus %d is not "
+                         "supported -- population sharding across GPUs is described in DESIGN.md only.\n" % args.gpus)
+        sys.exit(2)
+    res = int8_workload(args) if args.workload == "cfg3" else linear_workload(args)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

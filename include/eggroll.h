@@ -1,0 +1,143 @@
+/*
+ * eggroll.h -- C ABI of the MI355X (gfx950) EGGROLL hot path.
+ *
+ * EGGROLL ("Evolution Strategies at the Hyperscale") evaluates a population of N members in one
+ * batched pass.  Member i sees the weights  W_i = M + sigma * E_i,  E_i = A_i B_i^T / sqrt(r),
+ * A_i in R^{d_out x r}, B_i in R^{d_in x r} (Sec. 4.1, Alg. 1), and the mean M is moved along
+ * sum_i f_i E_i (EGGROLL UPDATE box, Eq. eggroll_update).  The library never forms W_i or E_i:
+ *   forward:  u_i W_i^T = u_i M^T + (sigma/sqrt r) (u_i B_i) A_i^T      (Sec. 4.2)
+ *   update :  sum_i f_i A_i B_i^T = (diag(f) A)^T B, one contraction over K = N*r   (Sec. 4.2)
+ * and the factors A_i, B_i are never stored by the caller: they are a pure function of
+ * (seed, step, layer, which, member, index) from a counter-based generator (Sec. 1; Alg. 1
+ * "reconstruct E_j from the seeds").
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, valid on the device the
+ *     context was created for, 16-byte aligned.  The library allocates only its own scratch
+ *     (inside the context), never frees or keeps caller memory, never synchronises the stream:
+ *     all work is enqueued on the stream given at creation and is ordered on it.
+ *   - Matrices are dense row-major.  M = W[d_out][d_in].  Activations X[R][d_in], Y[R][d_out] with
+ *     R = member_count * rows_per_member, member-major: row q belongs to member
+ *     member_begin + q / rows_per_member.  Factors are laid out [member][d][rank] (rank fastest).
+ *   - Noise depends on the GLOBAL member id (member_begin + local index), so any partition of the
+ *     population into calls (or devices) regenerates identical factors.  Ids must stay < 2^32.
+ *   - Every call returns egg_status; nothing throws or aborts.  EGG_EINVAL: null pointer,
+ *     non-positive or inconsistent size, misaligned pointer, rank not in {1,2,4,8}, member range
+ *     outside [0, 2^32).  EGG_EUNSUPPORTED: a dtype/shape combination no kernel covers (the text
+ *     from eggroll_last_error says which).  EGG_EHIP: a HIP runtime call failed.  EGG_ENOMEM:
+ *     scratch could not be allocated.
+ *   - Noise stream (fixed contract, bit-exact):  Threefry-2x32-20.
+ *       stream key = Threefry(key=(seed lo32, seed hi32), counter=(step, layer | which<<31)),
+ *                    which: A = 0, B = 1, layer < 2^31;
+ *       words 2b, 2b+1 of member i's vector = Threefry(key = stream key, counter = (b, i)).
+ *     Normal value n (n = d*rank + l) comes from word n: u = ((word>>9) + 1/2) 2^-23; words
+ *     (2p, 2p+1) form a Box-Muller pair, z_2p = rho cos(2 pi u2), z_2p+1 = rho sin(2 pi u2),
+ *     rho = sqrt(-2 ln u1); rounded to fp32, and then to bf16 (nearest even) in bf16 mode.
+ *     Integer value n comes from byte n&3 (little end first) of word n>>2: with m = 2b+1,
+ *     q = floor(256/m): byte < q*m ? floor(byte/q) - b : 0.
+ */
+#ifndef EGGROLL_H
+#define EGGROLL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eggroll_ctx eggroll_ctx; /* opaque; owns scratch buffers and the stream handle */
+
+typedef enum { EGG_OK = 0, EGG_EINVAL = -1, EGG_EUNSUPPORTED = -2, EGG_EHIP = -3, EGG_ENOMEM = -4 } egg_status;
+typedef enum { EGG_F32 = 0, EGG_BF16 = 1, EGG_I8 = 2, EGG_U32 = 3 } egg_dtype;
+typedef enum { EGG_NORMAL = 0, EGG_UNIFORM_INT = 1, EGG_RAW = 2 } egg_dist;
+typedef enum { EGG_ACT_NONE = 0, EGG_ACT_GELU = 1 } egg_act;
+
+/* names one weight matrix at one ES iteration (Alg. 1: the seeds every worker knows) */
+typedef struct { uint64_t seed; uint32_t step; uint32_t layer; } egg_key;
+
+typedef struct {
+    int64_t member_begin;     /* global id of the first member of this call              */
+    int64_t member_count;     /* members in this call                                    */
+    int32_t rows_per_member;  /* S: rows of X per member (tokens evaluated by a member)  */
+    int32_t d_out, d_in;      /* M is d_out x d_in                                       */
+    int32_t rank;             /* r in {1,2,4,8}                                          */
+} egg_shape;
+
+/* Context.  `device`: HIP device ordinal; `hip_stream`: a hipStream_t (NULL = default stream).
+   Host pointers.  Destroy synchronises the stream and frees the scratch. */
+egg_status eggroll_create(eggroll_ctx** out, int device, void* hip_stream);
+egg_status eggroll_destroy(eggroll_ctx* ctx);
+const char* eggroll_strerror(egg_status s);
+/* text of the last failure on this context (host string owned by the context) */
+const char* eggroll_last_error(const eggroll_ctx* ctx);
+
+/* 1/(N * sigma * sqrt(r)): the constant of the Monte-Carlo estimator (Eq. matrix_mc) times the
+   1/sqrt(r) of E_i, so that  scale * sum_i f_i A_i B_i^T  =  (1/(sigma N)) sum_i f_i E_i.
+   (Alg. 1 absorbs 1/sigma into the learning rate; pass your own `scale` for that form.) */
+double eggroll_default_scale(int64_t population, double sigma, int rank);
+
+/*
+ * (1) Materialise the factors (Sec. 1 "reconstruct noise on demand"; Alg. 1 sampling lines).
+ *   A_out[member_count][d_out][rank], B_out[member_count][d_in][rank]; either may be NULL.
+ *   dist = EGG_NORMAL      dtype EGG_F32 or EGG_BF16      Gaussian factors
+ *   dist = EGG_UNIFORM_INT dtype EGG_I8                   integers on {-int_bound..int_bound}
+ *   dist = EGG_RAW         dtype EGG_U32                  the raw 32-bit words (one per element)
+ * rows_per_member is ignored.
+ */
+egg_status eggroll_noise_gen(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, egg_dtype dtype,
+                             egg_dist dist, int int_bound, void* A_out, void* B_out);
+
+/*
+ * (2) Population forward of one linear layer (Sec. 4.2):
+ *   Y[q][j] = act( sum_k X[q][k] W[j][k] + (sigma/sqrt r) sum_l t[q][l] A_i[j][l] ),
+ *   t[q][l] = sum_k X[q][k] B_i[k][l],  i = member of row q.
+ * io_dtype (W, X and the factors): EGG_BF16 (MFMA bf16, fp32 accumulate) or EGG_F32.
+ * y_dtype: EGG_BF16 or EGG_F32 (EGG_F32 only when io_dtype is EGG_F32 or for inspection).
+ * sigma == 0 runs the same kernels with the correction switched off (the unperturbed pass).
+ * A_cache / B_cache: optional side outputs holding exactly what eggroll_noise_gen would write
+ * for this key and shape, for reuse by eggroll_update; NULL = do not keep.
+ * d_in must be a multiple of 8 (bf16) or 4 (fp32).
+ */
+egg_status eggroll_perturbed_forward(eggroll_ctx* ctx, egg_key key, const egg_shape* shape,
+                                     egg_dtype io_dtype, egg_dtype y_dtype, float sigma, egg_act act,
+                                     const void* W, const void* X, void* Y, void* A_cache, void* B_cache);
+
+/*
+ * (2') Integer form (App. "Matrix Multiplication", "Adding EGGROLL Perturbations"), rank 1, square
+ * W[d][d] int8 (d = d_out = d_in, multiple of 16), one row per member, repeated `steps` times:
+ *   acc  = h W^T (int32);  dot = h . B_i (int32)
+ *   h'_j = clamp( (acc_j + ((dot * int32(A_i[j])) >> corr_shift)) >> out_shift, -127, 127 )
+ * Shifts are arithmetic (floor).  H_in, H_out: int8 [member_count][d]; may alias.  The factors are
+ * integers on {-int_bound..int_bound}, fixed over the `steps` applications.  Bit-exact.
+ */
+egg_status eggroll_perturbed_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound,
+                                        int corr_shift, int out_shift, int steps, const int8_t* W,
+                                        const int8_t* H_in, int8_t* H_out);
+
+/*
+ * (3) Update direction (EGGROLL UPDATE box; Sec. 4.2 "(diag(f)A)^T B"):
+ *   G[j][k] = (accumulate ? G[j][k] : 0) + scale * sum_i fitness[i] sum_l A_i[j][l] B_i[k][l]
+ * G: fp32 [d_out][d_in].  fitness: fp32 [member_count], used as given (centring / z-scoring /
+ * ranking is the caller's shaping).  noise_dtype: EGG_BF16 or EGG_F32 -- the precision the forward
+ * pass evaluated the factors in.  A_cache/B_cache: the side outputs of the forward (or of
+ * eggroll_noise_gen); NULL = regenerate from the key.
+ * If W != NULL:  W[j][k] += lr * G[j][k], rounded to w_dtype (EGG_BF16 or EGG_F32), after G is final.
+ * rows_per_member is ignored.
+ */
+egg_status eggroll_update(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, egg_dtype noise_dtype,
+                          const float* fitness, float scale, int accumulate, float* G, void* W,
+                          egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache);
+
+/*
+ * Per-kernel timing for benchmarks.  With profiling on, every kernel the library launches is
+ * bracketed by HIP events on the context's stream.  eggroll_profile_read synchronises the stream
+ * and fills names[i] (pointers to static strings), launches[i], total_ms[i] for up to `cap`
+ * kernels; returns the number of distinct kernels (or a negative egg_status).  Reading resets.
+ */
+egg_status eggroll_profile_enable(eggroll_ctx* ctx, int on);
+int eggroll_profile_read(eggroll_ctx* ctx, const char** names, int64_t* launches, double* total_ms, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGGROLL_H */

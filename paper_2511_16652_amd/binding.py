@@ -1,0 +1,176 @@
+"""Python binding of libeggroll (argument marshalling only; every step runs in the HIP kernels).
+
+The functions mirror ``include/eggroll.h`` one to one and take ``torch`` CUDA(ROCm) tensors, whose
+``data_ptr()`` is handed to the C ABI.  PyTorch is used for device memory and streams only.
+There is no CPU fallback: if the shared library is missing, importing this module's loader raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libeggroll.so")
+
+EGG_OK, EGG_EINVAL, EGG_EUNSUPPORTED, EGG_EHIP, EGG_ENOMEM = 0, -1, -2, -3, -4
+EGG_F32, EGG_BF16, EGG_I8, EGG_U32 = 0, 1, 2, 3
+EGG_NORMAL, EGG_UNIFORM_INT, EGG_RAW = 0, 1, 2
+EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
+
+EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
+           "eggroll_default_scale", "eggroll_noise_gen", "eggroll_perturbed_forward",
+           "eggroll_perturbed_forward_i8", "eggroll_update", "eggroll_profile_enable",
+           "eggroll_profile_read"]
+
+
+class EggKey(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("step", ctypes.c_uint32), ("layer", ctypes.c_uint32)]
+
+
+class EggShape(ctypes.Structure):
+    _fields_ = [("member_begin", ctypes.c_int64), ("member_count", ctypes.c_int64),
+                ("rows_per_member", ctypes.c_int32), ("d_out", ctypes.c_int32),
+                ("d_in", ctypes.c_int32), ("rank", ctypes.c_int32)]
+
+
+class EggrollError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("eggroll status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libeggroll.so and declares the signatures.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -m paper_2511_16652_amd.build` "
+            "(there is no CPU fallback)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+    P = ctypes.POINTER
+    lib.eggroll_create.argtypes = [P(vp), i32, vp]
+    lib.eggroll_create.restype = i32
+    lib.eggroll_destroy.argtypes = [vp]
+    lib.eggroll_destroy.restype = i32
+    lib.eggroll_strerror.argtypes = [i32]
+    lib.eggroll_strerror.restype = ctypes.c_char_p
+    lib.eggroll_last_error.argtypes = [vp]
+    lib.eggroll_last_error.restype = ctypes.c_char_p
+    lib.eggroll_default_scale.argtypes = [i64, ctypes.c_double, i32]
+    lib.eggroll_default_scale.restype = ctypes.c_double
+    lib.eggroll_noise_gen.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, vp, vp]
+    lib.eggroll_noise_gen.restype = i32
+    lib.eggroll_perturbed_forward.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp]
+    lib.eggroll_perturbed_forward.restype = i32
+    lib.eggroll_perturbed_forward_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, vp, vp, vp]
+    lib.eggroll_perturbed_forward_i8.restype = i32
+    lib.eggroll_update.argtypes = [vp, EggKey, P(EggShape), i32, vp, f32, i32, vp, vp, i32, f32, vp, vp]
+    lib.eggroll_update.restype = i32
+    lib.eggroll_profile_enable.argtypes = [vp, i32]
+    lib.eggroll_profile_enable.restype = i32
+    lib.eggroll_profile_read.argtypes = [vp, P(ctypes.c_char_p), P(i64), P(ctypes.c_double), i32]
+    lib.eggroll_profile_read.restype = i32
+    _lib = lib
+    return lib
+
+
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float32: EGG_F32, torch.bfloat16: EGG_BF16, torch.int8: EGG_I8,
+            torch.uint32: EGG_U32, torch.int32: EGG_U32}[t.dtype]
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous device tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def eggroll_default_scale(population: int, sigma: float, rank: int) -> float:
+    return float(load_library().eggroll_default_scale(population, sigma, rank))
+
+
+class Context:
+    """eggroll_ctx bound to a torch device and (optionally) a torch stream."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the EGGROLL library runs on MI355X only")
+        self._lib = load_library()
+        self._torch_stream = stream  # keep alive
+        handle = ctypes.c_void_p()
+        sp = ctypes.c_void_p(stream.cuda_stream) if stream is not None else ctypes.c_void_p(
+            torch.cuda.current_stream(device).cuda_stream)
+        st = self._lib.eggroll_create(ctypes.byref(handle), device, sp)
+        if st != EGG_OK:
+            raise EggrollError(st, self._lib.eggroll_strerror(st).decode())
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.eggroll_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != EGG_OK:
+            raise EggrollError(st, "%s (%s)" % (self._lib.eggroll_strerror(st).decode(),
+                                                self._lib.eggroll_last_error(self._h).decode()))
+
+    # -- entry points ------------------------------------------------------------------------
+    def eggroll_noise_gen(self, key, shape, dtype, dist, int_bound, A_out, B_out):
+        self._check(self._lib.eggroll_noise_gen(self._h, key, ctypes.byref(shape), dtype, dist,
+                                                int_bound, _ptr(A_out), _ptr(B_out)))
+
+    def eggroll_perturbed_forward(self, key, shape, sigma, act, W, X, Y, A_cache=None, B_cache=None):
+        self._check(self._lib.eggroll_perturbed_forward(
+            self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
+            _ptr(W), _ptr(X), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
+
+    def eggroll_perturbed_forward_i8(self, key, shape, int_bound, corr_shift, out_shift, steps, W, H_in, H_out):
+        self._check(self._lib.eggroll_perturbed_forward_i8(
+            self._h, key, ctypes.byref(shape), int_bound, corr_shift, out_shift, steps,
+            _ptr(W), _ptr(H_in), _ptr(H_out)))
+
+    def eggroll_update(self, key, shape, noise_dtype, fitness, scale, accumulate, G, W=None, lr=0.0,
+                       A_cache=None, B_cache=None):
+        w_dtype = _dtype_code(W) if W is not None else EGG_F32
+        self._check(self._lib.eggroll_update(
+            self._h, key, ctypes.byref(shape), noise_dtype, _ptr(fitness), float(scale), int(accumulate),
+            _ptr(G), _ptr(W), w_dtype, float(lr), _ptr(A_cache), _ptr(B_cache)))
+
+    # -- per-kernel timing -----------------------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._check(self._lib.eggroll_profile_enable(self._h, int(on)))
+
+    def profile_read(self):
+        """{kernel name: (launches, total milliseconds)} since the last read."""
+        cap = 64
+        names = (ctypes.c_char_p * cap)()
+        launches = (ctypes.c_int64 * cap)()
+        ms = (ctypes.c_double * cap)()
+        n = self._lib.eggroll_profile_read(self._h, names, launches, ms, cap)
+        if n < 0:
+            self._check(n)
+        return {names[i].decode(): (int(launches[i]), float(ms[i])) for i in range(min(n, cap))}
+
+
+def make_key(seed: int, step: int, layer: int) -> EggKey:
+    return EggKey(seed, step, layer)
+
+
+def make_shape(member_begin, member_count, rows_per_member, d_out, d_in, rank) -> EggShape:
+    return EggShape(member_begin, member_count, rows_per_member, d_out, d_in, rank)

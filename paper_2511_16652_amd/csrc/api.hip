@@ -1,0 +1,304 @@
+// C ABI of libeggroll: argument validation, scratch management, and the sequencing of kernels for
+// each entry point of include/eggroll.h.  No arithmetic of the method happens on the host.
+#include <stdarg.h>
+#include <string.h>
+
+#include "common.hpp"
+
+namespace egg {
+
+egg_status fail(eggroll_ctx* c, egg_status s, const char* fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return s;
+}
+
+egg_status check_hip(eggroll_ctx* c, hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return EGG_OK;
+    return fail(c, EGG_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+egg_status reserve(eggroll_ctx* c, eggroll_ctx::Buf& b, size_t bytes)
+{
+    if (b.bytes >= bytes) return EGG_OK;
+    if (b.p) {
+        // work that still reads the old buffer is ordered on our stream
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, EGG_EHIP, "sync before scratch growth");
+        (void)hipFree(b.p);
+        b.p = nullptr;
+        b.bytes = 0;
+    }
+    const size_t want = (bytes + 255) & ~size_t(255);
+    hipError_t e = hipMalloc(&b.p, want);
+    if (e != hipSuccess) {
+        b.p = nullptr;
+        (void)hipGetLastError();
+        return fail(c, EGG_ENOMEM, "scratch of %zu bytes: %s", want, hipGetErrorString(e));
+    }
+    b.bytes = want;
+    return EGG_OK;
+}
+
+KernelScope::KernelScope(eggroll_ctx* ctx, const char* n) : c(ctx), name(n)
+{
+    if (!c->prof) return;
+    auto get = [&]() {
+        hipEvent_t e = nullptr;
+        if (!c->free_events.empty()) {
+            e = c->free_events.back();
+            c->free_events.pop_back();
+        } else if (hipEventCreate(&e) != hipSuccess) {
+            e = nullptr;
+        }
+        return e;
+    };
+    a = get();
+    b = get();
+    if (a) (void)hipEventRecord(a, c->stream);
+}
+
+KernelScope::~KernelScope()
+{
+    if (!c->prof || !a || !b) return;
+    (void)hipEventRecord(b, c->stream);
+    c->recs.push_back({name, a, b});
+}
+
+egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows)
+{
+    if (!s) return fail(c, EGG_EINVAL, "shape is NULL");
+    if (s->member_count <= 0 || s->d_out <= 0 || s->d_in <= 0) return fail(c, EGG_EINVAL, "non-positive size");
+    if (need_rows && s->rows_per_member <= 0) return fail(c, EGG_EINVAL, "rows_per_member must be positive");
+    if (s->rank != 1 && s->rank != 2 && s->rank != 4 && s->rank != 8)
+        return fail(c, EGG_EINVAL, "rank %d not in {1,2,4,8}", s->rank);
+    if (s->member_begin < 0 || s->member_begin + s->member_count > (int64_t(1) << 32))
+        return fail(c, EGG_EINVAL, "member ids must lie in [0, 2^32)");
+    return EGG_OK;
+}
+
+}  // namespace egg
+
+using namespace egg;
+
+extern "C" {
+
+egg_status eggroll_create(eggroll_ctx** out, int device, void* hip_stream)
+{
+    if (!out) return EGG_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return EGG_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return EGG_EHIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return EGG_EHIP;
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return EGG_EUNSUPPORTED;  // kernels are gfx950-only
+    eggroll_ctx* c = new (std::nothrow) eggroll_ctx();
+    if (!c) return EGG_ENOMEM;
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    egg_status s = reserve(c, c->zero_page, 256);
+    if (s == EGG_OK && hipMemsetAsync(c->zero_page.p, 0, 256, c->stream) != hipSuccess) s = EGG_EHIP;
+    if (s != EGG_OK) {
+        delete c;
+        return s;
+    }
+    *out = c;
+    return EGG_OK;
+}
+
+egg_status eggroll_destroy(eggroll_ctx* c)
+{
+    if (!c) return EGG_EINVAL;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->zero_page};
+    for (auto* b : bufs)
+        if (b->p) (void)hipFree(b->p);
+    for (auto& r : c->recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    for (auto e : c->free_events) (void)hipEventDestroy(e);
+    delete c;
+    return EGG_OK;
+}
+
+const char* eggroll_strerror(egg_status s)
+{
+    switch (s) {
+        case EGG_OK: return "ok";
+        case EGG_EINVAL: return "invalid argument";
+        case EGG_EUNSUPPORTED: return "unsupported dtype/shape combination or device";
+        case EGG_EHIP: return "HIP runtime error";
+        case EGG_ENOMEM: return "out of device memory for scratch";
+    }
+    return "unknown status";
+}
+
+const char* eggroll_last_error(const eggroll_ctx* c) { return c ? c->err.c_str() : "no context"; }
+
+double eggroll_default_scale(int64_t population, double sigma, int rank)
+{
+    return 1.0 / ((double)population * sigma * sqrt((double)rank));
+}
+
+egg_status eggroll_noise_gen(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype dtype, egg_dist dist,
+                             int int_bound, void* A_out, void* B_out)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, false);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    const bool ok = (dist == EGG_NORMAL && (dtype == EGG_F32 || dtype == EGG_BF16)) ||
+                    (dist == EGG_UNIFORM_INT && dtype == EGG_I8) || (dist == EGG_RAW && dtype == EGG_U32);
+    if (!ok) return fail(c, EGG_EUNSUPPORTED, "noise_gen: dist %d with dtype %d", (int)dist, (int)dtype);
+    if (dist == EGG_UNIFORM_INT && (int_bound < 0 || int_bound > 127)) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if ((A_out && !aligned16(A_out)) || (B_out && !aligned16(B_out))) return fail(c, EGG_EINVAL, "outputs must be 16-byte aligned");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    if (A_out) {
+        s = launch_noise(c, make_stream_key(key.seed, key.step, key.layer, 0), (uint32_t)shape->member_begin,
+                         shape->member_count, (int64_t)shape->d_out * shape->rank, dtype, dist, int_bound, A_out);
+        if (s != EGG_OK) return s;
+    }
+    if (B_out) {
+        s = launch_noise(c, make_stream_key(key.seed, key.step, key.layer, 1), (uint32_t)shape->member_begin,
+                         shape->member_count, (int64_t)shape->d_in * shape->rank, dtype, dist, int_bound, B_out);
+        if (s != EGG_OK) return s;
+    }
+    return EGG_OK;
+}
+
+egg_status eggroll_perturbed_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                     egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                     void* Y, void* A_cache, void* B_cache)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, true);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!W || !X || !Y) return fail(c, EGG_EINVAL, "W, X, Y must be non-NULL");
+    if (!aligned16(W) || !aligned16(X) || !aligned16(Y) || !aligned16(A_cache) || !aligned16(B_cache))
+        return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
+    if (io_dtype != EGG_BF16 && io_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "io_dtype %d", (int)io_dtype);
+    if (y_dtype != EGG_BF16 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "y_dtype %d", (int)y_dtype);
+    if (io_dtype == EGG_F32 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "fp32 inputs need fp32 output");
+    if (act != EGG_ACT_NONE && act != EGG_ACT_GELU) return fail(c, EGG_EINVAL, "unknown activation");
+    const int kq = io_dtype == EGG_BF16 ? 8 : 4;
+    if (shape->d_in % kq) return fail(c, EGG_EUNSUPPORTED, "d_in must be a multiple of %d", kq);
+    if (shape->d_out % 4) return fail(c, EGG_EUNSUPPORTED, "d_out must be a multiple of 4");
+    if (!(sigma == sigma) || sigma < 0.0f) return fail(c, EGG_EINVAL, "sigma must be >= 0");
+    if (sigma == 0.0f && (A_cache || B_cache))
+        return fail(c, EGG_EINVAL, "sigma == 0 generates no factors: caches must be NULL");
+    const int64_t R = shape->member_count * (int64_t)shape->rows_per_member;
+    if (R > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "more than 2^31 rows in one call");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+
+    float* t = nullptr;
+    if (sigma != 0.0f) {
+        s = reserve(c, c->t_buf, (size_t)R * shape->rank * sizeof(float));
+        if (s != EGG_OK) return s;
+        t = (float*)c->t_buf.p;
+        s = launch_project(c, make_stream_key(key.seed, key.step, key.layer, 1), *shape, io_dtype, X, t, B_cache);
+        if (s != EGG_OK) return s;
+    }
+    return launch_forward_gemm(c, make_stream_key(key.seed, key.step, key.layer, 0), *shape, io_dtype, y_dtype, sigma,
+                               act, W, X, Y, t, A_cache);
+}
+
+egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound,
+                                        int corr_shift, int out_shift, int steps, const int8_t* W, const int8_t* H_in,
+                                        int8_t* H_out)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, false);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!W || !H_in || !H_out) return fail(c, EGG_EINVAL, "W, H_in, H_out must be non-NULL");
+    if (!aligned16(W) || !aligned16(H_in) || !aligned16(H_out)) return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
+    if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
+    if (shape->d_out != shape->d_in) return fail(c, EGG_EUNSUPPORTED, "integer recurrence needs a square matrix");
+    if (shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "d must be a multiple of 16");
+    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (corr_shift < 0 || corr_shift > 31 || out_shift < 0 || out_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
+    if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");
+    // int32 accumulators: |acc| <= d*127^2, |dot * A| <= d*127*bound^2
+    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+        return fail(c, EGG_EUNSUPPORTED, "d too large for int32 accumulation");
+    if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_forward_i8(c, make_stream_key(key.seed, key.step, key.layer, 0),
+                             make_stream_key(key.seed, key.step, key.layer, 1), *shape, int_bound, corr_shift,
+                             out_shift, steps, W, H_in, H_out);
+}
+
+egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype noise_dtype,
+                          const float* fitness, float scale, int accumulate, float* G, void* W, egg_dtype w_dtype,
+                          float lr, const void* A_cache, const void* B_cache)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, false);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!fitness || !G) return fail(c, EGG_EINVAL, "fitness and G must be non-NULL");
+    if (!aligned16(G) || !aligned16(W) || !aligned16(A_cache) || !aligned16(B_cache) || (reinterpret_cast<uintptr_t>(fitness) & 3))
+        return fail(c, EGG_EINVAL, "misaligned pointer");
+    if (noise_dtype != EGG_BF16 && noise_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "noise_dtype %d", (int)noise_dtype);
+    if (W && w_dtype != EGG_BF16 && w_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "w_dtype %d", (int)w_dtype);
+    if (shape->d_out % 4) return fail(c, EGG_EUNSUPPORTED, "d_out must be a multiple of 4");
+    if ((A_cache == nullptr) != (B_cache == nullptr)) return fail(c, EGG_EINVAL, "pass both caches or neither");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_update(c, make_stream_key(key.seed, key.step, key.layer, 0),
+                         make_stream_key(key.seed, key.step, key.layer, 1), *shape, noise_dtype, fitness, scale,
+                         accumulate, G, W, w_dtype, lr, A_cache, B_cache);
+}
+
+egg_status eggroll_profile_enable(eggroll_ctx* c, int on)
+{
+    if (!c) return EGG_EINVAL;
+    c->prof = on != 0;
+    return EGG_OK;
+}
+
+int eggroll_profile_read(eggroll_ctx* c, const char** names, int64_t* launches, double* total_ms, int cap)
+{
+    if (!c || cap < 0) return EGG_EINVAL;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, EGG_EHIP, "profile sync");
+    std::vector<const char*> order;
+    std::map<std::string, std::pair<int64_t, double>> acc;
+    for (auto& r : c->recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            auto it = acc.find(r.name);
+            if (it == acc.end()) {
+                order.push_back(r.name);
+                acc[r.name] = {1, (double)ms};
+            } else {
+                it->second.first += 1;
+                it->second.second += ms;
+            }
+        }
+        c->free_events.push_back(r.a);
+        c->free_events.push_back(r.b);
+    }
+    c->recs.clear();
+    int n = 0;
+    for (const char* nm : order) {
+        if (n < cap) {
+            if (names) names[n] = nm;
+            if (launches) launches[n] = acc[nm].first;
+            if (total_ms) total_ms[n] = acc[nm].second;
+        }
+        ++n;
+    }
+    return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Host-side plumbing shared by the translation units of libeggroll: the context (stream, scratch,
+// error text, optional per-kernel event timing) and launch helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/eggroll.h"
+#include "rng.hpp"
+
+struct eggroll_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+
+    // scratch, grown on demand and kept for the life of the context
+    struct Buf {
+        void* p = nullptr;
+        size_t bytes = 0;
+    };
+    Buf t_buf;        // projections t[R][r] fp32 (forward) / int32 dots (int8 path)
+    Buf a_buf, b_buf; // materialised [member][d][r] factors when the caller keeps no cache
+    Buf fnorm;        // update: power-of-two normaliser of the fitness vector
+    Buf pack_a;       // update: K-packed diag(f)A panel
+    Buf pack_b;       // update: K-packed B panel
+    Buf i8_a, i8_b;   // int8 path: factors, generated once per episode
+    Buf i8_h;         // int8 path: ping-pong state
+    Buf zero_page;    // 256 zero bytes (K-tail loads of the GEMM core)
+
+    // profiling
+    bool prof = false;
+    struct Rec {
+        const char* name;
+        hipEvent_t a, b;
+    };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> free_events;
+};
+
+namespace egg {
+
+egg_status fail(eggroll_ctx* c, egg_status s, const char* fmt, ...);
+egg_status check_hip(eggroll_ctx* c, hipError_t e, const char* what);
+egg_status reserve(eggroll_ctx* c, eggroll_ctx::Buf& b, size_t bytes);
+
+// RAII bracket: records events around one kernel launch when profiling is on
+struct KernelScope {
+    eggroll_ctx* c;
+    const char* name;
+    hipEvent_t a = nullptr, b = nullptr;
+    KernelScope(eggroll_ctx* ctx, const char* n);
+    ~KernelScope();
+};
+
+// EGGROLL_GEMM_LOADER=staged selects the register-staged global->LDS path of the GEMM core
+// (default: direct-to-LDS loads).
+inline bool use_direct_loader()
+{
+    static const int v = [] {
+        const char* e = getenv("EGGROLL_GEMM_LOADER");
+        return (e && e[0] == 's') ? 0 : 1;
+    }();
+    return v != 0;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows);
+
+// entry points implemented per translation unit (kernel launchers)
+egg_status launch_noise(eggroll_ctx* c, const StreamKey& k, uint32_t member_begin, int64_t members, int64_t n,
+                        egg_dtype dtype, egg_dist dist, int int_bound, void* out);
+egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
+                          float* t, void* B_cache);
+egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
+                               float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
+                               void* A_cache);
+egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
+                         egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
+                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache);
+egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
+                             int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
+                             const int8_t* H_in, int8_t* H_out);
+
+}  // namespace egg

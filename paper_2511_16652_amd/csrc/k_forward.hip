@@ -1,0 +1,205 @@
+// Population forward of one linear layer (Sec. 4.2):
+//   Y = X W^T   (shared MFMA GEMM over all N*S rows)   +   (sigma/sqrt r) t A_i^T   (epilogue)
+// The epilogue regenerates exactly the factor entries A_i[j..j+3][:] that the lane's four outputs
+// need -- for one row per member every entry of A is produced exactly once over the grid -- applies
+// the correction in fp32, optionally keeps A_i for the update, applies the activation and stores.
+#include "common.hpp"
+#include "gemm_core.hpp"
+
+namespace egg {
+
+// Where the lane's factor entries A_i[m..m+3][0..RANK-1] come from:
+//   REGEN  (rank 1, one row per member): regenerated in registers from the counter stream -- each
+//          entry of A is needed by exactly one lane of the grid, so nothing is stored or re-read;
+//   otherwise read from a materialised [member][d_out][RANK] buffer (written just before by the
+//          noise kernel, the caller's A_cache if one was given): with S rows per member the buffer
+//          is RANK/S of the output size, and every entry is generated once instead of S times.
+template <bool BF16, int RANK, bool REGEN>
+struct FwdEpi {
+    typedef float value_t;
+    struct Args {
+        StreamKey ka;
+        uint32_t member_begin;
+        int S, d_out;
+        float c;  // sigma / sqrt(r); 0 switches the correction off
+        int act, y_bf16;
+        void* Y;
+        const float* t;
+        void* A_buf;  // REGEN: optional cache to fill; otherwise the materialised factors to read
+    };
+    const Args a;
+    float tc[RANK];
+    uint32_t member;
+    int64_t ml;
+
+    __device__ __forceinline__ FwdEpi(const Args& a_, char*) : a(a_) {}
+
+    __device__ __forceinline__ void column(int n, bool valid)
+    {
+        if (!valid || a.c == 0.f) return;
+        ml = n / a.S;
+        member = a.member_begin + (uint32_t)ml;
+#pragma unroll
+        for (int l = 0; l < RANK; ++l) tc[l] = a.c * a.t[(int64_t)n * RANK + l];
+    }
+
+    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid)
+    {
+        if (!valid || m >= a.d_out) return;  // m and d_out are multiples of 4
+        float y[4] = {v[0], v[1], v[2], v[3]};
+        if (a.c != 0.f) {
+            float z[4 * RANK];
+            const int64_t aoff = (ml * a.d_out + m) * RANK;  // element offset of A_i[m][0]
+            if constexpr (REGEN) {
+                static_assert(RANK == 1, "in-register regeneration is the rank-1 path");
+                const uint32_t blk0 = (uint32_t)m >> 1;
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    uint32_t w0, w1;
+                    noise_words(a.ka, member, blk0 + b, w0, w1);
+                    normal_pair<!BF16>(w0, w1, z[2 * b], z[2 * b + 1]);
+                }
+                if constexpr (BF16) {
+                    uint2 p;
+                    p.x = pack_bf16x2(z[0], z[1]);
+                    p.y = pack_bf16x2(z[2], z[3]);
+                    z[0] = bf16_lo(p.x); z[1] = bf16_hi(p.x);
+                    z[2] = bf16_lo(p.y); z[3] = bf16_hi(p.y);
+                    if (a.A_buf) *(uint2*)((uint16_t*)a.A_buf + aoff) = p;
+                } else {
+                    if (a.A_buf) *(float4*)((float*)a.A_buf + aoff) = make_float4(z[0], z[1], z[2], z[3]);
+                }
+            } else {
+                if constexpr (BF16) {
+                    const uint2* src = (const uint2*)((const uint16_t*)a.A_buf + aoff);
+#pragma unroll
+                    for (int v4 = 0; v4 < RANK; ++v4) {
+                        const uint2 p = src[v4];
+                        z[4 * v4] = __uint_as_float(p.x << 16); z[4 * v4 + 1] = __uint_as_float(p.x & 0xFFFF0000u);
+                        z[4 * v4 + 2] = __uint_as_float(p.y << 16); z[4 * v4 + 3] = __uint_as_float(p.y & 0xFFFF0000u);
+                    }
+                } else {
+                    const float4* src = (const float4*)((const float*)a.A_buf + aoff);
+#pragma unroll
+                    for (int v4 = 0; v4 < RANK; ++v4) {
+                        const float4 p = src[v4];
+                        z[4 * v4] = p.x; z[4 * v4 + 1] = p.y; z[4 * v4 + 2] = p.z; z[4 * v4 + 3] = p.w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float corr = 0.f;
+#pragma unroll
+                for (int l = 0; l < RANK; ++l) corr = fmaf(tc[l], z[e * RANK + l], corr);
+                y[e] += corr;
+            }
+        }
+        if (a.act == EGG_ACT_GELU) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = 0.5f * y[e] * (1.0f + erff(y[e] * 0.70710678118654752f));
+        }
+        const int64_t off = (int64_t)n * a.d_out + m;
+        if (a.y_bf16) {
+            uint2 p;
+            p.x = pack_bf16x2(y[0], y[1]);
+            p.y = pack_bf16x2(y[2], y[3]);
+            *(uint2*)((uint16_t*)a.Y + off) = p;
+        } else {
+            *(float4*)((float*)a.Y + off) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    }
+};
+
+template <class MT, int BM, int BN, int WM, int WN, bool DIRECT, class Epi>
+static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
+                              const typename Epi::Args& ea)
+{
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, DIRECT, Epi>;
+    const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
+    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    if (st != EGG_OK) return st;
+    const int64_t grid = (int64_t)tiles_m * tiles_n;
+    if (grid > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many tiles");
+    KernelScope ks(c, name);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks, tiles_m, tiles_n,
+                       (const char*)c->zero_page.p, ea);
+    return check_hip(c, hipGetLastError(), name);
+}
+
+template <bool BF16, int RANK, bool REGEN>
+static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype yd, float sigma,
+                                   egg_act act, const void* W, const void* X, void* Y, const float* t, void* A_buf)
+{
+    typedef FwdEpi<BF16, RANK, REGEN> Epi;
+    const int esz = BF16 ? 2 : 4;
+    const int64_t R = s.member_count * (int64_t)s.rows_per_member;
+    Operand P{(const char*)W, (int64_t)s.d_in * esz, 16, s.d_out};
+    Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
+    const int kchunks = s.d_in * esz / 16;
+    typename Epi::Args ea{ka, (uint32_t)s.member_begin, s.rows_per_member, s.d_out, sigma / sqrtf((float)s.rank),
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf};
+    const bool direct = use_direct_loader();
+    if (!operand_offsets_fit(P, 256) || !operand_offsets_fit(Q, 256)) return fail(c, EGG_EUNSUPPORTED, "d_in too large for 32-bit tile offsets");
+    if constexpr (BF16) {
+        const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
+        if (big_tiles >= 192) {
+            if constexpr (REGEN) {  // tuning knob for the large-tile wave layout (default 0: 2 x 4 waves)
+                static const int variant = [] { const char* e = getenv("EGGROLL_GEMM_VARIANT"); return e ? atoi(e) : 0; }();
+                if (variant == 1) return launch_gemm<MmaBf16, 256, 256, 2, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+                if (variant == 2) return launch_gemm<MmaBf16, 256, 256, 4, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+                if (variant == 3) return launch_gemm<MmaBf16, 256, 128, 2, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+            }
+            return direct ? launch_gemm<MmaBf16, 256, 256, 2, 4, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea)
+                          : launch_gemm<MmaBf16, 256, 256, 2, 4, false, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+        }
+        return direct ? launch_gemm<MmaBf16, 128, 128, 2, 2, true, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea)
+                      : launch_gemm<MmaBf16, 128, 128, 2, 2, false, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
+    } else {
+        return direct ? launch_gemm<MmaF32, 128, 128, 2, 2, true, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea)
+                      : launch_gemm<MmaF32, 128, 128, 2, 2, false, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);
+    }
+}
+
+egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
+                               float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
+                               void* A_cache)
+{
+    const bool bf = io == EGG_BF16;
+    // rank 1 with one row per member (or the unperturbed pass): regenerate in the epilogue
+    if (sigma == 0.f || (s.rank == 1 && s.rows_per_member == 1)) {
+        return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache)
+                  : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache);
+    }
+    // otherwise materialise A once (into the caller's cache if there is one) and read it back
+    void* A_buf = A_cache;
+    if (!A_buf) {
+        const size_t bytes = (size_t)s.member_count * s.d_out * s.rank * (bf ? 2 : 4);
+        egg_status st = reserve(c, c->a_buf, bytes);
+        if (st != EGG_OK) return st;
+        A_buf = c->a_buf.p;
+    }
+    egg_status st = launch_noise(c, ka, (uint32_t)s.member_begin, s.member_count, (int64_t)s.d_out * s.rank, io,
+                                 EGG_NORMAL, 0, A_buf);
+    if (st != EGG_OK) return st;
+#define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf)
+    if (bf) {
+        switch (s.rank) {
+            case 1: EGG_FWD(true, 1);
+            case 2: EGG_FWD(true, 2);
+            case 4: EGG_FWD(true, 4);
+            default: EGG_FWD(true, 8);
+        }
+    } else {
+        switch (s.rank) {
+            case 1: EGG_FWD(false, 1);
+            case 2: EGG_FWD(false, 2);
+            case 4: EGG_FWD(false, 4);
+            default: EGG_FWD(false, 8);
+        }
+    }
+#undef EGG_FWD
+}
+
+}  // namespace egg

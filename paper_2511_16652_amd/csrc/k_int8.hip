@@ -1,0 +1,132 @@
+// Integer perturbed matmul of the int8 recurrent model, bit-exact
+// (App. "Matrix Multiplication": u @ M = I8(uM / (16 sqrt n)), a right shift for n = 4^d;
+//  App. "Adding EGGROLL Perturbations": I8((u theta^T + ((u . B) I32(A) >> (4 + sigma_hat))) / (16 sqrt n))).
+// Per step: one wave-per-row int8 dot kernel for u . B_i, then the int8 MFMA NT core for u theta^T
+// whose epilogue adds the shifted rank-1 term, shifts, saturates to [-127, 127] and stores int8.
+// The factors are fixed while a member is evaluated (Alg. 1), so they are generated once per call
+// into scratch and re-read from L2/HBM at every step.
+#include "common.hpp"
+#include "gemm_core.hpp"
+
+namespace egg {
+
+// dots[row] = sum_k H[row][k] * B[row][k]   (int8 x int8 -> int32), one wave per row
+__global__ __launch_bounds__(256) void dot_i8_kernel(const int8_t* __restrict__ H, const int8_t* __restrict__ B,
+                                                     int64_t rows, int d, int* __restrict__ dots)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const u32x4* h = (const u32x4*)(H + row * d);
+    const u32x4* b = (const u32x4*)(B + row * d);
+    int acc = 0;
+    for (int ch = lane; ch < (d >> 4); ch += 64) {
+        const u32x4 hv = h[ch], bv = b[ch];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int x = (int)(int8_t)(hv[w] >> (8 * q));
+                const int y = (int)(int8_t)(bv[w] >> (8 * q));
+                acc += x * y;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) dots[row] = acc;
+}
+
+struct I8Epi {
+    typedef int value_t;
+    struct Args {
+        const int8_t* A;  // [rows][d] factors
+        const int* dots;  // [rows]
+        int8_t* H_out;    // [rows][d]
+        int d, corr_shift, out_shift;
+    };
+    const Args a;
+    int dot;
+    __device__ __forceinline__ I8Epi(const Args& a_, char*) : a(a_), dot(0) {}
+    __device__ __forceinline__ void column(int n, bool valid)
+    {
+        if (valid) dot = a.dots[n];
+    }
+    __device__ __forceinline__ void store4(int m, int n, const int (&v)[4], bool valid)
+    {
+        if (!valid || m >= a.d) return;
+        const int64_t off = (int64_t)n * a.d + m;
+        const uint32_t a4 = *(const uint32_t*)(a.A + off);
+        uint32_t out = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int ae = (int)(int8_t)(a4 >> (8 * e));
+            const int corr = (dot * ae) >> a.corr_shift;  // arithmetic shift: floor
+            int y = (v[e] + corr) >> a.out_shift;
+            y = min(127, max(-127, y));
+            out |= ((uint32_t)y & 0xFFu) << (8 * e);
+        }
+        *(uint32_t*)(a.H_out + off) = out;
+    }
+};
+
+template <int BM, int BN, int WM, int WN>
+static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand& Q, int kchunks, const I8Epi::Args& ea)
+{
+    const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
+    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
+    auto kern = use_direct_loader() ? gemm_nt_kernel<MmaI8, BM, BN, WM, WN, true, I8Epi> : gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, I8Epi>;
+    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    if (st != EGG_OK) return st;
+    KernelScope ks(c, "forward_gemm_i8");
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks,
+                       tiles_m, tiles_n, (const char*)c->zero_page.p, ea);
+    return check_hip(c, hipGetLastError(), "forward_gemm_i8");
+}
+
+egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
+                             int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
+                             const int8_t* H_in, int8_t* H_out)
+{
+    const int d = s.d_in;
+    const int64_t rows = s.member_count;
+    const size_t hbytes = (size_t)rows * d;
+    egg_status st;
+    if ((st = reserve(c, c->i8_a, hbytes)) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_b, hbytes)) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_h, 2 * ((hbytes + 255) & ~size_t(255)))) != EGG_OK) return st;
+    if ((st = reserve(c, c->t_buf, (size_t)rows * sizeof(int))) != EGG_OK) return st;
+    int8_t* A = (int8_t*)c->i8_a.p;
+    int8_t* B = (int8_t*)c->i8_b.p;
+    int8_t* scratch[2] = {(int8_t*)c->i8_h.p, (int8_t*)c->i8_h.p + ((hbytes + 255) & ~size_t(255))};
+    int* dots = (int*)c->t_buf.p;
+
+    if ((st = launch_noise(c, ka, (uint32_t)s.member_begin, rows, d, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
+    if ((st = launch_noise(c, kb, (uint32_t)s.member_begin, rows, d, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
+
+    const int64_t big_tiles = ((d + 255) / 256) * ((rows + 255) / 256);
+    const int8_t* src = H_in;
+    for (int t = 0; t < steps; ++t) {
+        int8_t* dst = (t == steps - 1) ? H_out : scratch[t & 1];
+        const bool alias = (dst == src);  // only possible for steps == 1 with H_out == H_in
+        if (alias) dst = scratch[0];
+        {
+            KernelScope ks(c, "dot_i8");
+            hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, src, B, rows, d, dots);
+        }
+        if ((st = check_hip(c, hipGetLastError(), "dot_i8 launch")) != EGG_OK) return st;
+        Operand P{(const char*)W, (int64_t)d, 16, d};
+        Operand Q{(const char*)src, (int64_t)d, 16, (int)rows};
+        I8Epi::Args ea{A, dots, dst, d, corr_shift, out_shift};
+        st = big_tiles >= 192 ? launch_i8_gemm<256, 256, 2, 4>(c, P, Q, d / 16, ea) : launch_i8_gemm<128, 128, 2, 2>(c, P, Q, d / 16, ea);
+        if (st != EGG_OK) return st;
+        if (alias) {
+            if ((st = check_hip(c, hipMemcpyAsync(H_out, dst, hbytes, hipMemcpyDeviceToDevice, c->stream), "copy back")) != EGG_OK) return st;
+        }
+        src = dst;
+    }
+    return EGG_OK;
+}
+
+}  // namespace egg

@@ -1,0 +1,131 @@
+// Projection pre-pass of the population forward:  t[q][l] = sum_k X[q][k] * B_i[k][l]
+// (Sec. 4.2: for r = 1 "a batch of N vector-vector dot products of length d_in"; the B x r
+// intermediate of the arithmetic-intensity appendix).  One workgroup per member: B_i is regenerated
+// once into LDS (and optionally kept in the caller's cache), then the member's S rows are streamed
+// against it, one wave per row.  HBM-bound on X for large S, integer-ALU bound (noise) for S = 1.
+#include "common.hpp"
+
+namespace egg {
+
+template <bool BF16, int RANK>
+__global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int d_in,
+                                                      const void* __restrict__ X, float* __restrict__ t,
+                                                      void* __restrict__ B_cache)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x;
+    const int64_t ml = blockIdx.x;  // local member
+    const uint32_t member = member_begin + (uint32_t)ml;
+    const int n = d_in * RANK;  // even: d_in is a multiple of 4
+
+    // ---- phase 1: B_i -> LDS (storage dtype), optional cache -------------------------------------
+    for (int b = tid; b < (n >> 1); b += 256) {
+        uint32_t w0, w1;
+        noise_words(kb, member, (uint32_t)b, w0, w1);
+        float z0, z1;
+        normal_pair<!BF16>(w0, w1, z0, z1);
+        if constexpr (BF16) {
+            const uint32_t pk = pack_bf16x2(z0, z1);
+            ((uint32_t*)smem)[b] = pk;
+            if (B_cache) ((uint32_t*)B_cache)[ml * (n >> 1) + b] = pk;
+        } else {
+            ((float2*)smem)[b] = make_float2(z0, z1);
+            if (B_cache) ((float2*)B_cache)[ml * (n >> 1) + b] = make_float2(z0, z1);
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: one wave per row ----------------------------------------------------------------
+    constexpr int EPC = BF16 ? 8 : 4;  // elements per 16-byte chunk of X
+    const int lane = tid & 63, wave = tid >> 6;
+    const int chunks = d_in / EPC;
+    for (int s = wave; s < S; s += 4) {
+        const int64_t row = ml * S + s;
+        const uint4* xr = (const uint4*)((const char*)X + row * (int64_t)d_in * (BF16 ? 2 : 4));
+        float acc[RANK];
+#pragma unroll
+        for (int l = 0; l < RANK; ++l) acc[l] = 0.f;
+        for (int ch = lane; ch < chunks; ch += 64) {
+            const uint4 xv = xr[ch];
+            float x[EPC];
+            if constexpr (BF16) {
+                const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x[2 * e] = __uint_as_float(w[e] << 16);
+                    x[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+                }
+            } else {
+                x[0] = __uint_as_float(xv.x); x[1] = __uint_as_float(xv.y);
+                x[2] = __uint_as_float(xv.z); x[3] = __uint_as_float(xv.w);
+            }
+            // B_i[k][l] for the chunk's k range: EPC*RANK consecutive elements = RANK 16-byte reads
+            const uint4* bp = (const uint4*)smem + (int64_t)ch * RANK;
+            float bv[EPC * RANK];
+#pragma unroll
+            for (int v = 0; v < RANK; ++v) {
+                const uint4 q = bp[v];
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+                if constexpr (BF16) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        bv[v * 8 + 2 * e] = __uint_as_float(w[e] << 16);
+                        bv[v * 8 + 2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) bv[v * 4 + e] = __uint_as_float(w[e]);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPC; ++e)
+#pragma unroll
+                for (int l = 0; l < RANK; ++l) acc[l] = fmaf(x[e], bv[e * RANK + l], acc[l]);
+        }
+#pragma unroll
+        for (int l = 0; l < RANK; ++l) {
+            float v = acc[l];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0) t[row * RANK + l] = v;
+        }
+    }
+}
+
+template <bool BF16>
+static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, const void* X, float* t,
+                                   void* B_cache)
+{
+    const size_t lds = (size_t)s.d_in * s.rank * (BF16 ? 2 : 4);
+    if (lds > 128 * 1024) return fail(c, EGG_EUNSUPPORTED, "d_in * rank = %lld too large for the projection pass", (long long)s.d_in * s.rank);
+    const dim3 g((unsigned)s.member_count), b(256);
+    if (s.member_count > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many members in one call");
+    const uint32_t mb = (uint32_t)s.member_begin;
+#define EGG_LAUNCH_PROJECT(R)                                                                                        \
+    {                                                                                                                \
+        auto kern = project_kernel<BF16, R>;                                                                         \
+        if (lds > 48 * 1024) {                                                                                       \
+            egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "project smem attr"); \
+            if (st != EGG_OK) return st;                                                                             \
+        }                                                                                                            \
+        KernelScope ks(c, "project");                                                                                \
+        hipLaunchKernelGGL(kern, g, b, lds, c->stream, kb, mb, s.rows_per_member, s.d_in, X, t, B_cache);            \
+    }
+    switch (s.rank) {
+        case 1: EGG_LAUNCH_PROJECT(1) break;
+        case 2: EGG_LAUNCH_PROJECT(2) break;
+        case 4: EGG_LAUNCH_PROJECT(4) break;
+        default: EGG_LAUNCH_PROJECT(8) break;
+    }
+#undef EGG_LAUNCH_PROJECT
+    return check_hip(c, hipGetLastError(), "project launch");
+}
+
+egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
+                          float* t, void* B_cache)
+{
+    return io == EGG_BF16 ? launch_project_t<true>(c, kb, s, X, t, B_cache)
+                          : launch_project_t<false>(c, kb, s, X, t, B_cache);
+}
+
+}  // namespace egg

@@ -1,0 +1,198 @@
+// EGGROLL update direction (EGGROLL UPDATE box; Sec. 4.2):
+//   G = scale * sum_i f_i A_i B_i^T = scale * (diag(f~) A~)^T B~,  A~ in R^{K x d_out}, B~ in R^{K x d_in},
+//   K = N*r, row kappa = i*r + l holds A_i[:, l] (resp. B_i[:, l]), f~ repeats f r times.
+// Two steps: (1) a pack pass turns the [member][d][r] factors (the forward's caches, or freshly
+// regenerated ones) into K-packed panels -- 16-byte chunks of consecutive kappa for one column --
+// with the fitness folded into the A panel; (2) the MFMA NT core contracts the panels over K.
+// bf16 factors are packed as fp16: every bf16 normal is exactly representable there and f_i*a keeps
+// 11 significant bits instead of 8; fp32 factors stay fp32.  No atomics: each G entry has one owner
+// and a fixed summation order, so the result is run-to-run identical.
+#include "common.hpp"
+#include "gemm_core.hpp"
+
+namespace egg {
+
+// fnorm[0] = 2^ceil(log2(max|f|)) (1 if all zero), fnorm[1] = 1/fnorm[0].  Folding f/fnorm[0] into the
+// fp16 panel and fnorm[0] into the epilogue scale is exact (a power of two) and keeps f_i*a inside
+// the fp16 range whatever the magnitude of the fitness values.
+__global__ __launch_bounds__(256) void fitness_norm_kernel(const float* __restrict__ f, int64_t n, float* __restrict__ fnorm)
+{
+    __shared__ float red[256];
+    float m = 0.f;
+    for (int64_t i = threadIdx.x; i < n; i += 256) m = fmaxf(m, fabsf(f[i]));
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float mx = red[0];
+        float p = 1.f;
+        if (mx > 0.f && mx < 3.0e38f) {
+            int e;
+            (void)frexpf(mx, &e);  // mx = frac * 2^e, frac in [0.5, 1)
+            p = ldexpf(1.f, e);
+        }
+        fnorm[0] = p;
+        fnorm[1] = 1.f / p;
+    }
+}
+
+// out chunk (kg, col) at (kg*d + col)*16 bytes holds kappa = kg*EPC .. +EPC-1 of column `col`.
+template <bool BF16>
+__global__ __launch_bounds__(256) void pack_kernel(const void* __restrict__ src, const float* __restrict__ fitness,
+                                                   const float* __restrict__ fnorm, int64_t members, int d, int rank, int64_t kgroups,
+                                                   void* __restrict__ out)
+{
+    constexpr int EPC = BF16 ? 8 : 4;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= kgroups * d) return;
+    const int64_t kg = gid / d;
+    const int col = (int)(gid - kg * d);
+    const int64_t K = members * rank;
+    const float finv = fitness ? fnorm[1] : 1.f;
+    float v[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+        const int64_t kappa = kg * EPC + e;
+        float x = 0.f;
+        if (kappa < K) {
+            const int64_t i = kappa / rank;
+            const int l = (int)(kappa - i * rank);
+            const int64_t off = (i * d + col) * rank + l;
+            if constexpr (BF16) x = __uint_as_float((uint32_t)((const uint16_t*)src)[off] << 16);
+            else x = ((const float*)src)[off];
+            if (fitness) x *= fitness[i] * finv;
+        }
+        v[e] = x;
+    }
+    if constexpr (BF16) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h2 p;
+            p[0] = (_Float16)v[2 * e];  // round to nearest even
+            p[1] = (_Float16)v[2 * e + 1];
+            o[e] = __builtin_bit_cast(uint32_t, p);
+        }
+        ((u32x4*)out)[gid] = o;
+    } else {
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = __float_as_uint(v[e]);
+        ((u32x4*)out)[gid] = o;
+    }
+}
+
+struct UpdEpi {
+    typedef float value_t;
+    struct Args {
+        float* G;
+        void* W;
+        const float* fnorm;
+        int d_out, d_in;
+        float scale, lr;
+        int accumulate, w_bf16;
+    };
+    const Args a;
+    float scale;
+    __device__ __forceinline__ UpdEpi(const Args& a_, char*) : a(a_) { scale = a.scale * a.fnorm[0]; }
+    __device__ __forceinline__ void column(int, bool) {}
+    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid)
+    {
+        if (!valid || m >= a.d_out) return;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t idx = (int64_t)(m + e) * a.d_in + n;
+            float g = scale * v[e];
+            if (a.accumulate) g += a.G[idx];
+            a.G[idx] = g;
+            if (a.W) {
+                if (a.w_bf16) {
+                    uint16_t* w = (uint16_t*)a.W + idx;
+                    *w = f32_to_bf16_bits(fmaf(a.lr, g, bf16_bits_to_f32(*w)));
+                } else {
+                    float* w = (float*)a.W + idx;
+                    *w = fmaf(a.lr, g, *w);
+                }
+            }
+        }
+    }
+};
+
+template <class MT, int BM, int BN, int WM, int WN>
+static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
+                                  const UpdEpi::Args& ea)
+{
+    const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
+    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
+    auto kern = use_direct_loader() ? gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpi> : gemm_nt_kernel<MT, BM, BN, WM, WN, false, UpdEpi>;
+    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    if (st != EGG_OK) return st;
+    KernelScope ks(c, name);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks,
+                       tiles_m, tiles_n, (const char*)c->zero_page.p, ea);
+    return check_hip(c, hipGetLastError(), name);
+}
+
+egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
+                         egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
+                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache)
+{
+    const bool bf = noise_dtype == EGG_BF16;
+    const int esz = bf ? 2 : 4, epc = bf ? 8 : 4;
+    const int64_t K = s.member_count * (int64_t)s.rank;
+    const int64_t kgroups = (K + epc - 1) / epc;
+    if (kgroups > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "population * rank too large");
+    egg_status st;
+
+    // factors in [member][d][r] layout: the caller's caches, or regenerated into scratch
+    const void* A_src = A_cache;
+    const void* B_src = B_cache;
+    if (!A_src) {
+        const size_t na = (size_t)s.member_count * s.d_out * s.rank * esz, nb = (size_t)s.member_count * s.d_in * s.rank * esz;
+        if ((st = reserve(c, c->a_buf, na)) != EGG_OK) return st;
+        if ((st = reserve(c, c->b_buf, nb)) != EGG_OK) return st;
+        if ((st = launch_noise(c, ka, (uint32_t)s.member_begin, s.member_count, (int64_t)s.d_out * s.rank, noise_dtype, EGG_NORMAL, 0, c->a_buf.p)) != EGG_OK) return st;
+        if ((st = launch_noise(c, kb, (uint32_t)s.member_begin, s.member_count, (int64_t)s.d_in * s.rank, noise_dtype, EGG_NORMAL, 0, c->b_buf.p)) != EGG_OK) return st;
+        A_src = c->a_buf.p;
+        B_src = c->b_buf.p;
+    }
+
+    if ((st = reserve(c, c->fnorm, 256)) != EGG_OK) return st;
+    float* fnorm = (float*)c->fnorm.p;
+    {
+        KernelScope ks(c, "fitness_norm");
+        hipLaunchKernelGGL(fitness_norm_kernel, dim3(1), dim3(256), 0, c->stream, fitness, s.member_count, fnorm);
+    }
+    if ((st = reserve(c, c->pack_a, (size_t)kgroups * s.d_out * 16)) != EGG_OK) return st;
+    if ((st = reserve(c, c->pack_b, (size_t)kgroups * s.d_in * 16)) != EGG_OK) return st;
+    {
+        const int64_t ta = kgroups * s.d_out, tb = kgroups * s.d_in;
+        if ((ta + 255) / 256 > 0x7FFFFFFF || (tb + 255) / 256 > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "pack grid too large");
+        KernelScope ks(c, "update_pack");
+        if (bf) {
+            hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)((ta + 255) / 256)), dim3(256), 0, c->stream, A_src, fitness, fnorm, s.member_count, s.d_out, s.rank, kgroups, c->pack_a.p);
+            hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)((tb + 255) / 256)), dim3(256), 0, c->stream, B_src, (const float*)nullptr, fnorm, s.member_count, s.d_in, s.rank, kgroups, c->pack_b.p);
+        } else {
+            hipLaunchKernelGGL(pack_kernel<false>, dim3((unsigned)((ta + 255) / 256)), dim3(256), 0, c->stream, A_src, fitness, fnorm, s.member_count, s.d_out, s.rank, kgroups, c->pack_a.p);
+            hipLaunchKernelGGL(pack_kernel<false>, dim3((unsigned)((tb + 255) / 256)), dim3(256), 0, c->stream, B_src, (const float*)nullptr, fnorm, s.member_count, s.d_in, s.rank, kgroups, c->pack_b.p);
+        }
+        if ((st = check_hip(c, hipGetLastError(), "pack launch")) != EGG_OK) return st;
+    }
+
+    Operand P{(const char*)c->pack_a.p, 16, (int64_t)s.d_out * 16, s.d_out};
+    Operand Q{(const char*)c->pack_b.p, 16, (int64_t)s.d_in * 16, s.d_in};
+    UpdEpi::Args ea{G, W, fnorm, s.d_out, s.d_in, scale, lr, accumulate, w_dtype == EGG_BF16 ? 1 : 0};
+    if (bf) {
+        const int64_t big_tiles = ((s.d_out + 255) / 256) * (int64_t)((s.d_in + 255) / 256);
+        if (big_tiles >= 192) return launch_upd_gemm<MmaF16, 256, 256, 2, 4>(c, "update_gemm_f16", P, Q, (int)kgroups, ea);
+        return launch_upd_gemm<MmaF16, 128, 128, 2, 2>(c, "update_gemm_f16_small", P, Q, (int)kgroups, ea);
+    }
+    return launch_upd_gemm<MmaF32, 128, 128, 2, 2>(c, "update_gemm_f32", P, Q, (int)kgroups, ea);
+}
+
+}  // namespace egg

@@ -1,0 +1,45 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the header
+declares, and the binding declares the same set (no compute calls: there is no GPU here)."""
+import os
+import re
+
+import pytest
+
+from paper_2511_16652_amd import binding as eb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "eggroll.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(eggroll_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert header_functions() == sorted(eb.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(eb.LIB_PATH):
+        pytest.fail("libeggroll.so has not been built (python -m paper_2511_16652_amd.build)")
+    lib = eb.load_library()
+    for name in header_functions():
+        assert hasattr(lib, name), name
+
+
+def test_host_only_entry_points():
+    lib = eb.load_library()
+    assert lib.eggroll_strerror(eb.EGG_OK) == b"ok"
+    assert b"invalid" in lib.eggroll_strerror(eb.EGG_EINVAL)
+    assert abs(eb.eggroll_default_scale(4096, 1e-3, 1) - 1.0 / (4096 * 1e-3)) < 1e-12
+    assert abs(eb.eggroll_default_scale(16, 0.5, 4) - 1.0 / (16 * 0.5 * 2.0)) < 1e-12
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2511_16652_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, f
