@@ -57,17 +57,6 @@ struct KernelScope {
     ~KernelScope();
 };
 
-// EGGROLL_GEMM_LOADER=staged selects the register-staged global->LDS path of the GEMM core
-// (default: direct-to-LDS loads).
-inline bool use_direct_loader()
-{
-    static const int v = [] {
-        const char* e = getenv("EGGROLL_GEMM_LOADER");
-        return (e && e[0] == 's') ? 0 : 1;
-    }();
-    return v != 0;
-}
-
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows);

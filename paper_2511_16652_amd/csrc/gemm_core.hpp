@@ -6,15 +6,24 @@
 //   - the update contraction (diag(f)A)^T B over K = N*r (P, Q = K-packed factor panels), Sec. 4.2
 //   - the int8 x int8 -> int32 matmul of the integer model, App. "Matrix Multiplication".
 // A workgroup owns a BM x BN tile of C; 64-wide waves own 32x32 MFMA blocks of it.  K advances in
-// tiles of 8 chunks (128 bytes per row), double-buffered in LDS.  Rows of an LDS tile are 128 bytes
-// with the chunk slot XOR-swizzled by (row>>1)&7, which makes the 16-byte fragment reads of any 16
-// neighbouring rows hit distinct banks; the swizzle is applied on the global side so that
-// direct-to-LDS loads (which place lane t's 16 bytes at base + 16 t) can be used.
+// stages of 8 chunks (128 bytes per row) double-buffered in LDS; the global loads of stage kt+2 are
+// in flight in registers while stage kt is multiplied and stage kt+1 sits in the other LDS buffer.
+// Rows of an LDS stage are 128 bytes with the chunk slot XOR-swizzled by (row>>1)&7, which makes
+// the 16-byte fragment reads of any 16 neighbouring rows hit distinct banks (measured: zero bank
+// conflicts).
 // The epilogue is a functor that receives, per lane, 4 consecutive rows m..m+3 of one column n:
 // that is exactly one aligned group of factor entries A_i[m..m+3][:] for the member of column n.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+// diagnosis switches for standalone experiments (never set in the library build)
+#ifndef EGG_DBG_SKIP_LOADS
+#define EGG_DBG_SKIP_LOADS 0
+#endif
+#ifndef EGG_DBG_SKIP_MMA
+#define EGG_DBG_SKIP_MMA 0
+#endif
 
 namespace egg {
 
@@ -87,57 +96,45 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     tn = in_group / gsz;
 }
 
-// Global -> LDS movement of one K-tile (BM + BN rows of 128 bytes).  Load `it` of a thread covers
-// chunk-linear index it*NT + tid: row = idx/8, LDS slot = idx%8.  Addresses are a wave-uniform
-// 64-bit base (tile origin + K offset, kept in scalar registers) plus a loop-invariant 32-bit
-// per-lane offset.  DIRECT uses the LDS-DMA form of the global load (lane t of a wave lands at
-// base + 16 t); otherwise the tile is staged in registers and written with ds_write_b128.
-template <int BM, int BN, int NT, bool DIRECT>
+// Global -> LDS movement of one K-stage (ROWS rows of 128 bytes), staged through registers:
+// global_load_dwordx4 into `regs` one whole stage ahead of its use, then ds_write_b128 into the LDS
+// buffer that the last barrier retired.  (The LDS-DMA form of the global load was measured at less
+// than half the L2 streaming rate of plain 16-byte loads on gfx950, so it is not used.)
+// Load `it` of a thread covers chunk-linear index it*NT + tid: row = idx/8, LDS slot = idx%8,
+// global chunk = slot ^ ((row>>1)&7).  Addresses are a wave-uniform 64-bit base (tile origin + K
+// offset, kept in scalar registers) plus a loop-invariant 32-bit per-lane offset.
+template <int ROWS, int NT>
 struct Loader {
-    static constexpr int LP = BM * 8 / NT, LQ = BN * 8 / NT;
-    u32x4 rp[DIRECT ? 1 : LP], rq[DIRECT ? 1 : LQ];
+    static constexpr int L = ROWS * 8 / NT;
+    uint32_t off[L];
+    int chunk[L];  // global chunk index (0..7) of each load, for the K tail
+    u32x4 regs[L];
 
-    template <int L>
-    __device__ __forceinline__ void side(const char* base, const uint32_t (&off)[L], const int (&chunk)[L], int kfirst,
-                                         int kchunks, bool tail, char* sdst, const char* zero_page, int wave,
-                                         u32x4 (&regs)[DIRECT ? 1 : L])
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid)
+    {
+#pragma unroll
+        for (int it = 0; it < L; ++it) {
+            const int c = it * NT + tid;
+            const int row = c >> 3;
+            chunk[it] = (c & 7) ^ ((row >> 1) & 7);
+            const int rl = min(row, o.rows - 1 - row0);  // rows past the end re-read the last valid row
+            off[it] = (uint32_t)((int64_t)rl * o.row_stride + (int64_t)chunk[it] * o.kc_stride);
+        }
+    }
+    // chunks past the end of K (only possible in the last stage) read the zero page instead
+    __device__ __forceinline__ void load(const char* base, int kfirst, int kchunks, const char* zero_page)
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
             const char* g = base + (uint64_t)off[it];
-            if (tail && kfirst + chunk[it] >= kchunks) g = zero_page;
-            if constexpr (DIRECT) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                                 (lds_ptr_t)(sdst + (it * NT + wave * 64) * 16), 16, 0, 0);
-            } else {
-                regs[it] = *(const u32x4*)g;
-            }
+            if (kfirst + chunk[it] >= kchunks) g = zero_page;
+            regs[it] = *(const u32x4*)g;
         }
     }
-
-    __device__ __forceinline__ void issue(int kt, int kchunks, char* sbase, const char* pb, const char* qb,
-                                          const uint32_t (&po)[LP], const uint32_t (&qo)[LQ], const int (&cp)[LP],
-                                          const int (&cq)[LQ], int64_t pstep, int64_t qstep, const char* zero_page,
-                                          int wave)
+    __device__ __forceinline__ void store(char* sdst, int tid) const
     {
-        const char* pk = pb + (int64_t)kt * pstep;
-        const char* qk = qb + (int64_t)kt * qstep;
-        if (kt * 8 + 8 <= kchunks) {  // full K-tile: no predicate on the loads
-            side<LP>(pk, po, cp, kt * 8, kchunks, false, sbase, zero_page, wave, rp);
-            side<LQ>(qk, qo, cq, kt * 8, kchunks, false, sbase + BM * 128, zero_page, wave, rq);
-        } else {
-            side<LP>(pk, po, cp, kt * 8, kchunks, true, sbase, zero_page, wave, rp);
-            side<LQ>(qk, qo, cq, kt * 8, kchunks, true, sbase + BM * 128, zero_page, wave, rq);
-        }
-    }
-    __device__ __forceinline__ void commit(char* sbase, int tid)
-    {
-        if constexpr (!DIRECT) {
 #pragma unroll
-            for (int it = 0; it < LP; ++it) *(u32x4*)(sbase + (it * NT + tid) * 16) = rp[it];
-#pragma unroll
-            for (int it = 0; it < LQ; ++it) *(u32x4*)(sbase + BM * 128 + (it * NT + tid) * 16) = rq[it];
-        }
+        for (int it = 0; it < L; ++it) *(u32x4*)(sdst + (it * NT + tid) * 16) = regs[it];
     }
 };
 
@@ -147,16 +144,25 @@ inline bool operand_offsets_fit(const Operand& o, int tile_rows)
     return (int64_t)tile_rows * o.row_stride + 8 * o.kc_stride < (int64_t(1) << 32);
 }
 
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes()
+{
+    return (size_t)2 * (BM + BN) * 128;
+}
+
 // Epi requirements:
-//   struct Args (trivially copyable);  __device__ Epi(const Args&, char* lds_scratch);
+//   struct Args (trivially copyable);  static constexpr int lds_per_wave(int wtm);
+//   __device__ Epi(const Args&, char* wave_lds_slice, int lane);
 //   __device__ void column(int n, bool valid);                       called once per owned column
-//   __device__ void store4(int m, int n, const T (&v)[4], bool col_valid);   rows m..m+3 of column n
+//   __device__ void store4(int m, int n, const T (&v)[4], bool col_valid, int ml);  rows m..m+3 of column n
+//   template <int WTM> __device__ void flush(int mw0, int nb0, int n_rows);   after each 32-column block
 //
-// Main loop, per K-tile (4 MFMA k-steps): the fragments of k-step s+1 are read from LDS while the
-// MFMAs of k-step s run (two fragment register sets); the global->LDS loads of the next K-tile are
-// issued right after the barrier that retires the previous one, so they have a whole tile of MFMA
-// work to land; the single barrier per K-tile sits in the middle of the last k-step.
-template <class MT, int BM, int BN, int WM, int WN, bool DIRECT, class Epi>
+// Main loop, per K-stage (4 MFMA k-steps): the fragments of k-step s+1 are read from LDS while the
+// MFMAs of k-step s run (two fragment register sets).  During k-step 1 the registers holding stage
+// kt+1 are written to the free LDS buffer, during k-step 2 the loads of stage kt+2 are issued into
+// them (a whole stage of MFMA work to land); the single barrier of the stage sits in the middle of
+// k-step 3, after which the first fragments of stage kt+1 are read.
+template <class MT, int BM, int BN, int WM, int WN, class Epi>
 __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, const char* zero_page,
                                                                    typename Epi::Args ea)
@@ -164,10 +170,10 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     constexpr int NT = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MB = WTM / 32, NB = WTN / 32;
-    constexpr int LP = BM * 8 / NT, LQ = BN * 8 / NT;  // 16-byte loads per thread per K-tile
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile rows must divide over the threads");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tiles are made of 32x32 blocks");
-    constexpr int STAGE_BYTES = (BM + BN) * 128;
+    constexpr int PITCH = 128;  // bytes per LDS row
+    constexpr int STAGE_BYTES = (BM + BN) * PITCH;
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "stage rows must divide over the threads");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && MB % 2 == 0, "wave tiles are made of 32x32 blocks");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -180,29 +186,12 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // ---- global -> LDS addressing -------------------------------------------------------------
-    // load `it` of this thread covers chunk-linear index c = it*NT + tid of the tile:
-    // row = c / 8, LDS slot = c % 8, global chunk = slot ^ ((row>>1)&7).
     const char* pb = P.base + (int64_t)m0 * P.row_stride;
     const char* qb = Q.base + (int64_t)n0 * Q.row_stride;
-    uint32_t po[LP], qo[LQ];
-    int cp[LP], cq[LQ];  // global chunk index (0..7) of each load, for the K tail
-#pragma unroll
-    for (int it = 0; it < LP; ++it) {
-        const int c = it * NT + tid;
-        const int row = c >> 3;
-        cp[it] = (c & 7) ^ ((row >> 1) & 7);
-        const int rl = min(row, P.rows - 1 - m0);  // rows past the end re-read the last valid row
-        po[it] = (uint32_t)((int64_t)rl * P.row_stride + (int64_t)cp[it] * P.kc_stride);
-    }
-#pragma unroll
-    for (int it = 0; it < LQ; ++it) {
-        const int c = it * NT + tid;
-        const int row = c >> 3;
-        cq[it] = (c & 7) ^ ((row >> 1) & 7);
-        const int rl = min(row, Q.rows - 1 - n0);
-        qo[it] = (uint32_t)((int64_t)rl * Q.row_stride + (int64_t)cq[it] * Q.kc_stride);
-    }
+    Loader<BM, NT> lp;
+    Loader<BN, NT> lq;
+    lp.init(P, m0, tid);
+    lq.init(Q, n0, tid);
     const int64_t pstep = 8 * P.kc_stride, qstep = 8 * Q.kc_stride;
 
     // ---- LDS fragment addressing ----------------------------------------------------------------
@@ -212,9 +201,9 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     const int fsw = (frow >> 1) & 7;
     int foff[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * 128 + (((2 * ks + (lane >> 5)) ^ fsw) << 4);
-    const int a_base = wm * WTM * 128;
-    const int b_base = BM * 128 + wn * WTN * 128;
+    for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * PITCH + (((2 * ks + (lane >> 5)) ^ fsw) << 4);
+    const int a_base = wm * WTM * PITCH;
+    const int b_base = BM * PITCH + wn * WTN * PITCH;
 
     typename MT::acc_t acc[MB][NB];
 #pragma unroll
@@ -225,60 +214,100 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     const int KT = (kchunks + 7) >> 3;
-    Loader<BM, BN, NT, DIRECT> ld;
     u32x4 fa[2][MB], fb[2][NB];
+    constexpr int LOADS = Loader<BM, NT>::L + Loader<BN, NT>::L;
 
-#define EGG_READ_FRAGS(BUF, STAGE, KS)                                                                         \
+#define EGG_LOAD(KT_)                                                                                          \
     {                                                                                                          \
-        const char* sa_ = lds + (STAGE)*STAGE_BYTES + a_base + foff[KS];                                       \
-        const char* sb_ = lds + (STAGE)*STAGE_BYTES + b_base + foff[KS];                                       \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) fa[BUF][i] = *(const u32x4*)(sa_ + i * 32 * 128);       \
-        _Pragma("unroll") for (int j = 0; j < NB; ++j) fb[BUF][j] = *(const u32x4*)(sb_ + j * 32 * 128);       \
+        lp.load(pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                                       \
+        lq.load(qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                                       \
+    }
+#define EGG_STORE(STAGE_)                                                                                      \
+    {                                                                                                          \
+        lp.store(lds + (STAGE_)*STAGE_BYTES, tid);                                                             \
+        lq.store(lds + (STAGE_)*STAGE_BYTES + BM * PITCH, tid);                                                \
+    }
+#define EGG_READ_FRAGS(BUF, STAGE, KS_)                                                                        \
+    {                                                                                                          \
+        const char* sa_ = lds + (STAGE)*STAGE_BYTES + a_base + foff[KS_];                                      \
+        const char* sb_ = lds + (STAGE)*STAGE_BYTES + b_base + foff[KS_];                                      \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) fa[BUF][i] = *(const u32x4*)(sa_ + i * 32 * PITCH);     \
+        _Pragma("unroll") for (int j = 0; j < NB; ++j) fb[BUF][j] = *(const u32x4*)(sb_ + j * 32 * PITCH);     \
     }
 #define EGG_MMA_ROWS(BUF, I0, I1)                                                                              \
     _Pragma("unroll") for (int i = I0; i < I1; ++i) _Pragma("unroll") for (int j = 0; j < NB; ++j)             \
-        MT::mma(fa[BUF][i], fb[BUF][j], acc[i][j]);
-// interleave: one LDS fragment read behind each of the first MB+NB MFMAs of a k-step
-#define EGG_SCHED_STEP()                                                                                       \
-    _Pragma("unroll") for (int r_ = 0; r_ < MB + NB; ++r_) {                                                   \
-        __builtin_amdgcn_sched_group_barrier(0x008, MT::MFMA_PER_MMA, 0);                                      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                     \
-    }                                                                                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, (MB * NB - MB - NB) * MT::MFMA_PER_MMA, 0);
+        if (!EGG_DBG_SKIP_MMA) MT::mma(fa[BUF][i], fb[BUF][j], acc[i][j]);
+// Scheduling patterns (sched_group_barrier masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write,
+// 0x020 VMEM read).  Every k-step pairs one LDS fragment read with each of its first MB+NB MFMAs;
+// k-step 1 additionally spreads the ds_writes of the next stage, k-step 2 the global loads of the
+// stage after it, so that neither forms a block of memory-only instructions before the barrier.
+#define EGG_SCHED(EXTRA_MASK, EXTRA_N)                                                                         \
+    {                                                                                                          \
+        constexpr int NM_ = MB * NB * MT::MFMA_PER_MMA, NR_ = MB + NB;                                         \
+        constexpr int PER_ = ((EXTRA_N) + NM_ - 1) / NM_;                                                      \
+        _Pragma("unroll") for (int r_ = 0; r_ < NM_; ++r_) {                                                   \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
+            if (r_ < NR_) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
+            if ((EXTRA_N) > 0 && r_ * PER_ < (EXTRA_N)) __builtin_amdgcn_sched_group_barrier(EXTRA_MASK, PER_, 0); \
+        }                                                                                                      \
+    }
+#define EGG_ITER(KT_, DO_STORE, DO_LOAD, MORE)                                                                 \
+    {                                                                                                          \
+        const int cur_ = (KT_)&1;                                                                              \
+        EGG_READ_FRAGS(1, cur_, 1)                                                                             \
+        EGG_MMA_ROWS(0, 0, MB)                                                                                 \
+        EGG_SCHED(0, 0)                                                                                        \
+        EGG_READ_FRAGS(0, cur_, 2)                                                                             \
+        EGG_MMA_ROWS(1, 0, MB)                                                                                 \
+        if (DO_STORE) {                                                                                        \
+            EGG_STORE(cur_ ^ 1) /* stage kt+1: registers -> the buffer retired by the last barrier */          \
+            EGG_SCHED(0x200, LOADS)                                                                            \
+        } else {                                                                                               \
+            EGG_SCHED(0, 0)                                                                                    \
+        }                                                                                                      \
+        EGG_READ_FRAGS(1, cur_, 3)                                                                             \
+        EGG_MMA_ROWS(0, 0, MB)                                                                                 \
+        if (DO_LOAD) {                                                                                         \
+            EGG_LOAD((KT_) + 2) /* stage kt+2 -> registers, a whole stage of MFMA work to land */              \
+            EGG_SCHED(0x020, LOADS)                                                                            \
+        } else {                                                                                               \
+            EGG_SCHED(0, 0)                                                                                    \
+        }                                                                                                      \
+        EGG_MMA_ROWS(1, 0, MB / 2)                                                                             \
+        __syncthreads();                                                                                       \
+        if (MORE) EGG_READ_FRAGS(0, cur_ ^ 1, 0)                                                               \
+        EGG_MMA_ROWS(1, MB / 2, MB)                                                                            \
+    }
 
-    ld.issue(0, kchunks, lds, pb, qb, po, qo, cp, cq, pstep, qstep, zero_page, wave);
-    ld.commit(lds, tid);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS data has landed
+    // prologue: stage 0 into LDS, stage 1 into registers
+    EGG_LOAD(0)
+    EGG_STORE(0)
+    if (KT > 1) EGG_LOAD(1)
     __syncthreads();
     EGG_READ_FRAGS(0, 0, 0)
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        char* nxt = lds + (cur ^ 1) * STAGE_BYTES;
-        if (more) ld.issue(kt + 1, kchunks, nxt, pb, qb, po, qo, cp, cq, pstep, qstep, zero_page, wave);
-        EGG_READ_FRAGS(1, cur, 1)
-        EGG_MMA_ROWS(0, 0, MB)
-        EGG_SCHED_STEP()
-        EGG_READ_FRAGS(0, cur, 2)
-        EGG_MMA_ROWS(1, 0, MB)
-        EGG_SCHED_STEP()
-        EGG_READ_FRAGS(1, cur, 3)
-        EGG_MMA_ROWS(0, 0, MB)
-        EGG_SCHED_STEP()
-        EGG_MMA_ROWS(1, 0, MB / 2)
-        if (more) ld.commit(nxt, tid);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (more) EGG_READ_FRAGS(0, cur ^ 1, 0)
-        EGG_MMA_ROWS(1, MB / 2, MB)
+    int kt = 0;
+    if (!EGG_DBG_SKIP_LOADS) {
+        for (; kt + 2 < KT; ++kt) EGG_ITER(kt, true, true, true)     // steady state
+        if (kt + 1 < KT) { EGG_ITER(kt, true, false, true) ++kt; }   // last stage is in registers
+        EGG_ITER(kt, false, false, false)                            // last stage
+    } else {
+        for (; kt + 1 < KT; ++kt) EGG_ITER(kt, false, false, true)
+        EGG_ITER(kt, false, false, false)
     }
+#undef EGG_ITER
+#undef EGG_SCHED
+#undef EGG_LOAD
+#undef EGG_STORE
 #undef EGG_READ_FRAGS
 #undef EGG_MMA_ROWS
-#undef EGG_SCHED_STEP
 
     // ---- epilogue -------------------------------------------------------------------------------
-    Epi epi(ea, lds);
+    // The LDS stages are dead now; each wave gets a private slice of them as staging space, so that
+    // an epilogue can turn the MFMA layout (a lane owns 4 consecutive rows of one column) into
+    // row-contiguous 16-byte stores.
+    __syncthreads();
+    Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int n = n0 + wn * WTN + j * 32 + (lane & 31);
@@ -288,14 +317,51 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
         for (int i = 0; i < MB; ++i) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int m = m0 + wm * WTM + i * 32 + q * 8 + (lane >> 5) * 4;
+                const int ml = i * 32 + q * 8 + (lane >> 5) * 4;  // row inside the wave tile
                 typename Epi::value_t v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-                epi.store4(m, n, v, nvalid);
+                epi.store4(m0 + wm * WTM + ml, n, v, nvalid, ml);
             }
         }
+        epi.template flush<WTM>(m0 + wm * WTM, n0 + wn * WTN + j * 32, Q.rows);
     }
 }
+
+// Staging helper for epilogues whose output is row-major [n][m] with 2-byte elements: store4 parks a
+// lane's 4 consecutive m-values of column n in the wave's LDS slice as row (n & 31); flush writes
+// the 32 x WTM block out with 16-byte stores, 16 lanes per 256 contiguous bytes.
+struct RowStager2B {
+    char* base;
+    int lane;
+    static constexpr __host__ __device__ int pitch(int wtm) { return wtm * 2 + 16; }
+    static constexpr __host__ __device__ int bytes(int wtm) { return 32 * pitch(wtm); }
+    __device__ __forceinline__ void put(int wtm_pitch, int ml, uint32_t lo, uint32_t hi) const
+    {
+        *(uint2*)(base + (lane & 31) * wtm_pitch + ml * 2) = make_uint2(lo, hi);
+    }
+    // out: element pointer of the row-major destination with `ld` elements per row; rows nb0..nb0+31
+    // (valid below n_rows), columns mw0..mw0+WTM-1 (valid below m_cols, a multiple of 4)
+    template <int WTM>
+    __device__ __forceinline__ void flush(uint16_t* out, int64_t ld, int mw0, int nb0, int n_rows, int m_cols) const
+    {
+        constexpr int P = pitch(WTM), CPR = WTM / 8;  // 16-byte chunks per row
+        __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): the wave's own LDS writes have landed
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 32 * CPR / 64; ++it) {
+            const int c = it * 64 + lane;
+            const int row = c / CPR, cc = c % CPR;
+            const int n = nb0 + row, m = mw0 + cc * 8;
+            if (n < n_rows && m < m_cols) {
+                const u32x4 v = *(const u32x4*)(base + row * P + cc * 16);
+                uint16_t* dst = out + (int64_t)n * ld + m;
+                if (m + 8 <= m_cols) *(u32x4*)dst = v;
+                else *(uint2*)dst = make_uint2(v[0], v[1]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();  // the slice is reused by the next column block
+    }
+};
 
 }  // namespace egg

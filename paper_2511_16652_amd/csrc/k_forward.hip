@@ -26,30 +26,38 @@ struct FwdEpi {
         void* Y;
         const float* t;
         void* A_buf;  // REGEN: optional cache to fill; otherwise the materialised factors to read
+        int wtm_pitch;  // RowStager2B::pitch of the launched wave tile
     };
     const Args a;
+    RowStager2B sty, sta;  // staging slices: bf16 Y block, and (REGEN, bf16) the A_i block kept for the update
     float tc[RANK];
     uint32_t member;
-    int64_t ml;
+    int64_t ml_member;
 
-    __device__ __forceinline__ FwdEpi(const Args& a_, char*) : a(a_) {}
+    // bf16 outputs are staged through LDS; the regenerated bf16 factors too when a cache is kept
+    static constexpr __host__ __device__ int lds_per_wave(int wtm) { return (REGEN && BF16 ? 2 : 1) * RowStager2B::bytes(wtm); }
+
+    __device__ __forceinline__ FwdEpi(const Args& a_, char* slice, int lane)
+        : a(a_), sty{slice, lane}, sta{slice + RowStager2B::bytes((a_.wtm_pitch - 16) / 2), lane}
+    {
+    }
 
     __device__ __forceinline__ void column(int n, bool valid)
     {
         if (!valid || a.c == 0.f) return;
-        ml = n / a.S;
-        member = a.member_begin + (uint32_t)ml;
+        ml_member = n / a.S;
+        member = a.member_begin + (uint32_t)ml_member;
 #pragma unroll
         for (int l = 0; l < RANK; ++l) tc[l] = a.c * a.t[(int64_t)n * RANK + l];
     }
 
-    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid)
+    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid, int ml)
     {
-        if (!valid || m >= a.d_out) return;  // m and d_out are multiples of 4
+        const bool live = valid && m < a.d_out;  // m and d_out are multiples of 4
         float y[4] = {v[0], v[1], v[2], v[3]};
-        if (a.c != 0.f) {
+        if (live && a.c != 0.f) {
             float z[4 * RANK];
-            const int64_t aoff = (ml * a.d_out + m) * RANK;  // element offset of A_i[m][0]
+            const int64_t aoff = (ml_member * a.d_out + m) * RANK;  // element offset of A_i[m][0]
             if constexpr (REGEN) {
                 static_assert(RANK == 1, "in-register regeneration is the rank-1 path");
                 const uint32_t blk0 = (uint32_t)m >> 1;
@@ -60,12 +68,10 @@ struct FwdEpi {
                     normal_pair<!BF16>(w0, w1, z[2 * b], z[2 * b + 1]);
                 }
                 if constexpr (BF16) {
-                    uint2 p;
-                    p.x = pack_bf16x2(z[0], z[1]);
-                    p.y = pack_bf16x2(z[2], z[3]);
-                    z[0] = bf16_lo(p.x); z[1] = bf16_hi(p.x);
-                    z[2] = bf16_lo(p.y); z[3] = bf16_hi(p.y);
-                    if (a.A_buf) *(uint2*)((uint16_t*)a.A_buf + aoff) = p;
+                    const uint32_t p0 = pack_bf16x2(z[0], z[1]), p1 = pack_bf16x2(z[2], z[3]);
+                    z[0] = bf16_lo(p0); z[1] = bf16_hi(p0);
+                    z[2] = bf16_lo(p1); z[3] = bf16_hi(p1);
+                    if (a.A_buf) sta.put(a.wtm_pitch, ml, p0, p1);
                 } else {
                     if (a.A_buf) *(float4*)((float*)a.A_buf + aoff) = make_float4(z[0], z[1], z[2], z[3]);
                 }
@@ -75,8 +81,8 @@ struct FwdEpi {
 #pragma unroll
                     for (int v4 = 0; v4 < RANK; ++v4) {
                         const uint2 p = src[v4];
-                        z[4 * v4] = __uint_as_float(p.x << 16); z[4 * v4 + 1] = __uint_as_float(p.x & 0xFFFF0000u);
-                        z[4 * v4 + 2] = __uint_as_float(p.y << 16); z[4 * v4 + 3] = __uint_as_float(p.y & 0xFFFF0000u);
+                        z[4 * v4] = bf16_lo(p.x); z[4 * v4 + 1] = bf16_hi(p.x);
+                        z[4 * v4 + 2] = bf16_lo(p.y); z[4 * v4 + 3] = bf16_hi(p.y);
                     }
                 } else {
                     const float4* src = (const float4*)((const float*)a.A_buf + aoff);
@@ -99,25 +105,35 @@ struct FwdEpi {
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] = 0.5f * y[e] * (1.0f + erff(y[e] * 0.70710678118654752f));
         }
-        const int64_t off = (int64_t)n * a.d_out + m;
         if (a.y_bf16) {
-            uint2 p;
-            p.x = pack_bf16x2(y[0], y[1]);
-            p.y = pack_bf16x2(y[2], y[3]);
-            *(uint2*)((uint16_t*)a.Y + off) = p;
-        } else {
-            *(float4*)((float*)a.Y + off) = make_float4(y[0], y[1], y[2], y[3]);
+            sty.put(a.wtm_pitch, ml, pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));  // written out by flush
+        } else if (live) {
+            *(float4*)((float*)a.Y + (int64_t)n * a.d_out + m) = make_float4(y[0], y[1], y[2], y[3]);
+        }
+    }
+
+    template <int WTM>
+    __device__ __forceinline__ void flush(int mw0, int nb0, int n_rows)
+    {
+        if (a.y_bf16) sty.template flush<WTM>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
+        if constexpr (REGEN && BF16) {
+            // REGEN means one row per member, so local member index == row index: same addressing as Y
+            if (a.A_buf && a.c != 0.f) sta.template flush<WTM>((uint16_t*)a.A_buf, a.d_out, mw0, nb0, n_rows, a.d_out);
         }
     }
 };
 
-template <class MT, int BM, int BN, int WM, int WN, bool DIRECT, class Epi>
+template <class MT, int BM, int BN, int WM, int WN, class Epi>
 static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
-                              const typename Epi::Args& ea)
+                              typename Epi::Args ea)
 {
-    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, DIRECT, Epi>;
+    ea.wtm_pitch = RowStager2B::pitch(BM / WM);
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, Epi>;
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
-    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    size_t lds = gemm_lds_bytes<BM, BN>();
+    const size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
+    if (epi_lds > lds) lds = epi_lds;
+    if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     const int64_t grid = (int64_t)tiles_m * tiles_n;
@@ -139,26 +155,19 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
     typename Epi::Args ea{ka, (uint32_t)s.member_begin, s.rows_per_member, s.d_out, sigma / sqrtf((float)s.rank),
-                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf};
-    const bool direct = use_direct_loader();
-    if (!operand_offsets_fit(P, 256) || !operand_offsets_fit(Q, 256)) return fail(c, EGG_EUNSUPPORTED, "d_in too large for 32-bit tile offsets");
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
-            if constexpr (REGEN) {  // tuning knob for the large-tile wave layout (default 0: 2 x 4 waves)
+            if constexpr (REGEN) {  // tuning knob for the large-tile configuration
                 static const int variant = [] { const char* e = getenv("EGGROLL_GEMM_VARIANT"); return e ? atoi(e) : 0; }();
-                if (variant == 1) return launch_gemm<MmaBf16, 256, 256, 2, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
-                if (variant == 2) return launch_gemm<MmaBf16, 256, 256, 4, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
-                if (variant == 3) return launch_gemm<MmaBf16, 256, 128, 2, 2, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+                if (variant == 2) return launch_gemm<MmaBf16, 256, 256, 4, 2, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
             }
-            return direct ? launch_gemm<MmaBf16, 256, 256, 2, 4, true, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea)
-                          : launch_gemm<MmaBf16, 256, 256, 2, 4, false, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+            return launch_gemm<MmaBf16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
         }
-        return direct ? launch_gemm<MmaBf16, 128, 128, 2, 2, true, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea)
-                      : launch_gemm<MmaBf16, 128, 128, 2, 2, false, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
+        return launch_gemm<MmaBf16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
     } else {
-        return direct ? launch_gemm<MmaF32, 128, 128, 2, 2, true, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea)
-                      : launch_gemm<MmaF32, 128, 128, 2, 2, false, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);
+        return launch_gemm<MmaF32, 128, 128, 2, 2, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);
     }
 }
 

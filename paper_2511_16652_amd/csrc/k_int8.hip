@@ -47,12 +47,15 @@ struct I8Epi {
     };
     const Args a;
     int dot;
-    __device__ __forceinline__ I8Epi(const Args& a_, char*) : a(a_), dot(0) {}
+    static constexpr __host__ __device__ int lds_per_wave(int) { return 0; }
+    __device__ __forceinline__ I8Epi(const Args& a_, char*, int) : a(a_), dot(0) {}
+    template <int WTM>
+    __device__ __forceinline__ void flush(int, int, int) {}
     __device__ __forceinline__ void column(int n, bool valid)
     {
         if (valid) dot = a.dots[n];
     }
-    __device__ __forceinline__ void store4(int m, int n, const int (&v)[4], bool valid)
+    __device__ __forceinline__ void store4(int m, int n, const int (&v)[4], bool valid, int)
     {
         if (!valid || m >= a.d) return;
         const int64_t off = (int64_t)n * a.d + m;
@@ -74,9 +77,9 @@ template <int BM, int BN, int WM, int WN>
 static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand& Q, int kchunks, const I8Epi::Args& ea)
 {
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
-    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = use_direct_loader() ? gemm_nt_kernel<MmaI8, BM, BN, WM, WN, true, I8Epi> : gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, I8Epi>;
+    auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, I8Epi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_gemm_i8");

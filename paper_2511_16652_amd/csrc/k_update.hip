@@ -98,9 +98,14 @@ struct UpdEpi {
     };
     const Args a;
     float scale;
-    __device__ __forceinline__ UpdEpi(const Args& a_, char*) : a(a_) { scale = a.scale * a.fnorm[0]; }
+    static constexpr __host__ __device__ int lds_per_wave(int) { return 0; }
+    __device__ __forceinline__ UpdEpi(const Args& a_, char*, int) : a(a_) { scale = a.scale * a.fnorm[0]; }
     __device__ __forceinline__ void column(int, bool) {}
-    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid)
+    template <int WTM>
+    __device__ __forceinline__ void flush(int, int, int) {}
+    // G is row-major [d_out][d_in] and a column n is one k: the 32 lanes of a half-wave already write
+    // 32 consecutive floats of one G row, so no staging is needed
+    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid, int)
     {
         if (!valid || m >= a.d_out) return;
 #pragma unroll
@@ -127,9 +132,9 @@ static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operan
                                   const UpdEpi::Args& ea)
 {
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
-    const size_t lds = 2 * (size_t)(BM + BN) * 128;
+    const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = use_direct_loader() ? gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpi> : gemm_nt_kernel<MT, BM, BN, WM, WN, false, UpdEpi>;
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, UpdEpi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, name);
