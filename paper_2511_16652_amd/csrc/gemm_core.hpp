@@ -100,23 +100,38 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 // global_load_dwordx4 into `regs` one whole stage ahead of its use, then ds_write_b128 into the LDS
 // buffer that the last barrier retired.  (The LDS-DMA form of the global load was measured at less
 // than half the L2 streaming rate of plain 16-byte loads on gfx950, so it is not used.)
-// Load `it` of a thread covers chunk-linear index it*NT + tid: row = idx/8, LDS slot = idx%8,
-// global chunk = slot ^ ((row>>1)&7).  Addresses are a wave-uniform 64-bit base (tile origin + K
-// offset, kept in scalar registers) plus a loop-invariant 32-bit per-lane offset.
-template <int ROWS, int NT>
+// Chunk (row, k) of a stage lives at LDS offset row*128 + ((k ^ ((row>>1)&7)) << 4).  Which chunk a
+// load covers is chosen so that a wave's 64 loads are contiguous in global memory:
+//   row-major operands (KPACK = false): idx = it*NT + tid -> row = idx/8, LDS slot = idx%8
+//                                       (8 lanes read the 128 contiguous bytes of a row);
+//   K-packed operands  (KPACK = true) : idx -> row = idx % ROWS, k = idx / ROWS
+//                                       (64 lanes read 64 consecutive rows of one k: 1 KB).
+// Addresses are a wave-uniform 64-bit base (tile origin + K offset, kept in scalar registers) plus
+// a loop-invariant 32-bit per-lane offset.
+template <int ROWS, int NT, bool KPACK>
 struct Loader {
     static constexpr int L = ROWS * 8 / NT;
     uint32_t off[L];
     int chunk[L];  // global chunk index (0..7) of each load, for the K tail
     u32x4 regs[L];
 
+    static __device__ __forceinline__ void coords(int it, int tid, int& row, int& k)
+    {
+        const int idx = it * NT + tid;
+        if constexpr (KPACK) {
+            row = idx % ROWS;
+            k = idx / ROWS;
+        } else {
+            row = idx >> 3;
+            k = (idx & 7) ^ ((row >> 1) & 7);
+        }
+    }
     __device__ __forceinline__ void init(const Operand& o, int row0, int tid)
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
-            const int c = it * NT + tid;
-            const int row = c >> 3;
-            chunk[it] = (c & 7) ^ ((row >> 1) & 7);
+            int row;
+            coords(it, tid, row, chunk[it]);
             const int rl = min(row, o.rows - 1 - row0);  // rows past the end re-read the last valid row
             off[it] = (uint32_t)((int64_t)rl * o.row_stride + (int64_t)chunk[it] * o.kc_stride);
         }
@@ -134,7 +149,11 @@ struct Loader {
     __device__ __forceinline__ void store(char* sdst, int tid) const
     {
 #pragma unroll
-        for (int it = 0; it < L; ++it) *(u32x4*)(sdst + (it * NT + tid) * 16) = regs[it];
+        for (int it = 0; it < L; ++it) {
+            int row, k;
+            coords(it, tid, row, k);
+            *(u32x4*)(sdst + row * 128 + ((k ^ ((row >> 1) & 7)) << 4)) = regs[it];
+        }
     }
 };
 
@@ -162,7 +181,7 @@ constexpr size_t gemm_lds_bytes()
 // kt+1 are written to the free LDS buffer, during k-step 2 the loads of stage kt+2 are issued into
 // them (a whole stage of MFMA work to land); the single barrier of the stage sits in the middle of
 // k-step 3, after which the first fragments of stage kt+1 are read.
-template <class MT, int BM, int BN, int WM, int WN, class Epi>
+template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi>
 __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, const char* zero_page,
                                                                    typename Epi::Args ea)
@@ -188,8 +207,8 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
 
     const char* pb = P.base + (int64_t)m0 * P.row_stride;
     const char* qb = Q.base + (int64_t)n0 * Q.row_stride;
-    Loader<BM, NT> lp;
-    Loader<BN, NT> lq;
+    Loader<BM, NT, KPACK> lp;
+    Loader<BN, NT, KPACK> lq;
     lp.init(P, m0, tid);
     lq.init(Q, n0, tid);
     const int64_t pstep = 8 * P.kc_stride, qstep = 8 * Q.kc_stride;
@@ -215,7 +234,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
 
     const int KT = (kchunks + 7) >> 3;
     u32x4 fa[2][MB], fb[2][NB];
-    constexpr int LOADS = Loader<BM, NT>::L + Loader<BN, NT>::L;
+    constexpr int LOADS = Loader<BM, NT, KPACK>::L + Loader<BN, NT, KPACK>::L;
 
 #define EGG_LOAD(KT_)                                                                                          \
     {                                                                                                          \

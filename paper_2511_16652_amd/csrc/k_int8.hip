@@ -79,7 +79,7 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, I8Epi>;
+    auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, I8Epi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_gemm_i8");

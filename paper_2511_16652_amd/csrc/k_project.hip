@@ -92,6 +92,45 @@ __global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t mem
     }
 }
 
+// One row per member and rank 1: nothing is shared between rows, so B_i never needs to sit in LDS.
+// Each thread multiplies the factor pairs it generates with the matching x pair on the fly; one
+// shuffle reduction per wave and a 4-entry LDS reduction finish the dot product.
+template <bool BF16>
+__global__ __launch_bounds__(256) void project_row_kernel(StreamKey kb, uint32_t member_begin, int d_in,
+                                                          const void* __restrict__ X, float* __restrict__ t,
+                                                          void* __restrict__ B_cache)
+{
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    const int64_t ml = blockIdx.x;
+    const uint32_t member = member_begin + (uint32_t)ml;
+    const int pairs = d_in >> 1;
+    float acc = 0.f;
+    for (int b = tid; b < pairs; b += 256) {
+        uint32_t w0, w1;
+        noise_words(kb, member, (uint32_t)b, w0, w1);
+        float z0, z1;
+        normal_pair<!BF16>(w0, w1, z0, z1);
+        if constexpr (BF16) {
+            const uint32_t pk = pack_bf16x2(z0, z1);
+            const uint32_t xv = ((const uint32_t*)X)[ml * pairs + b];
+            acc = fmaf(bf16_lo(xv), bf16_lo(pk), acc);
+            acc = fmaf(bf16_hi(xv), bf16_hi(pk), acc);
+            if (B_cache) ((uint32_t*)B_cache)[ml * pairs + b] = pk;
+        } else {
+            const float2 xv = ((const float2*)X)[ml * pairs + b];
+            acc = fmaf(xv.x, z0, acc);
+            acc = fmaf(xv.y, z1, acc);
+            if (B_cache) ((float2*)B_cache)[ml * pairs + b] = make_float2(z0, z1);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) t[ml] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 template <bool BF16>
 static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, const void* X, float* t,
                                    void* B_cache)
@@ -101,6 +140,11 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
     const dim3 g((unsigned)s.member_count), b(256);
     if (s.member_count > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many members in one call");
     const uint32_t mb = (uint32_t)s.member_begin;
+    if (s.rank == 1 && s.rows_per_member == 1) {
+        KernelScope ks(c, "project");
+        hipLaunchKernelGGL(project_row_kernel<BF16>, g, b, 0, c->stream, kb, mb, s.d_in, X, t, B_cache);
+        return check_hip(c, hipGetLastError(), "project launch");
+    }
 #define EGG_LAUNCH_PROJECT(R)                                                                                        \
     {                                                                                                                \
         auto kern = project_kernel<BF16, R>;                                                                         \

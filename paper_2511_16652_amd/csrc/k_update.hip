@@ -15,19 +15,19 @@ namespace egg {
 // fnorm[0] = 2^ceil(log2(max|f|)) (1 if all zero), fnorm[1] = 1/fnorm[0].  Folding f/fnorm[0] into the
 // fp16 panel and fnorm[0] into the epilogue scale is exact (a power of two) and keeps f_i*a inside
 // the fp16 range whatever the magnitude of the fitness values.
-__global__ __launch_bounds__(256) void fitness_norm_kernel(const float* __restrict__ f, int64_t n, float* __restrict__ fnorm)
+__global__ __launch_bounds__(1024) void fitness_norm_kernel(const float* __restrict__ f, int64_t n, float* __restrict__ fnorm)
 {
-    __shared__ float red[256];
+    __shared__ float red[16];
     float m = 0.f;
-    for (int64_t i = threadIdx.x; i < n; i += 256) m = fmaxf(m, fabsf(f[i]));
-    red[threadIdx.x] = m;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) m = fmaxf(m, fabsf(f[i]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
-        __syncthreads();
-    }
     if (threadIdx.x == 0) {
-        const float mx = red[0];
+        float mx = red[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
         float p = 1.f;
         if (mx > 0.f && mx < 3.0e38f) {
             int e;
@@ -86,6 +86,63 @@ __global__ __launch_bounds__(256) void pack_kernel(const void* __restrict__ src,
     }
 }
 
+// Rank-1 fast path of the pack pass: a thread turns an EPC x EPC block (EPC members x EPC columns,
+// one 16-byte load per member) into EPC output chunks that are contiguous in the panel, so both the
+// reads and the writes of a wave are fully coalesced.  Needs d % EPC == 0.
+template <bool BF16>
+__global__ __launch_bounds__(256) void pack_r1_kernel(const void* __restrict__ src, const float* __restrict__ fitness,
+                                                      const float* __restrict__ fnorm, int64_t members, int d,
+                                                      int64_t kgroups, void* __restrict__ out)
+{
+    constexpr int EPC = BF16 ? 8 : 4;
+    const int cgroups = d / EPC;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= kgroups * cgroups) return;
+    const int64_t kg = gid / cgroups;
+    const int col0 = (int)(gid - kg * cgroups) * EPC;
+    const float finv = fitness ? fnorm[1] : 1.f;
+    float x[EPC][EPC];  // [member][column]
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+        const int64_t i = kg * EPC + e;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        float fs = 0.f;
+        if (i < members) {
+            v = *(const u32x4*)((const char*)src + (i * d + col0) * (BF16 ? 2 : 4));
+            fs = fitness ? fitness[i] * finv : 1.f;
+        }
+        if constexpr (BF16) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                x[e][2 * w] = bf16_lo(v[w]) * fs;
+                x[e][2 * w + 1] = bf16_hi(v[w]) * fs;
+            }
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) x[e][w] = __uint_as_float(v[w]) * fs;
+        }
+    }
+    u32x4* o = (u32x4*)out + kg * d + col0;
+#pragma unroll
+    for (int cc = 0; cc < EPC; ++cc) {
+        u32x4 r;
+        if constexpr (BF16) {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                h2 p;
+                p[0] = (_Float16)x[2 * w][cc];  // round to nearest even
+                p[1] = (_Float16)x[2 * w + 1][cc];
+                r[w] = __builtin_bit_cast(uint32_t, p);
+            }
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) r[w] = __float_as_uint(x[w][cc]);
+        }
+        o[cc] = r;
+    }
+}
+
 struct UpdEpi {
     typedef float value_t;
     struct Args {
@@ -134,7 +191,7 @@ static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operan
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, UpdEpi>;
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, name);
@@ -171,7 +228,7 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
     float* fnorm = (float*)c->fnorm.p;
     {
         KernelScope ks(c, "fitness_norm");
-        hipLaunchKernelGGL(fitness_norm_kernel, dim3(1), dim3(256), 0, c->stream, fitness, s.member_count, fnorm);
+        hipLaunchKernelGGL(fitness_norm_kernel, dim3(1), dim3(1024), 0, c->stream, fitness, s.member_count, fnorm);
     }
     if ((st = reserve(c, c->pack_a, (size_t)kgroups * s.d_out * 16)) != EGG_OK) return st;
     if ((st = reserve(c, c->pack_b, (size_t)kgroups * s.d_in * 16)) != EGG_OK) return st;
@@ -179,13 +236,21 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
         const int64_t ta = kgroups * s.d_out, tb = kgroups * s.d_in;
         if ((ta + 255) / 256 > 0x7FFFFFFF || (tb + 255) / 256 > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "pack grid too large");
         KernelScope ks(c, "update_pack");
-        if (bf) {
-            hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)((ta + 255) / 256)), dim3(256), 0, c->stream, A_src, fitness, fnorm, s.member_count, s.d_out, s.rank, kgroups, c->pack_a.p);
-            hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)((tb + 255) / 256)), dim3(256), 0, c->stream, B_src, (const float*)nullptr, fnorm, s.member_count, s.d_in, s.rank, kgroups, c->pack_b.p);
-        } else {
-            hipLaunchKernelGGL(pack_kernel<false>, dim3((unsigned)((ta + 255) / 256)), dim3(256), 0, c->stream, A_src, fitness, fnorm, s.member_count, s.d_out, s.rank, kgroups, c->pack_a.p);
-            hipLaunchKernelGGL(pack_kernel<false>, dim3((unsigned)((tb + 255) / 256)), dim3(256), 0, c->stream, B_src, (const float*)nullptr, fnorm, s.member_count, s.d_in, s.rank, kgroups, c->pack_b.p);
-        }
+        auto pack = [&](const void* src, const float* fit, int d, void* dst) {
+            if (s.rank == 1 && d % epc == 0) {
+                const int64_t n = kgroups * (d / epc);
+                const dim3 g((unsigned)((n + 255) / 256)), b(256);
+                if (bf) hipLaunchKernelGGL(pack_r1_kernel<true>, g, b, 0, c->stream, src, fit, fnorm, s.member_count, d, kgroups, dst);
+                else hipLaunchKernelGGL(pack_r1_kernel<false>, g, b, 0, c->stream, src, fit, fnorm, s.member_count, d, kgroups, dst);
+            } else {
+                const int64_t n = kgroups * d;
+                const dim3 g((unsigned)((n + 255) / 256)), b(256);
+                if (bf) hipLaunchKernelGGL(pack_kernel<true>, g, b, 0, c->stream, src, fit, fnorm, s.member_count, d, s.rank, kgroups, dst);
+                else hipLaunchKernelGGL(pack_kernel<false>, g, b, 0, c->stream, src, fit, fnorm, s.member_count, d, s.rank, kgroups, dst);
+            }
+        };
+        pack(A_src, fitness, s.d_out, c->pack_a.p);
+        pack(B_src, nullptr, s.d_in, c->pack_b.p);
         if ((st = check_hip(c, hipGetLastError(), "pack launch")) != EGG_OK) return st;
     }
 
