@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 64 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -90,6 +92,13 @@ def linear_workload(args):
 
     def torch_mm():
         torch.matmul(X, W.t(), out=Y)
+
+    if args.calibrate_copy:  # a copy kernel of known size inside the same profile: reads 64 MiB, writes 64 MiB
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     t_step = timed(step, args.steps, args.warmup)
     t_fwd = timed(forward, args.steps, args.warmup)
