@@ -175,11 +175,15 @@ constexpr size_t gemm_lds_bytes()
 //   __device__ void column(int n, bool valid);                       called once per owned column
 //   __device__ void store4(int m, int n, const T (&v)[4], bool col_valid, int ml);  rows m..m+3 of column n
 //   template <int WTM> __device__ void flush(int mw0, int nb0, int n_rows);   after each 32-column block
+//   template <int MB, int NB> __device__ void prefetch(int mw0, int nw0, int lane, int n_rows);   at kernel start
+//   template <class MT, int MB, int NB> __device__ void extra_mma(acc_t (&acc)[MB][NB], int mw0, int nw0, int lane, int n_rows);
+//   template <int NT, int BM, int BN> __device__ bool tile_begin(char* lds_tail, int m0, int n0, int tid, int n_rows);
+//       called by all threads before the per-wave part; returns whether a barrier is needed
 //
 // Main loop, per K-stage (4 MFMA k-steps): the fragments of k-step s+1 are read from LDS while the
-// MFMAs of k-step s run (two fragment register sets).  During k-step 1 the registers holding stage
-// kt+1 are written to the free LDS buffer, during k-step 2 the loads of stage kt+2 are issued into
-// them (a whole stage of MFMA work to land); the single barrier of the stage sits in the middle of
+// MFMAs of k-step s run (two fragment register sets).  During k-steps 0..2 the registers holding
+// stage kt+1 are written to the free LDS buffer and the loads of stage kt+2 are issued into them
+// (most of a stage of MFMA work to land); the single barrier of the stage sits in the middle of
 // k-step 3, after which the first fragments of stage kt+1 are read.
 template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi>
 __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
@@ -201,9 +205,17 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
 
+#ifdef EGG_DBG_CLOCK
+    if (blockIdx.x == 0 && threadIdx.x == 0) { EGG_DBG_CLOCK[0] = clock64(); EGG_DBG_CLOCK[1] = wall_clock64(); }
+#endif
     int tm, tn;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
+
+    // the epilogue object exists from the start so that it can fetch small per-tile side data (held in
+    // registers across the main loop) instead of paying global-memory latency behind the last MFMA
+    Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
+    epi.template prefetch<MB, NB>(m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
 
     const char* pb = P.base + (int64_t)m0 * P.row_stride;
     const char* qb = Q.base + (int64_t)n0 * Q.row_stride;
@@ -234,7 +246,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
 
     const int KT = (kchunks + 7) >> 3;
     u32x4 fa[2][MB], fb[2][NB];
-    constexpr int LOADS = Loader<BM, NT, KPACK>::L + Loader<BN, NT, KPACK>::L;
+    constexpr int LP_ = Loader<BM, NT, KPACK>::L, LQ_ = Loader<BN, NT, KPACK>::L;
 
 #define EGG_LOAD(KT_)                                                                                          \
     {                                                                                                          \
@@ -260,37 +272,51 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
 // 0x020 VMEM read).  Every k-step pairs one LDS fragment read with each of its first MB+NB MFMAs;
 // k-step 1 additionally spreads the ds_writes of the next stage, k-step 2 the global loads of the
 // stage after it, so that neither forms a block of memory-only instructions before the barrier.
-#define EGG_SCHED(EXTRA_MASK, EXTRA_N)                                                                         \
+#define EGG_SCHED(MASK_A, N_A, MASK_B, N_B)                                                                    \
     {                                                                                                          \
         constexpr int NM_ = MB * NB * MT::MFMA_PER_MMA, NR_ = MB + NB;                                         \
-        constexpr int PER_ = ((EXTRA_N) + NM_ - 1) / NM_;                                                      \
+        constexpr int PA_ = ((N_A) + NM_ - 1) / NM_, PB_ = ((N_B) + NM_ - 1) / NM_;                            \
         _Pragma("unroll") for (int r_ = 0; r_ < NM_; ++r_) {                                                   \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
             if (r_ < NR_) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
-            if ((EXTRA_N) > 0 && r_ * PER_ < (EXTRA_N)) __builtin_amdgcn_sched_group_barrier(EXTRA_MASK, PER_, 0); \
+            if ((N_A) > 0 && r_ * PA_ < (N_A)) __builtin_amdgcn_sched_group_barrier(MASK_A, PA_, 0);           \
+            if ((N_B) > 0 && r_ * PB_ < (N_B)) __builtin_amdgcn_sched_group_barrier(MASK_B, PB_, 0);           \
         }                                                                                                      \
     }
+// Stage kt+1 travels registers -> LDS and stage kt+2 global -> registers in two halves (P rows, then
+// Q rows) spread over k-steps 0..2, so that no k-step carries the whole 64 KB LDS write burst:
+//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+2), ds_write Q(kt+1)
+//   k-step 2: load Q(kt+2)                k-step 3: barrier in the middle, then first fragments of kt+1
 #define EGG_ITER(KT_, DO_STORE, DO_LOAD, MORE)                                                                 \
     {                                                                                                          \
         const int cur_ = (KT_)&1;                                                                              \
+        char* nxt_ = lds + (cur_ ^ 1) * STAGE_BYTES;                                                           \
         EGG_READ_FRAGS(1, cur_, 1)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
-        EGG_SCHED(0, 0)                                                                                        \
+        if (DO_STORE) {                                                                                        \
+            lp.store(nxt_, tid);                                                                               \
+            EGG_SCHED(0x200, LP_, 0, 0)                                                                        \
+        } else {                                                                                               \
+            EGG_SCHED(0, 0, 0, 0)                                                                              \
+        }                                                                                                      \
         EGG_READ_FRAGS(0, cur_, 2)                                                                             \
         EGG_MMA_ROWS(1, 0, MB)                                                                                 \
-        if (DO_STORE) {                                                                                        \
-            EGG_STORE(cur_ ^ 1) /* stage kt+1: registers -> the buffer retired by the last barrier */          \
-            EGG_SCHED(0x200, LOADS)                                                                            \
+        if (DO_LOAD) lp.load(pb + (int64_t)((KT_) + 2) * pstep, ((KT_) + 2) * 8, kchunks, zero_page);          \
+        if (DO_STORE) lq.store(nxt_ + BM * PITCH, tid);                                                        \
+        if (DO_LOAD) {                                                                                         \
+            EGG_SCHED(0x020, LP_, 0x200, LQ_)                                                                  \
+        } else if (DO_STORE) {                                                                                 \
+            EGG_SCHED(0x200, LQ_, 0, 0)                                                                        \
         } else {                                                                                               \
-            EGG_SCHED(0, 0)                                                                                    \
+            EGG_SCHED(0, 0, 0, 0)                                                                              \
         }                                                                                                      \
         EGG_READ_FRAGS(1, cur_, 3)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
         if (DO_LOAD) {                                                                                         \
-            EGG_LOAD((KT_) + 2) /* stage kt+2 -> registers, a whole stage of MFMA work to land */              \
-            EGG_SCHED(0x020, LOADS)                                                                            \
+            lq.load(qb + (int64_t)((KT_) + 2) * qstep, ((KT_) + 2) * 8, kchunks, zero_page);                   \
+            EGG_SCHED(0x020, LQ_, 0, 0)                                                                        \
         } else {                                                                                               \
-            EGG_SCHED(0, 0)                                                                                    \
+            EGG_SCHED(0, 0, 0, 0)                                                                              \
         }                                                                                                      \
         EGG_MMA_ROWS(1, 0, MB / 2)                                                                             \
         __syncthreads();                                                                                       \
@@ -326,7 +352,10 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     // an epilogue can turn the MFMA layout (a lane owns 4 consecutive rows of one column) into
     // row-contiguous 16-byte stores.
     __syncthreads();
-    Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
+    // an epilogue may fold per-column-block rank-r terms into the accumulators with a few more MFMAs
+    epi.template extra_mma<MT, MB, NB>(acc, m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
+    // workgroup-level hook: an epilogue may pull per-tile side data into the LDS behind the wave slices
+    if (epi.template tile_begin<NT, BM, BN>(lds + WM * WN * Epi::lds_per_wave(WTM), m0, n0, tid, Q.rows)) __syncthreads();
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int n = n0 + wn * WTN + j * 32 + (lane & 31);

@@ -27,12 +27,136 @@ struct FwdEpi {
         const float* t;
         void* A_buf;  // REGEN: optional cache to fill; otherwise the materialised factors to read
         int wtm_pitch;  // RowStager2B::pitch of the launched wave tile
+        int stage_a;    // !REGEN: the tile's slice of A fits the LDS tail and is staged there
+        int mma_corr;   // !REGEN, bf16, S % 32 == 0: the correction is folded in by one extra MFMA per block
     };
+    static constexpr int A_STAGE_BYTES = 48 * 1024;
+    static constexpr bool REGEN_MODE = REGEN;
+    static constexpr bool IS_BF16 = BF16;
+    static constexpr int RANK_ELEMS_BYTES = RANK * (BF16 ? 2 : 4);
     const Args a;
     RowStager2B sty, sta;  // staging slices: bf16 Y block, and (REGEN, bf16) the A_i block kept for the update
     float tc[RANK];
     uint32_t member;
     int64_t ml_member;
+    const char* a_tile = nullptr;  // staged A slice: [member - first_member][m - m0][RANK]
+    int64_t first_member = 0;
+    int tile_m0 = 0, tile_rows = 0;
+
+    // When every 32-column block belongs to one member (S a multiple of 32), the rank-r correction of
+    // a 32x32 block is itself a small GEMM, Y[m][n] += sum_l A_i[m][l] * (c t[n][l]), and one more
+    // 32x32x16 MFMA per block adds it to the accumulators: its 16 K-slots hold A_i[m][0..r) twice and
+    // the fp32 value c*t split into two bf16 halves (hi, then lo = the rounding remainder), so the
+    // products stay accurate to about 2^-16.  The epilogue that follows is then the plain store.
+    static constexpr int AW = RANK >= 2 ? RANK / 2 : 1;  // 32-bit words of one A_i[m][0..RANK) row in bf16
+    static constexpr bool PREFETCH = RANK <= 4;  // rank 8 would not fit the register budget: it loads late
+    uint32_t pf_a[PREFETCH ? 4 : 1][2][AW];   // prefetched A rows of the lane, per (row block, column block)
+    float pf_t[2][RANK];                      // prefetched t of the lane's columns
+
+    template <int NB>
+    __device__ __forceinline__ void fetch_t(int nw0, int lane, int n_rows)
+    {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int nc = min(nw0 + j * 32 + (lane & 31), n_rows - 1);
+#pragma unroll
+            for (int l = 0; l < RANK; ++l) pf_t[j][l] = a.t[(int64_t)nc * RANK + l];
+        }
+    }
+    __device__ __forceinline__ void fetch_a(uint32_t (&dst)[AW], int m, int nblock0, int n_rows) const
+    {
+        const int64_t mlb = (int64_t)(min(nblock0, n_rows - 1) / a.S);  // the block's member (uniform)
+        const uint16_t* src = (const uint16_t*)a.A_buf + (mlb * a.d_out + min(m, a.d_out - 1)) * RANK;
+        if constexpr (RANK == 1) dst[0] = src[0];
+        else if constexpr (RANK == 2) dst[0] = *(const uint32_t*)src;
+        else if constexpr (RANK == 4) { const uint2 v = *(const uint2*)src; dst[0] = v.x; dst[1] = v.y; }
+        else { const u32x4 v = *(const u32x4*)src; dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3]; }
+    }
+
+    // issued at kernel start: the operands of extra_mma, so that their latency hides under the main loop
+    template <int MB, int NB>
+    __device__ __forceinline__ void prefetch(int mw0, int nw0, int lane, int n_rows)
+    {
+        if constexpr (!REGEN && BF16 && PREFETCH) {
+            static_assert(MB <= 4 && NB <= 2, "prefetch storage");
+            if (!a.mma_corr) return;
+            fetch_t<NB>(nw0, lane, n_rows);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int i = 0; i < MB; ++i) fetch_a(pf_a[i][j], mw0 + i * 32 + (lane & 31), nw0 + j * 32, n_rows);
+        }
+    }
+
+    template <class MT, int MB, int NB>
+    __device__ __forceinline__ void extra_mma(typename MT::acc_t (&acc)[MB][NB], int mw0, int nw0, int lane, int n_rows)
+    {
+        if constexpr (!REGEN && BF16 && RANK <= 8) {
+            if (!a.mma_corr) return;
+            if constexpr (!PREFETCH) fetch_t<NB>(nw0, lane, n_rows);
+            const int half = lane >> 5;  // K-slots 0..7 (hi part of c*t) or 8..15 (lo part)
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                uint32_t tb[4] = {0u, 0u, 0u, 0u};
+                float ct[RANK];
+#pragma unroll
+                for (int l = 0; l < RANK; ++l) {
+                    const float v = a.c * pf_t[j][l];
+                    const float hi = round_bf16(v);
+                    ct[l] = half ? v - hi : hi;
+                }
+#pragma unroll
+                for (int l = 0; l < RANK; l += 2) tb[l >> 1] = pack_bf16x2(ct[l], l + 1 < RANK ? ct[l + 1] : 0.f);
+                const u32x4 bfrag = {tb[0], tb[1], tb[2], tb[3]};
+#pragma unroll
+                for (int i = 0; i < MB; ++i) {
+                    u32x4 afrag = {0u, 0u, 0u, 0u};
+                    if constexpr (PREFETCH) {
+#pragma unroll
+                        for (int w = 0; w < AW; ++w) afrag[w] = pf_a[i][j][w];
+                    } else {
+                        uint32_t tmp[AW];
+                        fetch_a(tmp, mw0 + i * 32 + (lane & 31), nw0 + j * 32, n_rows);
+#pragma unroll
+                        for (int w = 0; w < AW; ++w) afrag[w] = tmp[w];
+                    }
+                    MT::mma(afrag, bfrag, acc[i][j]);  // rows m >= d_out hold a clamped copy and are never stored
+                }
+            }
+        }
+    }
+
+    // Materialised factors: with S rows per member a 256-column tile touches only BN/S + 1 members,
+    // so their A_i[m0 .. m0+BM) slices are fetched once, cooperatively and coalesced, instead of by
+    // 32 dependent global loads per lane behind live accumulators.
+    template <int NT, int BM, int BN>
+    __device__ __forceinline__ bool tile_begin(char* lds_tail, int m0, int n0, int tid, int n_rows)
+    {
+        if constexpr (REGEN) {
+            return false;
+        } else {
+            if (!a.stage_a || a.c == 0.f || a.mma_corr) return false;
+            constexpr int ESZ = BF16 ? 2 : 4;
+            first_member = n0 / a.S;
+            const int64_t last_member = (int64_t)(min(n0 + BN, n_rows) - 1) / a.S;
+            const int nm = (int)(last_member - first_member) + 1;
+            tile_m0 = m0;
+            tile_rows = min(BM, a.d_out - m0);               // valid rows of this tile
+            const int row_chunks = tile_rows * RANK * ESZ / 16;  // 16-byte chunks per member slice (d_out % 4 == 0)
+            constexpr int SLICE_CHUNKS = BM * RANK * ESZ / 16;
+            for (int idx = tid; idx < nm * row_chunks; idx += NT) {
+                const int ml = idx / row_chunks, ch = idx - ml * row_chunks;
+                const u32x4 v = *(const u32x4*)((const char*)a.A_buf + ((first_member + ml) * a.d_out + m0) * (int64_t)(RANK * ESZ) + (int64_t)ch * 16);
+                *(u32x4*)(lds_tail + ((int64_t)ml * SLICE_CHUNKS + ch) * 16) = v;
+            }
+            a_tile = lds_tail;
+            bm_rows = BM;
+            return true;
+        }
+    }
+
+    int bm_rows = 0;  // BM of the launched tile (rows per member slice in the staged A)
+    __device__ __forceinline__ int tile_stride() const { return bm_rows; }
 
     // bf16 outputs are staged through LDS; the regenerated bf16 factors too when a cache is kept
     static constexpr __host__ __device__ int lds_per_wave(int wtm) { return (REGEN && BF16 ? 2 : 1) * RowStager2B::bytes(wtm); }
@@ -44,7 +168,7 @@ struct FwdEpi {
 
     __device__ __forceinline__ void column(int n, bool valid)
     {
-        if (!valid || a.c == 0.f) return;
+        if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
         member = a.member_begin + (uint32_t)ml_member;
 #pragma unroll
@@ -55,7 +179,7 @@ struct FwdEpi {
     {
         const bool live = valid && m < a.d_out;  // m and d_out are multiples of 4
         float y[4] = {v[0], v[1], v[2], v[3]};
-        if (live && a.c != 0.f) {
+        if (live && a.c != 0.f && !(!REGEN && a.mma_corr)) {
             float z[4 * RANK];
             const int64_t aoff = (ml_member * a.d_out + m) * RANK;  // element offset of A_i[m][0]
             if constexpr (REGEN) {
@@ -76,8 +200,10 @@ struct FwdEpi {
                     if (a.A_buf) *(float4*)((float*)a.A_buf + aoff) = make_float4(z[0], z[1], z[2], z[3]);
                 }
             } else {
+                const char* abase = (const char*)a.A_buf + aoff * (BF16 ? 2 : 4);
+                if (a_tile) abase = a_tile + (((ml_member - first_member) * (int64_t)tile_stride() + (m - tile_m0)) * RANK) * (BF16 ? 2 : 4);
                 if constexpr (BF16) {
-                    const uint2* src = (const uint2*)((const uint16_t*)a.A_buf + aoff);
+                    const uint2* src = (const uint2*)abase;
 #pragma unroll
                     for (int v4 = 0; v4 < RANK; ++v4) {
                         const uint2 p = src[v4];
@@ -85,7 +211,7 @@ struct FwdEpi {
                         z[4 * v4 + 2] = bf16_lo(p.y); z[4 * v4 + 3] = bf16_hi(p.y);
                     }
                 } else {
-                    const float4* src = (const float4*)((const float*)a.A_buf + aoff);
+                    const float4* src = (const float4*)abase;
 #pragma unroll
                     for (int v4 = 0; v4 < RANK; ++v4) {
                         const float4 p = src[v4];
@@ -131,7 +257,17 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, false, Epi>;
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     size_t lds = gemm_lds_bytes<BM, BN>();
-    const size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
+    size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
+    ea.stage_a = 0;
+    ea.mma_corr = (!Epi::REGEN_MODE && Epi::IS_BF16 && ea.c != 0.f && ea.S % 32 == 0) ? 1 : 0;
+    if (!Epi::REGEN_MODE && ea.c != 0.f && !ea.mma_corr) {
+        const size_t need = (size_t)(BN / ea.S + 2) * BM * Epi::RANK_ELEMS_BYTES;
+        // 16-byte copies: every member slice must start and end on a 16-byte boundary
+        if (need <= (size_t)Epi::A_STAGE_BYTES && ((size_t)ea.d_out * Epi::RANK_ELEMS_BYTES) % 16 == 0) {
+            ea.stage_a = 1;
+            epi_lds += need;
+        }
+    }
     if (epi_lds > lds) lds = epi_lds;
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
@@ -155,14 +291,10 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
     typename Epi::Args ea{ka, (uint32_t)s.member_begin, s.rows_per_member, s.d_out, sigma / sqrtf((float)s.rank),
-                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0};
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
-            if constexpr (REGEN) {  // tuning knob for the large-tile configuration
-                static const int variant = [] { const char* e = getenv("EGGROLL_GEMM_VARIANT"); return e ? atoi(e) : 0; }();
-                if (variant == 2) return launch_gemm<MmaBf16, 256, 256, 4, 2, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
-            }
             return launch_gemm<MmaBf16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
         }
         return launch_gemm<MmaBf16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);

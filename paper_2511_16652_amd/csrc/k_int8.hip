@@ -51,6 +51,12 @@ struct I8Epi {
     __device__ __forceinline__ I8Epi(const Args& a_, char*, int) : a(a_), dot(0) {}
     template <int WTM>
     __device__ __forceinline__ void flush(int, int, int) {}
+    template <int NT, int BM, int BN>
+    __device__ __forceinline__ bool tile_begin(char*, int, int, int, int) { return false; }
+    template <class MT, int MB, int NB>
+    __device__ __forceinline__ void extra_mma(typename MT::acc_t (&)[MB][NB], int, int, int, int) {}
+    template <int MB, int NB>
+    __device__ __forceinline__ void prefetch(int, int, int, int) {}
     __device__ __forceinline__ void column(int n, bool valid)
     {
         if (valid) dot = a.dots[n];

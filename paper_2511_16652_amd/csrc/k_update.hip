@@ -160,6 +160,12 @@ struct UpdEpi {
     __device__ __forceinline__ void column(int, bool) {}
     template <int WTM>
     __device__ __forceinline__ void flush(int, int, int) {}
+    template <int NT, int BM, int BN>
+    __device__ __forceinline__ bool tile_begin(char*, int, int, int, int) { return false; }
+    template <class MT, int MB, int NB>
+    __device__ __forceinline__ void extra_mma(typename MT::acc_t (&)[MB][NB], int, int, int, int) {}
+    template <int MB, int NB>
+    __device__ __forceinline__ void prefetch(int, int, int, int) {}
     // G is row-major [d_out][d_in] and a column n is one k: the 32 lanes of a half-wave already write
     // 32 consecutive floats of one G row, so no staging is needed
     __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid, int)

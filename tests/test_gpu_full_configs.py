@@ -109,3 +109,52 @@ def test_config3_full_size_integer_recurrence(ctx):
     torch.cuda.synchronize()
     want = oracle.forward_i8(0, 0, 0, 0, wl.N, wl.d, wl.bound, wl.corr_shift, wl.out_shift, 2, wl.W, wl.H0)
     assert (out.cpu().numpy() == want).all()
+
+
+@pytest.mark.parametrize("name,d_out,d_in,N,S,r,act", [
+    ("mlp_up_gelu", 8192, 2048, 1024, 64, 4, eb.EGG_ACT_GELU),    # config 4, W1 with GELU, real layer shape
+    ("mlp_down", 2048, 8192, 512, 64, 4, eb.EGG_ACT_NONE),        # config 4, W2
+    ("decoder_ffn_up", 8192, 2048, 256, 256, 1, eb.EGG_ACT_GELU),  # config 5 ffn-up: 256 tokens per member
+    ("decoder_attn_proj", 2048, 2048, 512, 256, 1, eb.EGG_ACT_NONE),
+])
+def test_layer_shapes_of_configs_4_and_5(ctx, name, d_out, d_in, N, S, r, act):
+    """Real layer shapes of the MLP-stack and decoder configurations at a reduced population: forward
+    rows of sampled members against the explicit W_i, and sampled entries of G over all members."""
+    import torch
+    wl = inputs.make_linear(name, "bf16", d_out, d_in, N, S, r, 1e-3, 4000 + d_out % 97 + S)
+    W, X = to_device(wl.W, "bf16"), to_device(wl.X, "bf16")
+    R = N * S
+    Y = torch.empty((R, d_out), dtype=torch.bfloat16, device="cuda")
+    A = torch.empty((N, d_out, r), dtype=torch.bfloat16, device="cuda")
+    B = torch.empty((N, d_in, r), dtype=torch.bfloat16, device="cuda")
+    key, shape = eb.make_key(0, 0, 3), eb.make_shape(0, N, S, d_out, d_in, r)
+    # sigma 30x the configured one, so that the correction is well above the bf16 rounding of y
+    sigma = 0.03
+    ctx.eggroll_perturbed_forward(key, shape, sigma, act, W, X, Y, A, B)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    members = np.sort(rng.choice(N, 6, replace=False))
+    rows = np.concatenate([np.arange(m * S, (m + 1) * S) for m in members])
+    y = to_numpy(Y[torch.from_numpy(rows).cuda()])
+    ref = np.concatenate([oracle.forward(0, 0, 3, int(m), 1, S, d_out, d_in, r, oracle.NOISE_BF16, sigma,
+                                         oracle.ACT_GELU if act else oracle.ACT_NONE, wl.W, wl.X[m * S:(m + 1) * S])
+                          for m in members])
+    assert_close(y, ref, 1e-2, name + " sampled members")
+    # the same rows without perturbation differ visibly: the correction is really applied per member
+    base = wl.X[rows].astype(np.float64) @ wl.W.astype(np.float64).T
+    if not act:
+        assert np.abs(ref - base).max() > 20 * 1e-2 * np.sqrt(np.mean(base ** 2)) * 0.05
+
+    fit = inputs.centered(wl.raw_fitness).astype(np.float32)
+    scale = eb.eggroll_default_scale(N, sigma, r)
+    G = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    ctx.eggroll_update(key, shape, eb.EGG_BF16, torch.from_numpy(fit).cuda(), scale, 0, G, None, 0.0, A, B)
+    torch.cuda.synchronize()
+    g = G.cpu().numpy().astype(np.float64)
+    rms = np.sqrt(np.mean(g ** 2))
+    js, ks = rng.integers(0, d_out, 96), rng.integers(0, d_in, 96)
+    want = np.array([oracle.update_entry(0, 0, 3, 0, N, r, oracle.NOISE_BF16, fit.astype(np.float64), scale, int(j), int(k))
+                     for j, k in zip(js, ks)])
+    err = np.abs(g[js, ks] - want)
+    assert (err <= 1e-2 * (np.abs(want) + rms)).all()
+    assert (err > 2e-3 * (np.abs(want) + rms)).mean() < 0.03
