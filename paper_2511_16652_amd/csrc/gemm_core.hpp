@@ -113,7 +113,6 @@ struct Loader {
     static constexpr int L = ROWS * 8 / NT;
     uint32_t off[L];
     int chunk[L];  // global chunk index (0..7) of each load, for the K tail
-    u32x4 regs[L];
 
     static __device__ __forceinline__ void coords(int it, int tid, int& row, int& k)
     {
@@ -137,7 +136,8 @@ struct Loader {
         }
     }
     // chunks past the end of K (only possible in the last stage) read the zero page instead
-    __device__ __forceinline__ void load(const char* base, int kfirst, int kchunks, const char* zero_page)
+    __device__ __forceinline__ void load(u32x4 (&regs)[L], const char* base, int kfirst, int kchunks,
+                                         const char* zero_page) const
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
@@ -146,7 +146,7 @@ struct Loader {
             regs[it] = *(const u32x4*)g;
         }
     }
-    __device__ __forceinline__ void store(char* sdst, int tid) const
+    __device__ __forceinline__ void store(const u32x4 (&regs)[L], char* sdst, int tid) const
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
@@ -185,7 +185,7 @@ constexpr size_t gemm_lds_bytes()
 // stage kt+1 are written to the free LDS buffer and the loads of stage kt+2 are issued into them
 // (most of a stage of MFMA work to land); the single barrier of the stage sits in the middle of
 // k-step 3, after which the first fragments of stage kt+1 are read.
-template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi>
+template <class MT, int BM, int BN, int WM, int WN, bool KPACK, int PF, class Epi>
 __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, const char* zero_page,
                                                                    typename Epi::Args ea)
@@ -197,6 +197,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     constexpr int STAGE_BYTES = (BM + BN) * PITCH;
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "stage rows must divide over the threads");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && MB % 2 == 0, "wave tiles are made of 32x32 blocks");
+    static_assert(PF == 1 || PF == 2, "register prefetch depth");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -205,9 +206,6 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
 
-#ifdef EGG_DBG_CLOCK
-    if (blockIdx.x == 0 && threadIdx.x == 0) { EGG_DBG_CLOCK[0] = clock64(); EGG_DBG_CLOCK[1] = wall_clock64(); }
-#endif
     int tm, tn;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
@@ -248,16 +246,6 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     u32x4 fa[2][MB], fb[2][NB];
     constexpr int LP_ = Loader<BM, NT, KPACK>::L, LQ_ = Loader<BN, NT, KPACK>::L;
 
-#define EGG_LOAD(KT_)                                                                                          \
-    {                                                                                                          \
-        lp.load(pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                                       \
-        lq.load(qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                                       \
-    }
-#define EGG_STORE(STAGE_)                                                                                      \
-    {                                                                                                          \
-        lp.store(lds + (STAGE_)*STAGE_BYTES, tid);                                                             \
-        lq.store(lds + (STAGE_)*STAGE_BYTES + BM * PITCH, tid);                                                \
-    }
 #define EGG_READ_FRAGS(BUF, STAGE, KS_)                                                                        \
     {                                                                                                          \
         const char* sa_ = lds + (STAGE)*STAGE_BYTES + a_base + foff[KS_];                                      \
@@ -283,26 +271,28 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
             if ((N_B) > 0 && r_ * PB_ < (N_B)) __builtin_amdgcn_sched_group_barrier(MASK_B, PB_, 0);           \
         }                                                                                                      \
     }
-// Stage kt+1 travels registers -> LDS and stage kt+2 global -> registers in two halves (P rows, then
-// Q rows) spread over k-steps 0..2, so that no k-step carries the whole 64 KB LDS write burst:
-//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+2), ds_write Q(kt+1)
-//   k-step 2: load Q(kt+2)                k-step 3: barrier in the middle, then first fragments of kt+1
-#define EGG_ITER(KT_, DO_STORE, DO_LOAD, MORE)                                                                 \
+// Stage kt+1 travels registers -> LDS and stage kt+1+PF global -> registers in two halves (P rows,
+// then Q rows) spread over k-steps 0..2, so that no k-step carries the whole 64 KB LDS write burst:
+//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+1+PF), ds_write Q(kt+1)
+//   k-step 2: load Q(kt+1+PF)             k-step 3: barrier in the middle, then first fragments of kt+1
+// RS is the register set that holds stage kt+1 (and receives stage kt+1+PF).
+#define EGG_ITER(KT_, RS, DO_STORE, DO_LOAD, MORE)                                                             \
     {                                                                                                          \
         const int cur_ = (KT_)&1;                                                                              \
         char* nxt_ = lds + (cur_ ^ 1) * STAGE_BYTES;                                                           \
+        const int lk_ = (KT_) + 1 + PF;                                                                        \
         EGG_READ_FRAGS(1, cur_, 1)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
         if (DO_STORE) {                                                                                        \
-            lp.store(nxt_, tid);                                                                               \
+            lp.store(rp[RS], nxt_, tid);                                                                       \
             EGG_SCHED(0x200, LP_, 0, 0)                                                                        \
         } else {                                                                                               \
             EGG_SCHED(0, 0, 0, 0)                                                                              \
         }                                                                                                      \
         EGG_READ_FRAGS(0, cur_, 2)                                                                             \
         EGG_MMA_ROWS(1, 0, MB)                                                                                 \
-        if (DO_LOAD) lp.load(pb + (int64_t)((KT_) + 2) * pstep, ((KT_) + 2) * 8, kchunks, zero_page);          \
-        if (DO_STORE) lq.store(nxt_ + BM * PITCH, tid);                                                        \
+        if (DO_LOAD) lp.load(rp[RS], pb + (int64_t)lk_ * pstep, lk_ * 8, kchunks, zero_page);                  \
+        if (DO_STORE) lq.store(rq[RS], nxt_ + BM * PITCH, tid);                                                \
         if (DO_LOAD) {                                                                                         \
             EGG_SCHED(0x020, LP_, 0x200, LQ_)                                                                  \
         } else if (DO_STORE) {                                                                                 \
@@ -313,7 +303,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
         EGG_READ_FRAGS(1, cur_, 3)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
         if (DO_LOAD) {                                                                                         \
-            lq.load(qb + (int64_t)((KT_) + 2) * qstep, ((KT_) + 2) * 8, kchunks, zero_page);                   \
+            lq.load(rq[RS], qb + (int64_t)lk_ * qstep, lk_ * 8, kchunks, zero_page);                           \
             EGG_SCHED(0x020, LQ_, 0, 0)                                                                        \
         } else {                                                                                               \
             EGG_SCHED(0, 0, 0, 0)                                                                              \
@@ -323,27 +313,56 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
         if (MORE) EGG_READ_FRAGS(0, cur_ ^ 1, 0)                                                               \
         EGG_MMA_ROWS(1, MB / 2, MB)                                                                            \
     }
-
-    // prologue: stage 0 into LDS, stage 1 into registers
-    EGG_LOAD(0)
-    EGG_STORE(0)
-    if (KT > 1) EGG_LOAD(1)
-    __syncthreads();
-    EGG_READ_FRAGS(0, 0, 0)
-
-    int kt = 0;
-    if (!EGG_DBG_SKIP_LOADS) {
-        for (; kt + 2 < KT; ++kt) EGG_ITER(kt, true, true, true)     // steady state
-        if (kt + 1 < KT) { EGG_ITER(kt, true, false, true) ++kt; }   // last stage is in registers
-        EGG_ITER(kt, false, false, false)                            // last stage
-    } else {
-        for (; kt + 1 < KT; ++kt) EGG_ITER(kt, false, false, true)
-        EGG_ITER(kt, false, false, false)
+#define EGG_LOAD_STAGE(RS, KT_)                                                                                \
+    {                                                                                                          \
+        lp.load(rp[RS], pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                               \
+        lq.load(rq[RS], qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                               \
     }
+
+    // prologue: stage 0 into LDS, stages 1..PF into the register sets (stage s+1 lives in set s % PF ...)
+    u32x4 rp[PF][LP_], rq[PF][LQ_];
+    EGG_LOAD_STAGE(0, 0)
+    lp.store(rp[0], lds, tid);
+    lq.store(rq[0], lds + BM * PITCH, tid);
+    int kt = 0;
+    if constexpr (PF == 1) {
+        if (KT > 1) EGG_LOAD_STAGE(0, 1)
+        __syncthreads();
+        EGG_READ_FRAGS(0, 0, 0)
+        if (!EGG_DBG_SKIP_LOADS) {
+            for (; kt + 2 < KT; ++kt) EGG_ITER(kt, 0, true, true, true)      // steady state
+            if (kt + 1 < KT) { EGG_ITER(kt, 0, true, false, true) ++kt; }    // last stage is in registers
+            EGG_ITER(kt, 0, false, false, false)                             // last stage
+        } else {
+            for (; kt + 1 < KT; ++kt) EGG_ITER(kt, 0, false, false, true)
+            EGG_ITER(kt, 0, false, false, false)
+        }
+    } else {
+        // two register sets: stage kt+1 sits in set (kt+1)&1 while stage kt+2 is still landing in the other
+        if (KT > 1) EGG_LOAD_STAGE(1, 1)
+        if (KT > 2) EGG_LOAD_STAGE(0, 2)
+        __syncthreads();
+        EGG_READ_FRAGS(0, 0, 0)
+        for (; kt + 4 < KT; kt += 2) {  // steady state, unrolled by two so that the set index is static
+            EGG_ITER(kt, 1, true, true, true)
+            EGG_ITER(kt + 1, 0, true, true, true)
+        }
+        for (; kt < KT; ++kt) {  // the last stages: same steps, guarded
+            const bool st_ = kt + 1 < KT, ld_ = kt + 3 < KT;
+            if (kt & 1) {
+                if (st_ && ld_) EGG_ITER(kt, 0, true, true, true)
+                else if (st_) EGG_ITER(kt, 0, true, false, true)
+                else EGG_ITER(kt, 0, false, false, false)
+            } else {
+                if (st_ && ld_) EGG_ITER(kt, 1, true, true, true)
+                else if (st_) EGG_ITER(kt, 1, true, false, true)
+                else EGG_ITER(kt, 1, false, false, false)
+            }
+        }
+    }
+#undef EGG_LOAD_STAGE
 #undef EGG_ITER
 #undef EGG_SCHED
-#undef EGG_LOAD
-#undef EGG_STORE
 #undef EGG_READ_FRAGS
 #undef EGG_MMA_ROWS
 
