@@ -8,6 +8,8 @@
 // A workgroup owns a BM x BN tile of C; 64-wide waves own 32x32 MFMA blocks of it.  K advances in
 // stages of 8 chunks (128 bytes per row) double-buffered in LDS; the global loads of stage kt+2 are
 // in flight in registers while stage kt is multiplied and stage kt+1 sits in the other LDS buffer.
+// (Deeper register prefetch was measured on the short-K int8 problem: no gain, that loop is bound by
+// L2-to-CU bandwidth, not by latency.)
 // Rows of an LDS stage are 128 bytes with the chunk slot XOR-swizzled by (row>>1)&7, which makes
 // the 16-byte fragment reads of any 16 neighbouring rows hit distinct banks (measured: zero bank
 // conflicts).
@@ -16,14 +18,6 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-// diagnosis switches for standalone experiments (never set in the library build)
-#ifndef EGG_DBG_SKIP_LOADS
-#define EGG_DBG_SKIP_LOADS 0
-#endif
-#ifndef EGG_DBG_SKIP_MMA
-#define EGG_DBG_SKIP_MMA 0
-#endif
 
 namespace egg {
 
@@ -175,7 +169,7 @@ constexpr size_t gemm_lds_bytes()
 //   __device__ void column(int n, bool valid);                       called once per owned column
 //   __device__ void store4(int m, int n, const T (&v)[4], bool col_valid, int ml);  rows m..m+3 of column n
 //   template <int WTM> __device__ void flush(int mw0, int nb0, int n_rows);   after each 32-column block
-//   template <int MB, int NB> __device__ void prefetch(int mw0, int nw0, int lane, int n_rows);   at kernel start
+//   template <int MB, int NB> __device__ void prefetch(int mw0, int nw0, int lane, int n_rows);   late in the main loop
 //   template <class MT, int MB, int NB> __device__ void extra_mma(acc_t (&acc)[MB][NB], int mw0, int nw0, int lane, int n_rows);
 //   template <int NT, int BM, int BN> __device__ bool tile_begin(char* lds_tail, int m0, int n0, int tid, int n_rows);
 //       called by all threads before the per-wave part; returns whether a barrier is needed
@@ -185,8 +179,8 @@ constexpr size_t gemm_lds_bytes()
 // stage kt+1 are written to the free LDS buffer and the loads of stage kt+2 are issued into them
 // (most of a stage of MFMA work to land); the single barrier of the stage sits in the middle of
 // k-step 3, after which the first fragments of stage kt+1 are read.
-template <class MT, int BM, int BN, int WM, int WN, bool KPACK, int PF, class Epi>
-__global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
+template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi, int WG_PER_CU = 1>
+__global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, const char* zero_page,
                                                                    typename Epi::Args ea)
 {
@@ -197,7 +191,6 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     constexpr int STAGE_BYTES = (BM + BN) * PITCH;
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "stage rows must divide over the threads");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && MB % 2 == 0, "wave tiles are made of 32x32 blocks");
-    static_assert(PF == 1 || PF == 2, "register prefetch depth");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -210,10 +203,11 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // the epilogue object exists from the start so that it can fetch small per-tile side data (held in
-    // registers across the main loop) instead of paying global-memory latency behind the last MFMA
+    // The epilogue may fetch small per-tile side data ahead of time instead of paying global-memory
+    // latency behind the last MFMA: its prefetch hook runs where the main loop issues its last stage
+    // load, so the registers it fills are the ones the staged loads no longer need.
     Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
-    epi.template prefetch<MB, NB>(m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
+#define EGG_EPI_PREFETCH epi.template prefetch<MB, NB>(m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
 
     const char* pb = P.base + (int64_t)m0 * P.row_stride;
     const char* qb = Q.base + (int64_t)n0 * Q.row_stride;
@@ -255,7 +249,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
     }
 #define EGG_MMA_ROWS(BUF, I0, I1)                                                                              \
     _Pragma("unroll") for (int i = I0; i < I1; ++i) _Pragma("unroll") for (int j = 0; j < NB; ++j)             \
-        if (!EGG_DBG_SKIP_MMA) MT::mma(fa[BUF][i], fb[BUF][j], acc[i][j]);
+        MT::mma(fa[BUF][i], fb[BUF][j], acc[i][j]);
 // Scheduling patterns (sched_group_barrier masks: 0x008 MFMA, 0x100 LDS read, 0x200 LDS write,
 // 0x020 VMEM read).  Every k-step pairs one LDS fragment read with each of its first MB+NB MFMAs;
 // k-step 1 additionally spreads the ds_writes of the next stage, k-step 2 the global loads of the
@@ -271,28 +265,27 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
             if ((N_B) > 0 && r_ * PB_ < (N_B)) __builtin_amdgcn_sched_group_barrier(MASK_B, PB_, 0);           \
         }                                                                                                      \
     }
-// Stage kt+1 travels registers -> LDS and stage kt+1+PF global -> registers in two halves (P rows,
+// Stage kt+1 travels registers -> LDS and stage kt+2 global -> registers in two halves (P rows,
 // then Q rows) spread over k-steps 0..2, so that no k-step carries the whole 64 KB LDS write burst:
-//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+1+PF), ds_write Q(kt+1)
-//   k-step 2: load Q(kt+1+PF)             k-step 3: barrier in the middle, then first fragments of kt+1
-// RS is the register set that holds stage kt+1 (and receives stage kt+1+PF).
-#define EGG_ITER(KT_, RS, DO_STORE, DO_LOAD, MORE)                                                             \
+//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+2), ds_write Q(kt+1)
+//   k-step 2: load Q(kt+2)                k-step 3: barrier in the middle, then first fragments of kt+1
+#define EGG_ITER(KT_, DO_STORE, DO_LOAD, MORE)                                                                 \
     {                                                                                                          \
         const int cur_ = (KT_)&1;                                                                              \
         char* nxt_ = lds + (cur_ ^ 1) * STAGE_BYTES;                                                           \
-        const int lk_ = (KT_) + 1 + PF;                                                                        \
+        const int lk_ = (KT_) + 2;                                                                             \
         EGG_READ_FRAGS(1, cur_, 1)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
         if (DO_STORE) {                                                                                        \
-            lp.store(rp[RS], nxt_, tid);                                                                       \
+            lp.store(rp, nxt_, tid);                                                                       \
             EGG_SCHED(0x200, LP_, 0, 0)                                                                        \
         } else {                                                                                               \
             EGG_SCHED(0, 0, 0, 0)                                                                              \
         }                                                                                                      \
         EGG_READ_FRAGS(0, cur_, 2)                                                                             \
         EGG_MMA_ROWS(1, 0, MB)                                                                                 \
-        if (DO_LOAD) lp.load(rp[RS], pb + (int64_t)lk_ * pstep, lk_ * 8, kchunks, zero_page);                  \
-        if (DO_STORE) lq.store(rq[RS], nxt_ + BM * PITCH, tid);                                                \
+        if (DO_LOAD) lp.load(rp, pb + (int64_t)lk_ * pstep, lk_ * 8, kchunks, zero_page);                  \
+        if (DO_STORE) lq.store(rq, nxt_ + BM * PITCH, tid);                                                \
         if (DO_LOAD) {                                                                                         \
             EGG_SCHED(0x020, LP_, 0x200, LQ_)                                                                  \
         } else if (DO_STORE) {                                                                                 \
@@ -303,7 +296,7 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
         EGG_READ_FRAGS(1, cur_, 3)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
         if (DO_LOAD) {                                                                                         \
-            lq.load(rq[RS], qb + (int64_t)lk_ * qstep, lk_ * 8, kchunks, zero_page);                           \
+            lq.load(rq, qb + (int64_t)lk_ * qstep, lk_ * 8, kchunks, zero_page);                           \
             EGG_SCHED(0x020, LQ_, 0, 0)                                                                        \
         } else {                                                                                               \
             EGG_SCHED(0, 0, 0, 0)                                                                              \
@@ -313,53 +306,26 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_kernel(Operand P, Oper
         if (MORE) EGG_READ_FRAGS(0, cur_ ^ 1, 0)                                                               \
         EGG_MMA_ROWS(1, MB / 2, MB)                                                                            \
     }
-#define EGG_LOAD_STAGE(RS, KT_)                                                                                \
+#define EGG_LOAD_STAGE(KT_)                                                                                    \
     {                                                                                                          \
-        lp.load(rp[RS], pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                               \
-        lq.load(rq[RS], qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                               \
+        lp.load(rp, pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                               \
+        lq.load(rq, qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                               \
     }
 
-    // prologue: stage 0 into LDS, stages 1..PF into the register sets (stage s+1 lives in set s % PF ...)
-    u32x4 rp[PF][LP_], rq[PF][LQ_];
-    EGG_LOAD_STAGE(0, 0)
-    lp.store(rp[0], lds, tid);
-    lq.store(rq[0], lds + BM * PITCH, tid);
+    // prologue: stage 0 goes to LDS, stage 1 waits in the registers
+    u32x4 rp[LP_], rq[LQ_];
+    EGG_LOAD_STAGE(0)
+    lp.store(rp, lds, tid);
+    lq.store(rq, lds + BM * PITCH, tid);
+    if (KT > 1) EGG_LOAD_STAGE(1)
+    __syncthreads();
+    EGG_READ_FRAGS(0, 0, 0)
     int kt = 0;
-    if constexpr (PF == 1) {
-        if (KT > 1) EGG_LOAD_STAGE(0, 1)
-        __syncthreads();
-        EGG_READ_FRAGS(0, 0, 0)
-        if (!EGG_DBG_SKIP_LOADS) {
-            for (; kt + 2 < KT; ++kt) EGG_ITER(kt, 0, true, true, true)      // steady state
-            if (kt + 1 < KT) { EGG_ITER(kt, 0, true, false, true) ++kt; }    // last stage is in registers
-            EGG_ITER(kt, 0, false, false, false)                             // last stage
-        } else {
-            for (; kt + 1 < KT; ++kt) EGG_ITER(kt, 0, false, false, true)
-            EGG_ITER(kt, 0, false, false, false)
-        }
-    } else {
-        // two register sets: stage kt+1 sits in set (kt+1)&1 while stage kt+2 is still landing in the other
-        if (KT > 1) EGG_LOAD_STAGE(1, 1)
-        if (KT > 2) EGG_LOAD_STAGE(0, 2)
-        __syncthreads();
-        EGG_READ_FRAGS(0, 0, 0)
-        for (; kt + 4 < KT; kt += 2) {  // steady state, unrolled by two so that the set index is static
-            EGG_ITER(kt, 1, true, true, true)
-            EGG_ITER(kt + 1, 0, true, true, true)
-        }
-        for (; kt < KT; ++kt) {  // the last stages: same steps, guarded
-            const bool st_ = kt + 1 < KT, ld_ = kt + 3 < KT;
-            if (kt & 1) {
-                if (st_ && ld_) EGG_ITER(kt, 0, true, true, true)
-                else if (st_) EGG_ITER(kt, 0, true, false, true)
-                else EGG_ITER(kt, 0, false, false, false)
-            } else {
-                if (st_ && ld_) EGG_ITER(kt, 1, true, true, true)
-                else if (st_) EGG_ITER(kt, 1, true, false, true)
-                else EGG_ITER(kt, 1, false, false, false)
-            }
-        }
-    }
+    for (; kt + 2 < KT; ++kt) EGG_ITER(kt, true, true, true)      // steady state
+    EGG_EPI_PREFETCH
+    if (kt + 1 < KT) { EGG_ITER(kt, true, false, true) ++kt; }    // last stage is in registers
+    EGG_ITER(kt, false, false, false)                             // last stage
+#undef EGG_EPI_PREFETCH
 #undef EGG_LOAD_STAGE
 #undef EGG_ITER
 #undef EGG_SCHED

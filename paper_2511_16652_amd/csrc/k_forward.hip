@@ -254,7 +254,7 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
                               typename Epi::Args ea)
 {
     ea.wtm_pitch = RowStager2B::pitch(BM / WM);
-    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, false, 1, Epi>;
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, false, Epi>;
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     size_t lds = gemm_lds_bytes<BM, BN>();
     size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);

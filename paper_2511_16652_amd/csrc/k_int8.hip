@@ -1,12 +1,14 @@
 // Integer perturbed matmul of the int8 recurrent model, bit-exact
 // (App. "Matrix Multiplication": u @ M = I8(uM / (16 sqrt n)), a right shift for n = 4^d;
 //  App. "Adding EGGROLL Perturbations": I8((u theta^T + ((u . B) I32(A) >> (4 + sigma_hat))) / (16 sqrt n))).
-// Per step: one wave-per-row int8 dot kernel for u . B_i, then the int8 MFMA NT core for u theta^T
-// whose epilogue adds the shifted rank-1 term, shifts, saturates to [-127, 127] and stores int8.
+// Per step: the int8 MFMA NT core computes u theta^T; its epilogue adds the shifted rank-1 term,
+// shifts, saturates to [-127, 127], stores int8 and accumulates the next step's u . B_i (the first
+// step's dot products come from a wave-per-row dot kernel).
 // The factors are fixed while a member is evaluated (Alg. 1), so they are generated once per call
 // into scratch and re-read from L2/HBM at every step.
 #include "common.hpp"
 #include "gemm_core.hpp"
+#include <algorithm>
 
 namespace egg {
 
@@ -37,123 +39,165 @@ __global__ __launch_bounds__(256) void dot_i8_kernel(const int8_t* __restrict__ 
     if (lane == 0) dots[row] = acc;
 }
 
-// Epilogue of the integer step.  A lane owns, per 32-column block, the outputs h'[n][m..m+3] of 4*MB
-// groups; the matching bytes of A_i (for the correction) and of B_i (for the NEXT step's u . B) are
-// fetched at kernel start, so that no global-memory latency sits behind the last MFMA.  The next
-// step's dot product is accumulated here: per column the lane sums h'_j * B_i[j] over its rows, the
-// two half-waves are combined, and one integer atomicAdd per (wave, column) lands in dots_next --
-// integer addition is associative, so the result does not depend on the order of the atomics.
 __global__ __launch_bounds__(256) void zero_i32_kernel(int* __restrict__ p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = 0;
 }
 
+// Epilogue of the integer step.  The MFMA layout gives a lane 4 consecutive outputs of one row of
+// h' at a time, i.e. 4-byte accesses 1 KB apart; instead the int32 accumulators of a 32-row block
+// are parked in the wave's LDS slice and re-read row-wise, so that a lane finishes 16 consecutive
+// outputs of one row: one 16-byte load each of A_i (correction) and B_i (the NEXT step's u . B), one
+// 16-byte store of h'.  Wave tiles of 64 columns fetch those factor bytes and the dot products at
+// kernel start, so that no global-memory latency sits behind the last MFMA.  The next step's dot
+// product is accumulated here: a lane sums h'_j * B_i[j] over its 16 outputs, the lanes of a row are
+// combined by shuffles, and one integer atomicAdd per (wave, row) lands in dots_next -- integer
+// addition is associative, so the result does not depend on the order of the atomics.
+struct I8Args {
+    const int8_t* A;  // [rows][d] factors
+    const int8_t* B;  // [rows][d] factors
+    const int* dots;  // [rows]  u . B of this step
+    int* dots_next;   // [rows]  accumulates u' . B for the next step (zeroed by the host), or NULL
+    int8_t* H_out;    // [rows][d]
+    int d, corr_shift, out_shift;
+};
+
+template <bool DOT24>
 struct I8Epi {
     typedef int value_t;
-    struct Args {
-        const int8_t* A;  // [rows][d] factors
-        const int8_t* B;  // [rows][d] factors
-        const int* dots;  // [rows]  u . B of this step
-        int* dots_next;   // [rows]  accumulates u' . B for the next step (zeroed by the host), or NULL
-        int8_t* H_out;    // [rows][d]
-        int d, corr_shift, out_shift;
-    };
+    typedef I8Args Args;
+    static constexpr int MAX_PF_PASSES = 2;  // wave tiles up to 64 wide prefetch
     const Args a;
-    int dot[2];
-    uint32_t pa[2][2][4], pb[2][2][4];  // prefetched bytes of A_i and B_i: [row block][column block][q]
-    int part;                           // running partial of the next dot for the current column block
-    int cur_j, cur_iq;
-    bool have_pf;                       // small tiles prefetch; the 256x256 tile has no registers to spare
+    char* const stage;
+    const int lane;
+    u32x4 pa[2][MAX_PF_PASSES], pb[2][MAX_PF_PASSES];  // prefetched bytes of A_i and B_i: [row block][pass]
+    int pdot[2][MAX_PF_PASSES];
+    int cur_j;
+    int row_pitch;  // pitch(wave tile width), fixed by prefetch() at kernel start
 
-    static constexpr __host__ __device__ int lds_per_wave(int) { return 0; }
-    __device__ __forceinline__ I8Epi(const Args& a_, char*, int) : a(a_), part(0), cur_j(-1), cur_iq(0), have_pf(false) {}
+    static constexpr __host__ __device__ int pitch(int wtm) { return wtm * 4 + 16; }
+    static constexpr __host__ __device__ int lds_per_wave(int wtm) { return 32 * pitch(wtm); }
+    __device__ __forceinline__ I8Epi(const Args& a_, char* slice, int lane_) : a(a_), stage(slice), lane(lane_), cur_j(-1) {}
     template <int NT, int BM, int BN>
     __device__ __forceinline__ bool tile_begin(char*, int, int, int, int) { return false; }
     template <class MT, int MB, int NB>
     __device__ __forceinline__ void extra_mma(typename MT::acc_t (&)[MB][NB], int, int, int, int) {}
 
-    template <int MB, int NB>
-    __device__ __forceinline__ void prefetch(int mw0, int nw0, int lane, int n_rows)
+    // pass `it` of a 32-row block: the row (inside the block) and first column (inside the wave tile) of this lane
+    template <int WTM>
+    __device__ __forceinline__ void pass_coords(int it, int& row, int& mc) const
     {
-        static_assert(MB <= 4 && NB <= 2, "prefetch storage");
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const int n = min(nw0 + j * 32 + (lane & 31), n_rows - 1);
-            dot[j] = a.dots[n];
-            if constexpr (MB > 2) continue;
-            have_pf = true;
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int m = min(mw0 + i * 32 + q * 8 + (lane >> 5) * 4, a.d - 4);
-                    const int64_t off = (int64_t)n * a.d + m;
-                    pa[i][j][q] = *(const uint32_t*)(a.A + off);
-                    pb[i][j][q] = a.dots_next ? *(const uint32_t*)(a.B + off) : 0u;
-                }
-        }
-    }
-    __device__ __forceinline__ void column(int, bool)
-    {
-        ++cur_j;
-        cur_iq = 0;
-        part = 0;
-    }
-    __device__ __forceinline__ void store4(int m, int n, const int (&v)[4], bool valid, int)
-    {
-        const int i = cur_iq >> 2, q = cur_iq & 3;
-        ++cur_iq;
-        if (!valid || m >= a.d) return;
-        // cur_j, i, q are compile-time constants after unrolling; the selects below fold away
-        uint32_t a4 = 0, b4 = 0;
-        const int dj = cur_j == 0 ? dot[0] : dot[1];
-        if (have_pf) {
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                for (int ii = 0; ii < 2; ++ii)
-#pragma unroll
-                    for (int qq = 0; qq < 4; ++qq)
-                        if (jj == cur_j && ii == i && qq == q) {
-                            a4 = pa[ii][jj][qq];
-                            b4 = pb[ii][jj][qq];
-                        }
-        } else {
-            const int64_t off = (int64_t)n * a.d + m;
-            a4 = *(const uint32_t*)(a.A + off);
-            b4 = a.dots_next ? *(const uint32_t*)(a.B + off) : 0u;
-        }
-        uint32_t out = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int ae = (int)(int8_t)(a4 >> (8 * e));
-            const int corr = (dj * ae) >> a.corr_shift;  // arithmetic shift: floor
-            int y = (v[e] + corr) >> a.out_shift;
-            y = min(127, max(-127, y));
-            out |= ((uint32_t)y & 0xFFu) << (8 * e);
-            part += y * (int)(int8_t)(b4 >> (8 * e));
-        }
-        *(uint32_t*)(a.H_out + (int64_t)n * a.d + m) = out;
+        constexpr int CPR = WTM / 16;  // 16-byte output chunks per row
+        const int c = it * 64 + lane;
+        row = c / CPR;
+        mc = (c % CPR) * 16;
     }
     template <int WTM>
-    __device__ __forceinline__ void flush(int, int nb0, int n_rows)
+    __device__ __forceinline__ void fetch(int mw0, int nb0, int it, int n_rows, u32x4& av, u32x4& bv, int& dv) const
     {
-        if (!a.dots_next) return;
-        int p = part + __shfl_xor(part, 32, 64);  // the two half-waves hold different rows of the same column
-        const int lane = threadIdx.x & 63;
-        const int n = nb0 + lane;
-        if (lane < 32 && n < n_rows) atomicAdd(a.dots_next + n, p);
+        int row, mc;
+        pass_coords<WTM>(it, row, mc);
+        const int n = min(nb0 + row, n_rows - 1);
+        const int m = min(mw0 + mc, a.d - 16);
+        const int64_t off = (int64_t)n * a.d + m;
+        av = *(const u32x4*)(a.A + off);
+        if (a.dots_next) bv = *(const u32x4*)(a.B + off);
+        else bv = u32x4{0u, 0u, 0u, 0u};
+        dv = a.dots[n];
+    }
+
+    template <int MB, int NB>
+    __device__ __forceinline__ void prefetch(int mw0, int nw0, int, int n_rows)
+    {
+        static_assert(NB <= 2, "prefetch storage");
+        row_pitch = pitch(MB * 32);
+        if constexpr (MB <= MAX_PF_PASSES) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int it = 0; it < MB; ++it) fetch<MB * 32>(mw0, nw0 + j * 32, it, n_rows, pa[j][it], pb[j][it], pdot[j][it]);
+        }
+    }
+    __device__ __forceinline__ void column(int, bool) { ++cur_j; }
+    __device__ __forceinline__ void store4(int, int, const int (&v)[4], bool, int ml)
+    {
+        *(i32x4*)(stage + (lane & 31) * row_pitch + ml * 4) = i32x4{v[0], v[1], v[2], v[3]};
+    }
+
+    // one lane's 16 outputs of row nb0 + row: correction, shift, saturate, store, next-dot partial
+    template <int WTM>
+    __device__ __forceinline__ void finish_pass(int it, int mw0, int nb0, int n_rows, const u32x4& av, const u32x4& bv, int dv)
+    {
+        constexpr int P = pitch(WTM), CPR = WTM / 16;
+        int row, mc;
+        pass_coords<WTM>(it, row, mc);
+        const int n = nb0 + row, m = mw0 + mc;
+        const bool ok = n < n_rows && m < a.d;
+        const char* src = stage + row * P + mc * 4;
+        u32x4 out;
+        int part = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const i32x4 acc4 = *(const i32x4*)(src + w * 16);
+            int y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ae = (int)(int8_t)(av[w] >> (8 * e));
+                // |u . B| < 2^23 was checked on the host when DOT24: the full-rate 24-bit multiply is exact
+                const int prod = DOT24 ? __mul24(dv, ae) : dv * ae;
+                const int corr = prod >> a.corr_shift;  // arithmetic shift: floor
+                y[e] = min(127, max(-127, (acc4[e] + corr) >> a.out_shift));
+            }
+            // low bytes of y[0..3] -> one word (byte selectors 0-3: second operand, 4-7: first, 0x0c: zero)
+            const uint32_t o = __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
+                               __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu);
+            out[w] = o;
+            part = __builtin_amdgcn_sdot4((int)o, (int)bv[w], part, false);
+        }
+        if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
+        if (a.dots_next) {
+            if (!ok) part = 0;
+#pragma unroll
+            for (int off = 1; off < CPR; off <<= 1) part += __shfl_xor(part, off, 64);
+            if (mc == 0 && n < n_rows) atomicAdd(a.dots_next + n, part);
+        }
+    }
+
+    template <int WTM>
+    __device__ __forceinline__ void flush(int mw0, int nb0, int n_rows)
+    {
+        constexpr int PASSES = WTM / 32;
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes have landed
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (PASSES <= MAX_PF_PASSES) {
+            // cur_j is a compile-time constant after unrolling; the select folds away
+#pragma unroll
+            for (int it = 0; it < PASSES; ++it) {
+                if (cur_j == 0) finish_pass<WTM>(it, mw0, nb0, n_rows, pa[0][it], pb[0][it], pdot[0][it]);
+                else finish_pass<WTM>(it, mw0, nb0, n_rows, pa[1][it], pb[1][it], pdot[1][it]);
+            }
+        } else {
+            // wide tiles have no registers to spare across the main loop: fetch pass by pass
+#pragma unroll
+            for (int it = 0; it < PASSES; ++it) {
+                u32x4 av, bv;
+                int dv;
+                fetch<WTM>(mw0, nb0, it, n_rows, av, bv, dv);
+                finish_pass<WTM>(it, mw0, nb0, n_rows, av, bv, dv);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();  // the slice is reused by the next row block
     }
 };
 
-template <int BM, int BN, int WM, int WN>
-static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand& Q, int kchunks, const I8Epi::Args& ea)
+template <int BM, int BN, int WM, int WN, class Epi>
+static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand& Q, int kchunks, const typename Epi::Args& ea)
 {
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
-    const size_t lds = gemm_lds_bytes<BM, BN>();
+    const size_t lds = std::max(gemm_lds_bytes<BM, BN>(), (size_t)WM * WN * Epi::lds_per_wave(BM / WM));
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, 1, I8Epi>;
+    auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, Epi, (BM * BN <= 128 * 128 ? 2 : 1)>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_gemm_i8");
@@ -196,6 +240,8 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
     if ((st = check_hip(c, hipGetLastError(), "dot_i8 launch")) != EGG_OK) return st;
 
     const int64_t big_tiles = ((d + 255) / 256) * ((rows + 255) / 256);
+    // |u . B_i| <= d * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
+    const bool dot24 = (int64_t)d * 127 * int_bound < (int64_t(1) << 23);
     const int8_t* src = H_in;
     for (int t = 0; t < steps; ++t) {
         int8_t* dst = (t == steps - 1) ? H_out : scratch[t & 1];
@@ -203,9 +249,12 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
         if (alias) dst = scratch[0];
         Operand P{(const char*)W, (int64_t)d, 16, d};
         Operand Q{(const char*)src, (int64_t)d, 16, (int)rows};
-        I8Epi::Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
+        I8Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
                        dst, d, corr_shift, out_shift};
-        st = big_tiles >= 192 ? launch_i8_gemm<256, 256, 2, 4>(c, P, Q, d / 16, ea) : launch_i8_gemm<128, 128, 2, 2>(c, P, Q, d / 16, ea);
+        if (big_tiles >= 192)
+            st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d / 16, ea);
+        else
+            st = dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d / 16, ea);
         if (st != EGG_OK) return st;
         if (alias) {
             if ((st = check_hip(c, hipMemcpyAsync(H_out, dst, hbytes, hipMemcpyDeviceToDevice, c->stream), "copy back")) != EGG_OK) return st;

@@ -197,7 +197,7 @@ static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operan
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, true, 1, UpdEpi>;
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, name);
