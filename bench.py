@@ -33,6 +33,37 @@ def parse():
     return ap.parse_args()
 
 
+def profiled_traffic(workload, markers):
+    """HBM bytes per launch of the dominant kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE,
+    scaled by a copy of known size): the traffic table of profiles/<workload>_kernels.md, row of the
+    kernel whose name holds every marker.  None when no such profile is in the tree."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "%s_kernels.md" % workload)
+    if not os.path.exists(path):
+        return None
+    in_table = False
+    for line in open(path):
+        if line.startswith("## HBM traffic"):
+            in_table = True
+        elif in_table and line.startswith("|") and all(m in line for m in markers):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            try:
+                return int(cells[-1])
+            except ValueError:
+                return None
+    return None
+
+
+def calibration_copy():
+    """A copy kernel of known size inside the same profile (reads 64 MiB, writes 64 MiB): what
+    FETCH_SIZE / WRITE_SIZE report for it gives the scale of each counter."""
+    import torch
+    src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
 def prewarm(fn, seconds=0.4):
     """Untimed: keeps the GPU busy long enough for the shader clock to ramp from idle (measured on
     MI355X: ~1.55 GHz in the first milliseconds of MFMA work, ~2.05 GHz after a few hundred ms)."""
@@ -120,12 +151,8 @@ def linear_workload(args):
     def torch_mm():
         torch.matmul(X, W.t(), out=Y)
 
-    if args.calibrate_copy:  # a copy kernel of known size inside the same profile: reads 64 MiB, writes 64 MiB
-        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+    if args.calibrate_copy:
+        calibration_copy()
 
     prewarm(step)
     t_step = timed(step, args.steps, args.warmup)
@@ -171,7 +198,8 @@ def linear_workload(args):
         "ms": {"forward": 1e3 * t_fwd_nc, "forward_with_caches": 1e3 * t_fwd, "unperturbed": 1e3 * t_unp,
                "update": 1e3 * t_upd, "torch_matmul": 1e3 * t_mm},
         "roofline": {"bound": "mfma", "kernel": gemm_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None},
+                     "frac": achieved / peak,
+                     "traffic": profiled_traffic(args.workload, ("MmaBf16" if wl.dtype == "bf16" else "MmaF32", "FwdEpi"))},
         "update_roofline": {"bound": "mfma", "kernel": upd_name, "achieved": upd_tflops, "peak": peak,
                             "unit": "TFLOP/s", "frac": upd_tflops / peak},
         "kernels": kernels,
@@ -191,19 +219,32 @@ def cpu_baseline_linear(wl):
     from paper_2511_16652_amd import inputs
 
     nd = oracle.NOISE_BF16 if wl.dtype == "bf16" else oracle.NOISE_F32
-    per_member = 3.0 * wl.d_out * wl.d_in * wl.rank  # rough flop-equivalents, only used to size the sample
-    m = int(max(8, min(wl.N, 2e11 / per_member / 8)))
-    m = min(wl.N, max(oracle.threads(), m - m % oracle.threads()))
-    f = inputs.centered(wl.raw_fitness[:m])
-    t0 = time.perf_counter()
-    oracle.forward(wl.noise_seed, wl.step, wl.layer, 0, m, wl.S, wl.d_out, wl.d_in, wl.rank, nd, wl.sigma, 0,
-                   wl.W, wl.X[:m * wl.S])
-    t1 = time.perf_counter()
-    oracle.update(wl.noise_seed, wl.step, wl.layer, 0, m, wl.d_out, wl.d_in, wl.rank, nd, f, 1.0)
-    t2 = time.perf_counter()
-    return {"value": m * wl.S / (t2 - t0), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+    def run(m):
+        f = inputs.centered(wl.raw_fitness[:m])
+        t0 = time.perf_counter()
+        oracle.forward(wl.noise_seed, wl.step, wl.layer, 0, m, wl.S, wl.d_out, wl.d_in, wl.rank, nd, wl.sigma, 0,
+                       wl.W, wl.X[:m * wl.S])
+        t1 = time.perf_counter()
+        oracle.update(wl.noise_seed, wl.step, wl.layer, 0, m, wl.d_out, wl.d_in, wl.rank, nd, f, 1.0)
+        return t1 - t0, time.perf_counter() - t1
+
+    # a short probe sizes the sample to about 12 s of oracle time (the cost is linear in members)
+    th = oracle.threads()
+    probe = min(wl.N, 4 * th)
+    tf, tu = run(probe)
+    m = probe
+    for _ in range(2):  # the first estimate carries the probe's start-up cost: refine once
+        if tf + tu >= 8.0 or m >= wl.N:
+            break
+        want = int(12.0 * m / max(tf + tu, 1e-6))
+        want = min(wl.N, max(m, want - want % th))
+        if want == m:
+            break
+        m = want
+        tf, tu = run(m)
+    return {"value": m * wl.S / (tf + tu), "unit": "tokens/s", "cores": th, "kind": "oracle",
             "sample": "%d of %d members, forward (%.2f s) + update (%.2f s); cost is linear in members" % (
-                m, wl.N, t1 - t0, t2 - t1)}
+                m, wl.N, tf, tu)}
 
 
 def int8_workload(args):
@@ -225,6 +266,8 @@ def int8_workload(args):
     def step():
         ctx.eggroll_perturbed_forward_i8(key, shape, wl.bound, wl.corr_shift, wl.out_shift, wl.steps, W, H, out_t)
 
+    if args.calibrate_copy:
+        calibration_copy()
     prewarm(step)
     t_step = timed(step, args.steps, args.warmup)
     ctx.profile_enable(True)
@@ -243,15 +286,29 @@ def int8_workload(args):
         "config": {"workload": wl.name, "d": wl.d, "population": wl.N, "time_steps": wl.steps, "bound": wl.bound},
         "roofline": {"bound": "mfma", "kernel": "forward_gemm_i8", "achieved": achieved,
                      "peak": roofline.MFMA_PEAK_TFLOPS["i8"], "unit": "TOP/s",
-                     "frac": achieved / roofline.MFMA_PEAK_TFLOPS["i8"], "traffic": None},
+                     "frac": achieved / roofline.MFMA_PEAK_TFLOPS["i8"],
+                     "traffic": profiled_traffic(args.workload, ("MmaI8",))},
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        m = 64 * max(1, oracle.threads() // 8)
-        t0 = time.perf_counter()
-        oracle.forward_i8(0, 0, 0, 0, m, wl.d, wl.bound, wl.corr_shift, wl.out_shift, wl.steps, wl.W, wl.H0[:m])
-        dt = time.perf_counter() - t0
-        res["cpu_baseline"] = {"value": m * wl.steps / dt, "unit": "tokens/s", "cores": oracle.threads(),
+        def run(m):
+            t0 = time.perf_counter()
+            oracle.forward_i8(0, 0, 0, 0, m, wl.d, wl.bound, wl.corr_shift, wl.out_shift, wl.steps, wl.W, wl.H0[:m])
+            return time.perf_counter() - t0
+
+        th = oracle.threads()
+        m = min(wl.N, 4 * th)
+        dt = run(m)
+        for _ in range(2):  # size the sample to about 12 s of oracle time (the cost is linear in members)
+            if dt >= 8.0 or m >= wl.N:
+                break
+            want = int(12.0 * m / max(dt, 1e-6))
+            want = min(wl.N, max(m, want - want % th))
+            if want == m:
+                break
+            m = want
+            dt = run(m)
+        res["cpu_baseline"] = {"value": m * wl.steps / dt, "unit": "tokens/s", "cores": th,
                                "kind": "oracle", "sample": "%d of %d members, all %d time steps (%.2f s)" % (m, wl.N, wl.steps, dt)}
     ctx.close()
     return res
