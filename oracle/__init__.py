@@ -69,6 +69,14 @@ def _load():
         lib.oracle_forward_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32,
                                           vp, vp, vp]
         lib.oracle_forward_i8.restype = None
+        lib.oracle_forward_antithetic.argtypes = lib.oracle_forward.argtypes
+        lib.oracle_forward_antithetic.restype = i32
+        lib.oracle_forward_i8_antithetic.argtypes = lib.oracle_forward_i8.argtypes
+        lib.oracle_forward_i8_antithetic.restype = None
+        lib.oracle_update_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, vp, i64, vp, vp, vp]
+        lib.oracle_update_i8.restype = i32
+        lib.oracle_int_threshold.argtypes = [dbl, i64, dbl]
+        lib.oracle_int_threshold.restype = i64
         lib.oracle_threads.argtypes = []
         lib.oracle_threads.restype = i32
         _lib = lib
@@ -139,13 +147,15 @@ def noise_matrix(seed, step, layer, which, member, d, rank, noise_dtype) -> np.n
 
 
 def forward(seed, step, layer, member_begin, member_count, S, d_out, d_in, rank, noise_dtype,
-            sigma, act, W, X) -> np.ndarray:
-    """Explicit-W_i population forward; returns fp64 Y[member_count*S, d_out] (unrounded)."""
+            sigma, act, W, X, antithetic=False) -> np.ndarray:
+    """Explicit-W_i population forward; returns fp64 Y[member_count*S, d_out] (unrounded).
+    antithetic: members 2p, 2p+1 evaluate M + sigma E_p and M - sigma E_p (noise id p)."""
     W = _c(W, np.float64)
     X = _c(X, np.float64)
     assert W.shape == (d_out, d_in) and X.shape == (member_count * S, d_in)
     Y = np.empty((member_count * S, d_out), np.float64)
-    rc = _load().oracle_forward(seed, step, layer, member_begin, member_count, S, d_out, d_in,
+    fn = _load().oracle_forward_antithetic if antithetic else _load().oracle_forward
+    rc = fn(seed, step, layer, member_begin, member_count, S, d_out, d_in,
                                 rank, noise_dtype, float(sigma), act, _ptr(W), _ptr(X), _ptr(Y))
     if rc != 0:
         raise MemoryError("oracle_forward")
@@ -173,11 +183,34 @@ def update_entry(seed, step, layer, member_begin, member_count, rank, noise_dtyp
 
 
 def forward_i8(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift,
-               steps, W, H_in) -> np.ndarray:
+               steps, W, H_in, antithetic=False) -> np.ndarray:
     W = _c(W, np.int8)
     H = _c(H_in, np.int8)
     assert W.shape == (d, d) and H.shape == (member_count, d)
     out = np.empty_like(H)
-    _load().oracle_forward_i8(seed, step, layer, member_begin, member_count, d, bound, corr_shift,
+    fn = _load().oracle_forward_i8_antithetic if antithetic else _load().oracle_forward_i8
+    fn(seed, step, layer, member_begin, member_count, d, bound, corr_shift,
                               out_shift, steps, _ptr(W), _ptr(H), _ptr(out))
     return out
+
+
+def update_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, F, threshold, theta):
+    """Integer update: returns (theta', E) with E = sum_i F_i A_i B_i^T (int32) and
+    theta' = clamp(theta + sign(E) [|E| >= threshold], -127, 127)."""
+    F = _c(F, np.int8)
+    theta = _c(theta, np.int8)
+    assert F.shape == (member_count,) and theta.shape == (d_out, d_in)
+    out = np.empty_like(theta)
+    E = np.empty((d_out, d_in), np.int32)
+    rc = _load().oracle_update_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, _ptr(F),
+                                  int(threshold), _ptr(theta), _ptr(out), _ptr(E))
+    if rc == -1:
+        raise MemoryError("oracle_update_i8")
+    if rc == -2:
+        raise OverflowError("oracle_update_i8: |E| exceeds int32")
+    return out, E
+
+
+def int_threshold(alpha: float, n_terms: int, noise_std: float) -> int:
+    """trunc(noise_std * Phi^-1(1 - alpha/2)) * round(noise_std * sqrt(n_terms))."""
+    return int(_load().oracle_int_threshold(float(alpha), int(n_terms), float(noise_std)))

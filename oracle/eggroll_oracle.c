@@ -201,11 +201,11 @@ static double gelu_exact(double x) { return 0.5 * x * (1.0 + erf(x * 0.707106781
  * W[d_out*d_in], X[count*S*d_in], Y[count*S*d_out] all fp64 holding storage-dtype values.
  * Returns 0, or -1 if memory for the per-thread W_i could not be obtained.
  */
-int oracle_forward(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
-                   int64_t member_count, int S, int d_out, int d_in, int rank, int noise_dtype,
-                   double sigma, int act, const double* W, const double* X, double* Y)
+static int forward_worker(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                          int64_t member_count, int S, int d_out, int d_in, int rank, int noise_dtype,
+                          double sigma, int act, int antithetic, const double* W, const double* X, double* Y)
 {
-    const double c = sigma / sqrt((double)rank);
+    const double c0 = sigma / sqrt((double)rank);
     int failed = 0;
 #pragma omp parallel
     {
@@ -219,8 +219,11 @@ int oracle_forward(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_
 #pragma omp for schedule(dynamic, 1)
             for (int64_t m = 0; m < member_count; ++m) {
                 const int64_t member = member_begin + m;
-                oracle_noise_matrix(seed, step, layer, 0, member, d_out, rank, noise_dtype, A);
-                oracle_noise_matrix(seed, step, layer, 1, member, d_in, rank, noise_dtype, B);
+                /* antithetic: members 2p and 2p+1 evaluate M + sigma E_p and M - sigma E_p */
+                const int64_t noise_id = antithetic ? member / 2 : member;
+                const double c = (antithetic && (member & 1)) ? -c0 : c0;
+                oracle_noise_matrix(seed, step, layer, 0, noise_id, d_out, rank, noise_dtype, A);
+                oracle_noise_matrix(seed, step, layer, 1, noise_id, d_in, rank, noise_dtype, B);
                 for (int j = 0; j < d_out; ++j) {
                     for (int k = 0; k < d_in; ++k) {
                         double e = 0.0;
@@ -244,6 +247,27 @@ int oracle_forward(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_
         free(Wi); free(A); free(B);
     }
     return failed ? -1 : 0;
+}
+
+int oracle_forward(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                   int64_t member_count, int S, int d_out, int d_in, int rank, int noise_dtype,
+                   double sigma, int act, const double* W, const double* X, double* Y)
+{
+    return forward_worker(seed, step, layer, member_begin, member_count, S, d_out, d_in, rank, noise_dtype,
+                          sigma, act, 0, W, X, Y);
+}
+
+/*
+ * Antithetic pairs (used by the paper's integer and quantised experiments: App. "Fitness Shaping",
+ * "antithetical pair"): member ids 2p and 2p+1 share the factors of pair p (noise id p) and are
+ * evaluated at W = M + sigma E_p and W = M - sigma E_p.  member_begin counts members, not pairs.
+ */
+int oracle_forward_antithetic(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                              int64_t member_count, int S, int d_out, int d_in, int rank, int noise_dtype,
+                              double sigma, int act, const double* W, const double* X, double* Y)
+{
+    return forward_worker(seed, step, layer, member_begin, member_count, S, d_out, d_in, rank, noise_dtype,
+                          sigma, act, 1, W, X, Y);
 }
 
 /* ------------------------------------------------------------------------------------------ */
@@ -320,9 +344,9 @@ static int32_t shr_floor(int64_t v, int s) /* arithmetic shift: floor(v / 2^s) *
  *     h'_j   = clamp((acc_j + corr_j) >> out_shift, -127, 127)         "I8(. / (16 sqrt n))"
  * rank 1, square W (d x d), noise on {-bound..bound}.  H_in/H_out: [count][d].
  */
-void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
-                       int64_t member_count, int d, int bound, int corr_shift, int out_shift,
-                       int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
+static void forward_i8_worker(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                              int64_t member_count, int d, int bound, int corr_shift, int out_shift,
+                              int steps, int antithetic, const int8_t* W, const int8_t* H_in, int8_t* H_out)
 {
 #pragma omp parallel
     {
@@ -333,8 +357,12 @@ void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t mem
 #pragma omp for schedule(dynamic, 4)
         for (int64_t m = 0; m < member_count; ++m) {
             const int64_t member = member_begin + m;
-            oracle_noise_int(seed, step, layer, 0, member, 0, (uint64_t)d, bound, A);
-            oracle_noise_int(seed, step, layer, 1, member, 0, (uint64_t)d, bound, B);
+            const int64_t noise_id = antithetic ? member / 2 : member;
+            oracle_noise_int(seed, step, layer, 0, noise_id, 0, (uint64_t)d, bound, A);
+            oracle_noise_int(seed, step, layer, 1, noise_id, 0, (uint64_t)d, bound, B);
+            /* the negative member of a pair carries the perturbation A (-B)^T: one formula for both signs */
+            if (antithetic && (member & 1))
+                for (int k = 0; k < d; ++k) B[k] = (int8_t)(-B[k]);
             for (int k = 0; k < d; ++k) h[k] = H_in[(size_t)m * d + k];
             for (int t = 0; t < steps; ++t) {
                 int32_t dot = 0;
@@ -355,6 +383,102 @@ void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t mem
         }
         free(A); free(B); free(h); free(hn);
     }
+}
+
+void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                       int64_t member_count, int d, int bound, int corr_shift, int out_shift,
+                       int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
+{
+    forward_i8_worker(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift, steps, 0,
+                      W, H_in, H_out);
+}
+
+/* antithetic pairs in the integer model: members 2p, 2p+1 share noise id p; the odd one uses -B_p */
+void oracle_forward_i8_antithetic(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                                  int64_t member_count, int d, int bound, int corr_shift, int out_shift,
+                                  int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
+{
+    forward_i8_worker(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift, steps, 1,
+                      W, H_in, H_out);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* integer parameter update (App. "Parameter Update" of the integer pretraining section)       */
+/* ------------------------------------------------------------------------------------------ */
+/*
+ *   E[j,k]      = sum_i F_i A_i[j] B_i[k]                      int32, F_i in {-1, 0, 1}   "E = (diag(F)A)^T B"
+ *   theta'[j,k] = clamp(theta[j,k] + sign(E[j,k]) * [ |E[j,k]| >= threshold ], -127, 127)
+ * "when the absolute value of E is above a pre-specified threshold we move theta by one discrete
+ * bin in the direction of the sign of E".  The boundary case |E| == threshold moves (a reading: the
+ * paper says "above"; >= makes threshold 0 mean "every non-zero E moves").  E as explicit outer
+ * products member by member.  Returns 0, -1 on allocation failure, -2 if some |E| left int32.
+ * E_out may be NULL.
+ */
+int oracle_update_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
+                     int64_t member_count, int d_out, int d_in, int bound, const int8_t* F,
+                     int64_t threshold, const int8_t* theta_in, int8_t* theta_out, int32_t* E_out)
+{
+    int8_t* A = (int8_t*)malloc((size_t)d_out * (size_t)member_count + 1);
+    int8_t* B = (int8_t*)malloc((size_t)d_in * (size_t)member_count + 1);
+    if (!A || !B) { free(A); free(B); return -1; }
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < member_count; ++m) {
+        oracle_noise_int(seed, step, layer, 0, member_begin + m, 0, (uint64_t)d_out, bound, A + (size_t)d_out * (size_t)m);
+        oracle_noise_int(seed, step, layer, 1, member_begin + m, 0, (uint64_t)d_in, bound, B + (size_t)d_in * (size_t)m);
+    }
+    int overflow = 0;
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d_out; ++j) {
+        int64_t* e = (int64_t*)calloc((size_t)d_in, sizeof(int64_t));
+        for (int64_t m = 0; m < member_count; ++m) {
+            const int64_t fa = (int64_t)F[m] * (int64_t)A[(size_t)d_out * (size_t)m + j];
+            if (fa == 0) continue;
+            const int8_t* b = B + (size_t)d_in * (size_t)m;
+            for (int k = 0; k < d_in; ++k) e[k] += fa * (int64_t)b[k];
+        }
+        for (int k = 0; k < d_in; ++k) {
+            const int64_t v = e[k], mag = v < 0 ? -v : v;
+            if (mag > 2147483647LL) {
+#pragma omp atomic write
+                overflow = 1;
+            }
+            if (E_out) E_out[(size_t)j * d_in + k] = (int32_t)v;
+            int t = theta_in[(size_t)j * d_in + k];
+            if (mag >= threshold && v != 0) t += v > 0 ? 1 : -1;
+            if (t > 127) t = 127;
+            if (t < -127) t = -127;
+            theta_out[(size_t)j * d_in + k] = (int8_t)t;
+        }
+        free(e);
+    }
+    free(A); free(B);
+    return overflow ? -2 : 0;
+}
+
+/*
+ * Threshold of the integer update, precalculated on the CPU as the paper says:
+ *     I32(16 * Phi^-1(.)) * 16 sqrt(N)        for noise of standard deviation 16.
+ * Printed argument of Phi^-1 is (1 - alpha)/2; with it the updated fraction would be 1 - alpha, while
+ * the text states that alpha "approximately equals the fraction of parameters that are updated" and
+ * lets alpha decay from 1 towards 0.  Reading taken: the two-sided alpha-quantile z = Phi^-1(1 - alpha/2)
+ * (so P(|Z| >= z) = alpha), I32 = truncation, and 16 generalised to the standard deviation of the noise in
+ * use:  threshold = trunc(noise_std * z) * round(noise_std * sqrt(n_terms)).
+ * Phi^-1 by bisection on erfc (monotone; 200 halvings of [0, 40]).
+ */
+int64_t oracle_int_threshold(double alpha, int64_t n_terms, double noise_std)
+{
+    if (!(alpha > 0.0)) return INT64_MAX;
+    if (alpha >= 1.0) return 0;
+    double lo = 0.0, hi = 40.0;
+    for (int it = 0; it < 200; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (erfc(mid * 0.70710678118654752440) > alpha) lo = mid; /* P(|Z| >= mid) = erfc(mid / sqrt 2) */
+        else hi = mid;
+    }
+    const double z = 0.5 * (lo + hi);
+    const int64_t first = (int64_t)(noise_std * z); /* truncation */
+    const int64_t second = (int64_t)llround(noise_std * sqrt((double)n_terms));
+    return first * second;
 }
 
 int oracle_threads(void)
