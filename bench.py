@@ -278,6 +278,24 @@ def int8_workload(args):
     kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in prof.items()}
     ops = 2.0 * wl.N * wl.d * wl.d
     achieved = ops / (kernels["forward_gemm_i8"]["avg_us"] * 1e-6) / 1e12
+
+    # the integer parameter update over the same population (not part of the timed step: the metric is
+    # the recurrence), ternary fitness, threshold for about 20 % moves
+    rng = np.random.default_rng(5)
+    F = torch.from_numpy(rng.choice(np.array([-1, 1], np.int8), wl.N)).cuda()
+    theta = W.clone()
+    tau = eb.eggroll_int_threshold(0.2, wl.N, (wl.bound * (wl.bound + 1) / 3.0) ** 0.5)
+
+    def upd():
+        ctx.eggroll_update_i8(key, shape, wl.bound, F, tau, theta)
+
+    prewarm(upd, 0.2)
+    t_upd = timed(upd, args.steps, args.warmup)
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        upd()
+    uk = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in ctx.profile_read().items()}
+    ctx.profile_enable(False)
     res = {
         "metric": "population tokens/sec (integer perturbed recurrence), 1 GPU",
         "value": wl.N * wl.steps / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -289,6 +307,7 @@ def int8_workload(args):
                      "frac": achieved / roofline.MFMA_PEAK_TFLOPS["i8"],
                      "traffic": profiled_traffic(args.workload, ("MmaI8",))},
         "kernels": kernels,
+        "integer_update": {"ms": 1e3 * t_upd, "TOP/s": ops / t_upd / 1e12, "threshold": tau, "kernels": uk},
     }
     if not args.no_cpu_baseline:
         def run(m):

@@ -129,6 +129,28 @@ egg_status eggroll_update(eggroll_ctx* ctx, egg_key key, const egg_shape* shape,
                           egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache);
 
 /*
+ * (3') Integer parameter update (App. "Parameter Update" of the integer pretraining section), rank 1:
+ *   E[j][k]     = sum_i fitness[i] * A_i[j] * B_i[k]          int32; fitness[i] in {-1, 0, 1}
+ *   theta[j][k] = clamp( theta[j][k] + sign(E[j][k]) * [ |E[j][k]| >= threshold ], -127, 127 )
+ * theta: int8 [d_out][d_in], updated in place.  fitness: int8 [member_count] (with antithetic
+ * pairs: one shaped value sign(s+ - s-) per pair, and member ids are pair ids).  The factors are the
+ * integers on {-int_bound..int_bound} that eggroll_perturbed_forward_i8 uses for the same key.
+ * threshold >= 0 (0: every non-zero E moves its entry).  E_out: optional int32 [d_out][d_in].
+ * d_out and d_in must be multiples of 16, member_count * int_bound^2 < 2^31.  Bit-exact; the result
+ * does not depend on the order in which partial sums are combined.  rows_per_member is ignored.
+ */
+egg_status eggroll_update_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound,
+                             const int8_t* fitness, int32_t threshold, int8_t* theta, int32_t* E_out);
+
+/* Threshold of (3'), computed on the host as the paper prescribes: I32(16 Phi^-1(.)) * 16 sqrt(N) for
+   noise of standard deviation 16, read as the two-sided alpha-quantile (a fraction of about alpha of
+   the entries moves) and generalised to the standard deviation of the noise in use:
+       trunc(noise_std * z) * round(noise_std * sqrt(n_terms)),   P(|Z| >= z) = alpha.
+   alpha >= 1 gives 0; alpha <= 0 gives INT64_MAX.  Uniform integers on {-b..b} have
+   noise_std = sqrt(b(b+1)/3).  Host-only, no context needed. */
+int64_t eggroll_int_threshold(double alpha, int64_t n_terms, double noise_std);
+
+/*
  * Per-kernel timing for benchmarks.  With profiling on, every kernel the library launches is
  * bracketed by HIP events on the context's stream.  eggroll_profile_read synchronises the stream
  * and fills names[i] (pointers to static strings), launches[i], total_ms[i] for up to `cap`

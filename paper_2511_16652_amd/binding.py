@@ -19,8 +19,8 @@ EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
            "eggroll_default_scale", "eggroll_noise_gen", "eggroll_perturbed_forward",
-           "eggroll_perturbed_forward_i8", "eggroll_update", "eggroll_profile_enable",
-           "eggroll_profile_read"]
+           "eggroll_perturbed_forward_i8", "eggroll_update", "eggroll_update_i8",
+           "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
 
 
 class EggKey(ctypes.Structure):
@@ -72,6 +72,10 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_perturbed_forward_i8.restype = i32
     lib.eggroll_update.argtypes = [vp, EggKey, P(EggShape), i32, vp, f32, i32, vp, vp, i32, f32, vp, vp]
     lib.eggroll_update.restype = i32
+    lib.eggroll_update_i8.argtypes = [vp, EggKey, P(EggShape), i32, vp, ctypes.c_int32, vp, vp]
+    lib.eggroll_update_i8.restype = i32
+    lib.eggroll_int_threshold.argtypes = [ctypes.c_double, i64, ctypes.c_double]
+    lib.eggroll_int_threshold.restype = i64
     lib.eggroll_profile_enable.argtypes = [vp, i32]
     lib.eggroll_profile_enable.restype = i32
     lib.eggroll_profile_read.argtypes = [vp, P(ctypes.c_char_p), P(i64), P(ctypes.c_double), i32]
@@ -95,6 +99,10 @@ def _ptr(t):
 
 def eggroll_default_scale(population: int, sigma: float, rank: int) -> float:
     return float(load_library().eggroll_default_scale(population, sigma, rank))
+
+
+def eggroll_int_threshold(alpha: float, n_terms: int, noise_std: float) -> int:
+    return int(load_library().eggroll_int_threshold(float(alpha), int(n_terms), float(noise_std)))
 
 
 class Context:
@@ -151,6 +159,10 @@ class Context:
         self._check(self._lib.eggroll_update(
             self._h, key, ctypes.byref(shape), noise_dtype, _ptr(fitness), float(scale), int(accumulate),
             _ptr(G), _ptr(W), w_dtype, float(lr), _ptr(A_cache), _ptr(B_cache)))
+
+    def eggroll_update_i8(self, key, shape, int_bound, fitness, threshold, theta, E_out=None):
+        self._check(self._lib.eggroll_update_i8(
+            self._h, key, ctypes.byref(shape), int_bound, _ptr(fitness), int(threshold), _ptr(theta), _ptr(E_out)))
 
     # -- per-kernel timing -----------------------------------------------------------------------
     def profile_enable(self, on: bool):

@@ -1,5 +1,6 @@
 // C ABI of libeggroll: argument validation, scratch management, and the sequencing of kernels for
 // each entry point of include/eggroll.h.  No arithmetic of the method happens on the host.
+#include <math.h>
 #include <stdarg.h>
 #include <string.h>
 
@@ -258,6 +259,47 @@ egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, e
     return launch_update(c, make_stream_key(key.seed, key.step, key.layer, 0),
                          make_stream_key(key.seed, key.step, key.layer, 1), *shape, noise_dtype, fitness, scale,
                          accumulate, G, W, w_dtype, lr, A_cache, B_cache);
+}
+
+egg_status eggroll_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound, const int8_t* fitness,
+                             int32_t threshold, int8_t* theta, int32_t* E_out)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, false);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!fitness || !theta) return fail(c, EGG_EINVAL, "fitness and theta must be non-NULL");
+    if (!aligned16(theta) || !aligned16(E_out)) return fail(c, EGG_EINVAL, "theta and E_out must be 16-byte aligned");
+    if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
+    if (shape->d_out % 16 || shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "d_out and d_in must be multiples of 16");
+    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (threshold < 0) return fail(c, EGG_EINVAL, "threshold must be >= 0");
+    // int32 E: |E| <= N * bound^2
+    if (shape->member_count * (int64_t)int_bound * int_bound > 0x7FFFFFFFLL)
+        return fail(c, EGG_EUNSUPPORTED, "population too large for int32 accumulation");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_update_i8(c, make_stream_key(key.seed, key.step, key.layer, 0),
+                            make_stream_key(key.seed, key.step, key.layer, 1), *shape, int_bound, fitness, threshold,
+                            theta, E_out);
+}
+
+int64_t eggroll_int_threshold(double alpha, int64_t n_terms, double noise_std)
+{
+    if (!(alpha > 0.0)) return INT64_MAX;
+    if (alpha >= 1.0 || n_terms <= 0 || !(noise_std > 0.0)) return 0;
+    // z with erfc(z / sqrt 2) = alpha: Newton's method on g(z) = log erfc(z / sqrt 2) - log alpha, which is
+    // concave and decreasing, so the iteration from z = 0 increases monotonically to the root
+    const double la = log(alpha), rs2 = 0.70710678118654752440, c = 0.79788456080286535588;  // sqrt(2/pi)
+    double z = 0.0;
+    for (int it = 0; it < 200; ++it) {
+        const double q = erfc(z * rs2);
+        const double step = (log(q) - la) * q / (c * exp(-0.5 * z * z));  // -g/g', g' = -c exp(-z^2/2) / q
+        z += step;
+        if (fabs(step) <= 1e-16 * (1.0 + z)) break;
+    }
+    const int64_t first = (int64_t)(noise_std * z);  // truncation
+    const int64_t second = (int64_t)llround(noise_std * sqrt((double)n_terms));
+    return first * second;
 }
 
 egg_status eggroll_profile_enable(eggroll_ctx* c, int on)

@@ -76,4 +76,7 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out);
 
+egg_status launch_update_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
+                            int int_bound, const int8_t* F, int32_t threshold, int8_t* theta, int32_t* E_out);
+
 }  // namespace egg

@@ -181,7 +181,7 @@ constexpr size_t gemm_lds_bytes()
 // k-step 3, after which the first fragments of stage kt+1 are read.
 template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi, int WG_PER_CU = 1>
 __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
-                                                                   int tiles_n, const char* zero_page,
+                                                                   int tiles_n, int ksplit, const char* zero_page,
                                                                    typename Epi::Args ea)
 {
     constexpr int NT = WM * WN * 64;
@@ -199,8 +199,18 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
 
+    // split-K (ksplit > 0): consecutive groups of tiles_m * tiles_n workgroups own consecutive ranges of
+    // ksplit K-chunks; the epilogue then has to combine the partial tiles (integer atomics)
+    int tile_id = blockIdx.x, kbeg = 0;
+    if (ksplit > 0) {
+        const int tiles = tiles_m * tiles_n;
+        const int sp = tile_id / tiles;
+        tile_id -= sp * tiles;
+        kbeg = sp * ksplit;
+        kchunks = min(kchunks - kbeg, ksplit);
+    }
     int tm, tn;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    tile_coords(tile_id, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     // The epilogue may fetch small per-tile side data ahead of time instead of paying global-memory
@@ -209,8 +219,8 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
     Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
 #define EGG_EPI_PREFETCH epi.template prefetch<MB, NB>(m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
 
-    const char* pb = P.base + (int64_t)m0 * P.row_stride;
-    const char* qb = Q.base + (int64_t)n0 * Q.row_stride;
+    const char* pb = P.base + (int64_t)m0 * P.row_stride + (int64_t)kbeg * P.kc_stride;
+    const char* qb = Q.base + (int64_t)n0 * Q.row_stride + (int64_t)kbeg * Q.kc_stride;
     Loader<BM, NT, KPACK> lp;
     Loader<BN, NT, KPACK> lq;
     lp.init(P, m0, tid);

@@ -275,7 +275,7 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     const int64_t grid = (int64_t)tiles_m * tiles_n;
     if (grid > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many tiles");
     KernelScope ks(c, name);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks, tiles_m, tiles_n,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks, tiles_m, tiles_n, 0,
                        (const char*)c->zero_page.p, ea);
     return check_hip(c, hipGetLastError(), name);
 }

@@ -202,7 +202,7 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_gemm_i8");
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks,
-                       tiles_m, tiles_n, (const char*)c->zero_page.p, ea);
+                       tiles_m, tiles_n, 0, (const char*)c->zero_page.p, ea);
     return check_hip(c, hipGetLastError(), "forward_gemm_i8");
 }
 

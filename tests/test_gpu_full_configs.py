@@ -158,3 +158,25 @@ def test_layer_shapes_of_configs_4_and_5(ctx, name, d_out, d_in, N, S, r, act):
     err = np.abs(g[js, ks] - want)
     assert (err <= 1e-2 * (np.abs(want) + rms)).all()
     assert (err > 2e-3 * (np.abs(want) + rms)).mean() < 0.03
+
+
+def test_config3_full_size_integer_update(ctx):
+    """The integer update at config 3's size (1024 x 1024 int8 weights, all 8192 members), every
+    entry of E and of the moved weights bit for bit; then as pair fitness over 4096 pairs."""
+    import torch
+    wl = inputs.config3()
+    rng = np.random.default_rng(77)
+    std = np.sqrt(wl.bound * (wl.bound + 1) / 3.0)
+    for N in (wl.N, wl.N // 2):
+        F = rng.choice(np.array([-1, 0, 1], np.int8), N, p=[0.45, 0.1, 0.45])
+        tau = eb.eggroll_int_threshold(0.2, int((F != 0).sum()), std)
+        want_t, want_E = oracle.update_i8(0, 0, 0, 0, N, wl.d, wl.d, wl.bound, F, tau, wl.W)
+        th = torch.from_numpy(wl.W.copy()).cuda()
+        E = torch.empty((wl.d, wl.d), dtype=torch.int32, device="cuda")
+        ctx.eggroll_update_i8(eb.make_key(0, 0, 0), eb.make_shape(0, N, 1, wl.d, wl.d, 1), wl.bound,
+                              torch.from_numpy(F).cuda(), tau, th, E)
+        torch.cuda.synchronize()
+        assert (E.cpu().numpy() == want_E).all()
+        assert (th.cpu().numpy() == want_t).all()
+        moved = (want_t != wl.W).mean()
+        assert 0.1 < moved < 0.3, moved   # "alpha approximately equals the fraction of parameters that are updated"

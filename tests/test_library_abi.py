@@ -36,6 +36,13 @@ def test_host_only_entry_points():
     assert abs(eb.eggroll_default_scale(16, 0.5, 4) - 1.0 / (16 * 0.5 * 2.0)) < 1e-12
 
 
+def test_int_threshold_helper_matches_the_oracle():
+    import oracle
+    for alpha in (1.0, 0.9, 0.5, 0.3173, 0.1, 0.05, 1e-3, 1e-9, 0.0):
+        for n, std in ((4096, 16.0), (8192, 24.0 ** 0.5), (1, 1.0), (10 ** 6, 16.0)):
+            assert eb.eggroll_int_threshold(alpha, n, std) == oracle.int_threshold(alpha, n, std), (alpha, n, std)
+
+
 def test_product_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_2511_16652_amd")
     for dirpath, _, files in os.walk(pkg):
