@@ -61,7 +61,15 @@ typedef struct {
     int32_t rows_per_member;  /* S: rows of X per member (tokens evaluated by a member)  */
     int32_t d_out, d_in;      /* M is d_out x d_in                                       */
     int32_t rank;             /* r in {1,2,4,8}                                          */
+    int32_t antithetic;       /* forward passes only: 1 = members 2p, 2p+1 form pair p    */
 } egg_shape;
+
+/* Antithetic pairs (App. "Fitness Shaping": "antithetical pair"; used by the integer and quantised
+   experiments).  With antithetic = 1 the two members of pair p = member/2 share the factors of noise
+   id p and are evaluated at M + sigma E_p (even member) and M - sigma E_p (odd member); in the integer
+   form the odd member uses (A_p, -B_p).  member_begin and member_count still count members and must
+   be even; A_cache / B_cache then hold member_count/2 entries.  The update entry points take the pair
+   view instead: member ids = pair ids, one fitness value per pair (antithetic must be 0 there). */
 
 /* Context.  `device`: HIP device ordinal; `hip_stream`: a hipStream_t (NULL = default stream).
    Host pointers.  Destroy synchronises the stream and frees the scratch. */

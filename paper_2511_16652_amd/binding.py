@@ -30,7 +30,7 @@ class EggKey(ctypes.Structure):
 class EggShape(ctypes.Structure):
     _fields_ = [("member_begin", ctypes.c_int64), ("member_count", ctypes.c_int64),
                 ("rows_per_member", ctypes.c_int32), ("d_out", ctypes.c_int32),
-                ("d_in", ctypes.c_int32), ("rank", ctypes.c_int32)]
+                ("d_in", ctypes.c_int32), ("rank", ctypes.c_int32), ("antithetic", ctypes.c_int32)]
 
 
 class EggrollError(RuntimeError):
@@ -184,5 +184,5 @@ def make_key(seed: int, step: int, layer: int) -> EggKey:
     return EggKey(seed, step, layer)
 
 
-def make_shape(member_begin, member_count, rows_per_member, d_out, d_in, rank) -> EggShape:
-    return EggShape(member_begin, member_count, rows_per_member, d_out, d_in, rank)
+def make_shape(member_begin, member_count, rows_per_member, d_out, d_in, rank, antithetic=0) -> EggShape:
+    return EggShape(member_begin, member_count, rows_per_member, d_out, d_in, rank, int(antithetic))

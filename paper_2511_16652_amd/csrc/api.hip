@@ -73,7 +73,8 @@ KernelScope::~KernelScope()
     c->recs.push_back({name, a, b});
 }
 
-egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows)
+// forward_pass: the entry point understands antithetic pairs (the others take pair ids as member ids)
+egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bool forward_pass)
 {
     if (!s) return fail(c, EGG_EINVAL, "shape is NULL");
     if (s->member_count <= 0 || s->d_out <= 0 || s->d_in <= 0) return fail(c, EGG_EINVAL, "non-positive size");
@@ -82,6 +83,11 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows)
         return fail(c, EGG_EINVAL, "rank %d not in {1,2,4,8}", s->rank);
     if (s->member_begin < 0 || s->member_begin + s->member_count > (int64_t(1) << 32))
         return fail(c, EGG_EINVAL, "member ids must lie in [0, 2^32)");
+    if (s->antithetic != 0 && s->antithetic != 1) return fail(c, EGG_EINVAL, "antithetic must be 0 or 1");
+    if (s->antithetic && !forward_pass)
+        return fail(c, EGG_EINVAL, "antithetic applies to the forward passes; pass pair ids as member ids here");
+    if (s->antithetic && ((s->member_begin | s->member_count) & 1))
+        return fail(c, EGG_EINVAL, "antithetic pairs need an even member_begin and member_count");
     return EGG_OK;
 }
 
@@ -155,7 +161,7 @@ egg_status eggroll_noise_gen(eggroll_ctx* c, egg_key key, const egg_shape* shape
                              int int_bound, void* A_out, void* B_out)
 {
     if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, false);
+    egg_status s = validate_shape(c, shape, false, false);
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     const bool ok = (dist == EGG_NORMAL && (dtype == EGG_F32 || dtype == EGG_BF16)) ||
@@ -182,7 +188,7 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* c, egg_key key, const egg_shap
                                      void* Y, void* A_cache, void* B_cache)
 {
     if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, true);
+    egg_status s = validate_shape(c, shape, true, true);
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     if (!W || !X || !Y) return fail(c, EGG_EINVAL, "W, X, Y must be non-NULL");
@@ -219,7 +225,7 @@ egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_s
                                         int8_t* H_out)
 {
     if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, false);
+    egg_status s = validate_shape(c, shape, false, true);
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     if (!W || !H_in || !H_out) return fail(c, EGG_EINVAL, "W, H_in, H_out must be non-NULL");
@@ -245,7 +251,7 @@ egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, e
                           float lr, const void* A_cache, const void* B_cache)
 {
     if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, false);
+    egg_status s = validate_shape(c, shape, false, false);
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     if (!fitness || !G) return fail(c, EGG_EINVAL, "fitness and G must be non-NULL");
@@ -265,7 +271,7 @@ egg_status eggroll_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape
                              int32_t threshold, int8_t* theta, int32_t* E_out)
 {
     if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, false);
+    egg_status s = validate_shape(c, shape, false, false);
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     if (!fitness || !theta) return fail(c, EGG_EINVAL, "fitness and theta must be non-NULL");

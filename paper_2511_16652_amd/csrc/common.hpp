@@ -59,7 +59,7 @@ struct KernelScope {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows);
+egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bool forward_pass);
 
 // entry points implemented per translation unit (kernel launchers)
 egg_status launch_noise(eggroll_ctx* c, const StreamKey& k, uint32_t member_begin, int64_t members, int64_t n,

@@ -287,10 +287,13 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     typedef FwdEpi<BF16, RANK, REGEN> Epi;
     const int esz = BF16 ? 2 : 4;
     const int64_t R = s.member_count * (int64_t)s.rows_per_member;
+    // antithetic pairs: the epilogue sees pairs as members of 2S rows (noise id = row / 2S); the sign of
+    // the odd member is already folded into its projections t
+    const int anti = s.antithetic ? 2 : 1;
     Operand P{(const char*)W, (int64_t)s.d_in * esz, 16, s.d_out};
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
-    typename Epi::Args ea{ka, (uint32_t)s.member_begin, s.rows_per_member, s.d_out, sigma / sqrtf((float)s.rank),
+    typename Epi::Args ea{ka, (uint32_t)(s.member_begin / anti), s.rows_per_member * anti, s.d_out, sigma / sqrtf((float)s.rank),
                           (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
@@ -309,19 +312,21 @@ egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_sh
 {
     const bool bf = io == EGG_BF16;
     // rank 1 with one row per member (or the unperturbed pass): regenerate in the epilogue
-    if (sigma == 0.f || (s.rank == 1 && s.rows_per_member == 1)) {
+    // (with antithetic pairs a kept cache has one entry per pair, not per row: that goes the materialised way)
+    if (sigma == 0.f || (s.rank == 1 && s.rows_per_member == 1 && !(s.antithetic && A_cache))) {
         return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache)
                   : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache);
     }
     // otherwise materialise A once (into the caller's cache if there is one) and read it back
     void* A_buf = A_cache;
+    const int anti = s.antithetic ? 2 : 1;  // one set of factors per pair
     if (!A_buf) {
-        const size_t bytes = (size_t)s.member_count * s.d_out * s.rank * (bf ? 2 : 4);
+        const size_t bytes = (size_t)(s.member_count / anti) * s.d_out * s.rank * (bf ? 2 : 4);
         egg_status st = reserve(c, c->a_buf, bytes);
         if (st != EGG_OK) return st;
         A_buf = c->a_buf.p;
     }
-    egg_status st = launch_noise(c, ka, (uint32_t)s.member_begin, s.member_count, (int64_t)s.d_out * s.rank, io,
+    egg_status st = launch_noise(c, ka, (uint32_t)(s.member_begin / anti), s.member_count / anti, (int64_t)s.d_out * s.rank, io,
                                  EGG_NORMAL, 0, A_buf);
     if (st != EGG_OK) return st;
 #define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf)

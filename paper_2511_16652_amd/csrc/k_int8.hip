@@ -13,14 +13,15 @@
 namespace egg {
 
 // dots[row] = sum_k H[row][k] * B[row][k]   (int8 x int8 -> int32), one wave per row
+// anti: rows 2p, 2p+1 share the factors of pair p, and the odd row uses -B_p
 __global__ __launch_bounds__(256) void dot_i8_kernel(const int8_t* __restrict__ H, const int8_t* __restrict__ B,
-                                                     int64_t rows, int d, int* __restrict__ dots)
+                                                     int64_t rows, int d, int anti, int* __restrict__ dots)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const u32x4* h = (const u32x4*)(H + row * d);
-    const u32x4* b = (const u32x4*)(B + row * d);
+    const u32x4* b = (const u32x4*)(B + (anti ? row >> 1 : row) * d);
     int acc = 0;
     for (int ch = lane; ch < (d >> 4); ch += 64) {
         const u32x4 hv = h[ch], bv = b[ch];
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(256) void dot_i8_kernel(const int8_t* __restrict__ 
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) dots[row] = acc;
+    if (lane == 0) dots[row] = (anti && (row & 1)) ? -acc : acc;
 }
 
 __global__ __launch_bounds__(256) void zero_i32_kernel(int* __restrict__ p, int64_t n)
@@ -61,6 +62,7 @@ struct I8Args {
     int* dots_next;   // [rows]  accumulates u' . B for the next step (zeroed by the host), or NULL
     int8_t* H_out;    // [rows][d]
     int d, corr_shift, out_shift;
+    int anti;  // antithetic pairs: rows 2p, 2p+1 read the factors of pair p; the odd row uses -B_p
 };
 
 template <bool DOT24>
@@ -100,7 +102,7 @@ struct I8Epi {
         pass_coords<WTM>(it, row, mc);
         const int n = min(nb0 + row, n_rows - 1);
         const int m = min(mw0 + mc, a.d - 16);
-        const int64_t off = (int64_t)n * a.d + m;
+        const int64_t off = (int64_t)(a.anti ? n >> 1 : n) * a.d + m;
         av = *(const u32x4*)(a.A + off);
         if (a.dots_next) bv = *(const u32x4*)(a.B + off);
         else bv = u32x4{0u, 0u, 0u, 0u};
@@ -158,6 +160,7 @@ struct I8Epi {
         if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
         if (a.dots_next) {
             if (!ok) part = 0;
+            if (a.anti && (n & 1)) part = -part;  // h' . (-B_p)
 #pragma unroll
             for (int off = 1; off < CPR; off <<= 1) part += __shfl_xor(part, off, 64);
             if (mc == 0 && n < n_rows) atomicAdd(a.dots_next + n, part);
@@ -212,6 +215,9 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
 {
     const int d = s.d_in;
     const int64_t rows = s.member_count;
+    const int anti = s.antithetic ? 1 : 0;
+    const int64_t noise_ids = anti ? rows / 2 : rows;
+    const uint32_t first_id = (uint32_t)(anti ? s.member_begin / 2 : s.member_begin);
     const size_t hbytes = (size_t)rows * d;
     egg_status st;
     if ((st = reserve(c, c->i8_a, hbytes)) != EGG_OK) return st;
@@ -226,8 +232,8 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
     int8_t* scratch[2] = {(int8_t*)c->i8_h.p, (int8_t*)c->i8_h.p + ((hbytes + 255) & ~size_t(255))};
     char* dots_base = (char*)c->t_buf.p;
 
-    if ((st = launch_noise(c, ka, (uint32_t)s.member_begin, rows, d, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
-    if ((st = launch_noise(c, kb, (uint32_t)s.member_begin, rows, d, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
+    if ((st = launch_noise(c, ka, first_id, noise_ids, d, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
+    if ((st = launch_noise(c, kb, first_id, noise_ids, d, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
     {   // a fill kernel rather than a memset node, so that the call can sit inside a captured graph
         const int64_t nz = (int64_t)(dot_row / sizeof(int)) * (steps + 1);
         KernelScope ks(c, "zero_dots");
@@ -235,7 +241,7 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
     }
     {
         KernelScope ks(c, "dot_i8");
-        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, H_in, B, rows, d, (int*)dots_base);
+        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, H_in, B, rows, d, anti, (int*)dots_base);
     }
     if ((st = check_hip(c, hipGetLastError(), "dot_i8 launch")) != EGG_OK) return st;
 
@@ -250,7 +256,7 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
         Operand P{(const char*)W, (int64_t)d, 16, d};
         Operand Q{(const char*)src, (int64_t)d, 16, (int)rows};
         I8Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
-                       dst, d, corr_shift, out_shift};
+                       dst, d, corr_shift, out_shift, anti};
         if (big_tiles >= 192)
             st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d / 16, ea);
         else

@@ -3,12 +3,13 @@
 // intermediate of the arithmetic-intensity appendix).  One workgroup per member: B_i is regenerated
 // once into LDS (and optionally kept in the caller's cache), then the member's S rows are streamed
 // against it, one wave per row.  HBM-bound on X for large S, integer-ALU bound (noise) for S = 1.
+// With antithetic pairs a workgroup owns a pair: the factors are generated once for its 2S rows.
 #include "common.hpp"
 
 namespace egg {
 
 template <bool BF16, int RANK>
-__global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int d_in,
+__global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int anti_rows, int d_in,
                                                       const void* __restrict__ X, float* __restrict__ t,
                                                       void* __restrict__ B_cache)
 {
@@ -87,7 +88,9 @@ __global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t mem
             float v = acc[l];
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-            if (lane == 0) t[row * RANK + l] = v;
+            // antithetic pairs: the workgroup owns both members of a pair (2 x anti_rows rows); the second
+            // member is evaluated at -sigma, which is folded into its projections
+            if (lane == 0) t[row * RANK + l] = (anti_rows && s >= anti_rows) ? -v : v;
         }
     }
 }
@@ -132,9 +135,16 @@ __global__ __launch_bounds__(256) void project_row_kernel(StreamKey kb, uint32_t
 }
 
 template <bool BF16>
-static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, const void* X, float* t,
+static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const egg_shape& shape, const void* X, float* t,
                                    void* B_cache)
 {
+    egg_shape s = shape;  // the noise view: pairs as members of 2S rows when antithetic
+    const int anti_rows = shape.antithetic ? shape.rows_per_member : 0;
+    if (shape.antithetic) {
+        s.member_begin /= 2;
+        s.member_count /= 2;
+        s.rows_per_member *= 2;
+    }
     const size_t lds = (size_t)s.d_in * s.rank * (BF16 ? 2 : 4);
     if (lds > 128 * 1024) return fail(c, EGG_EUNSUPPORTED, "d_in * rank = %lld too large for the projection pass", (long long)s.d_in * s.rank);
     const dim3 g((unsigned)s.member_count), b(256);
@@ -153,7 +163,7 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
             if (st != EGG_OK) return st;                                                                             \
         }                                                                                                            \
         KernelScope ks(c, "project");                                                                                \
-        hipLaunchKernelGGL(kern, g, b, lds, c->stream, kb, mb, s.rows_per_member, s.d_in, X, t, B_cache);            \
+        hipLaunchKernelGGL(kern, g, b, lds, c->stream, kb, mb, s.rows_per_member, anti_rows, s.d_in, X, t, B_cache);            \
     }
     switch (s.rank) {
         case 1: EGG_LAUNCH_PROJECT(1) break;
