@@ -162,6 +162,30 @@ def linear_workload(args):
     t_upd = timed(update, args.steps, args.warmup)
     t_mm = timed(torch_mm, args.steps, args.warmup)
 
+    # the same population as antithetic pairs (App. "Fitness Shaping"): members 2p, 2p+1 share the factors
+    # of pair p, the update contracts over N/2 pairs with one fitness value per pair.  Reported beside the
+    # headline, never as `value`.
+    anti = None
+    if wl.N % 2 == 0:
+        shape_a = eb.make_shape(0, wl.N, wl.S, wl.d_out, wl.d_in, wl.rank, antithetic=1)
+        shape_p = eb.make_shape(0, wl.N // 2, 1, wl.d_out, wl.d_in, wl.rank)
+        fit_p = (fit[0::2] - fit[1::2]).contiguous()
+        scale_p = eb.eggroll_default_scale(wl.N // 2, wl.sigma, wl.rank)
+
+        def forward_a():
+            ctx.eggroll_perturbed_forward(key, shape_a, wl.sigma, eb.EGG_ACT_NONE, W, X, Y, None, None)
+
+        def update_a():
+            ctx.eggroll_update(key, shape_p, code, fit_p, scale_p, 0, G, None, 0.0, None, None)
+
+        def step_a():
+            forward_a()
+            update_a()
+
+        prewarm(step_a, 0.2)
+        ta, tfa, tua = (timed(f, args.steps, args.warmup) for f in (step_a, forward_a, update_a))
+        anti = {"ms_per_step": 1e3 * ta, "tokens_per_s": R / ta, "ms": {"forward": 1e3 * tfa, "update": 1e3 * tua}}
+
     # per-kernel durations of the same step, HIP events on the library's stream
     ctx.profile_enable(True)
     for _ in range(args.steps):
@@ -204,6 +228,8 @@ def linear_workload(args):
                             "unit": "TFLOP/s", "frac": upd_tflops / peak},
         "kernels": kernels,
     }
+    if anti:
+        out["antithetic_pairs"] = anti
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_linear(wl)
     ctx.close()

@@ -29,6 +29,7 @@ struct FwdEpi {
         int wtm_pitch;  // RowStager2B::pitch of the launched wave tile
         int stage_a;    // !REGEN: the tile's slice of A fits the LDS tail and is staged there
         int mma_corr;   // !REGEN, bf16, S % 32 == 0: the correction is folded in by one extra MFMA per block
+        int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
     };
     static constexpr int A_STAGE_BYTES = 48 * 1024;
     static constexpr bool REGEN_MODE = REGEN;
@@ -185,14 +186,37 @@ struct FwdEpi {
             if constexpr (REGEN) {
                 static_assert(RANK == 1, "in-register regeneration is the rank-1 path");
                 const uint32_t blk0 = (uint32_t)m >> 1;
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                uint32_t p0 = 0, p1 = 0;  // bf16: the four factors as two packed words
+                if (a.pair_share) {
+                    // antithetic pairs, one row per member: lanes n and n ^ 1 hold the two rows of one pair and
+                    // need the same four factors, so each generates one of the two Threefry blocks and they swap
+                    const int b = sty.lane & 1;
                     uint32_t w0, w1;
                     noise_words(a.ka, member, blk0 + b, w0, w1);
-                    normal_pair<!BF16>(w0, w1, z[2 * b], z[2 * b + 1]);
+                    float o0, o1;
+                    normal_pair<!BF16>(w0, w1, o0, o1);
+                    if constexpr (BF16) {
+                        const uint32_t own = pack_bf16x2(o0, o1), oth = __shfl_xor(own, 1, 64);
+                        p0 = b ? oth : own;
+                        p1 = b ? own : oth;
+                    } else {
+                        const float x0 = __shfl_xor(o0, 1, 64), x1 = __shfl_xor(o1, 1, 64);
+                        z[0] = b ? x0 : o0; z[1] = b ? x1 : o1;
+                        z[2] = b ? o0 : x0; z[3] = b ? o1 : x1;
+                    }
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+                        uint32_t w0, w1;
+                        noise_words(a.ka, member, blk0 + b, w0, w1);
+                        normal_pair<!BF16>(w0, w1, z[2 * b], z[2 * b + 1]);
+                    }
+                    if constexpr (BF16) {
+                        p0 = pack_bf16x2(z[0], z[1]);
+                        p1 = pack_bf16x2(z[2], z[3]);
+                    }
                 }
                 if constexpr (BF16) {
-                    const uint32_t p0 = pack_bf16x2(z[0], z[1]), p1 = pack_bf16x2(z[2], z[3]);
                     z[0] = bf16_lo(p0); z[1] = bf16_hi(p0);
                     z[2] = bf16_lo(p1); z[3] = bf16_hi(p1);
                     if (a.A_buf) sta.put(a.wtm_pitch, ml, p0, p1);
@@ -294,7 +318,7 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
     typename Epi::Args ea{ka, (uint32_t)(s.member_begin / anti), s.rows_per_member * anti, s.d_out, sigma / sqrtf((float)s.rank),
-                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0};
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0, (REGEN && s.antithetic) ? 1 : 0};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
