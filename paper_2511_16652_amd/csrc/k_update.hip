@@ -143,6 +143,51 @@ __global__ __launch_bounds__(256) void pack_r1_kernel(const void* __restrict__ s
     }
 }
 
+// Rank-1 bf16 factors without caches: regenerate straight into the K-packed fp16 panel.  A thread owns
+// one column pair (2jp, 2jp+1) of 8 consecutive members -- eight Threefry blocks, the same (member,
+// block) addressing every other kernel uses -- and writes the two finished 16-byte chunks, which are
+// neighbours in the panel: no [member][d] intermediate is written or re-read.
+__global__ __launch_bounds__(256) void gen_pack_r1_kernel(StreamKey key, uint32_t member_begin, const float* __restrict__ fitness,
+                                                          const float* __restrict__ fnorm, int64_t members, int d,
+                                                          int64_t kgroups, u32x4* __restrict__ out)
+{
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const int pairs = d >> 1;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= kgroups * pairs) return;
+    const int64_t kg = gid / pairs;
+    const int jp = (int)(gid - kg * pairs);
+    const float finv = fitness ? fnorm[1] : 1.f;
+    float lo[8], hi[8];  // columns 2jp and 2jp+1 of the 8 members
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int64_t i = kg * 8 + e;
+        lo[e] = hi[e] = 0.f;
+        if (i < members) {
+            uint32_t w0, w1;
+            noise_words(key, member_begin + (uint32_t)i, (uint32_t)jp, w0, w1);
+            float z0, z1;
+            normal_pair<false>(w0, w1, z0, z1);
+            const uint32_t pk = pack_bf16x2(z0, z1);  // the factors are bf16 values
+            const float fs = fitness ? fitness[i] * finv : 1.f;
+            lo[e] = bf16_lo(pk) * fs;
+            hi[e] = bf16_hi(pk) * fs;
+        }
+    }
+    u32x4 c0, c1;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        h2 p, q;
+        p[0] = (_Float16)lo[2 * w]; p[1] = (_Float16)lo[2 * w + 1];  // round to nearest even
+        q[0] = (_Float16)hi[2 * w]; q[1] = (_Float16)hi[2 * w + 1];
+        c0[w] = __builtin_bit_cast(uint32_t, p);
+        c1[w] = __builtin_bit_cast(uint32_t, q);
+    }
+    u32x4* o = out + kg * d + 2 * jp;
+    o[0] = c0;
+    o[1] = c1;
+}
+
 struct UpdEpi {
     typedef float value_t;
     struct Args {
@@ -218,9 +263,11 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
     egg_status st;
 
     // factors in [member][d][r] layout: the caller's caches, or regenerated into scratch
+    // (rank-1 bf16 without caches regenerates straight into the packed panels instead)
+    const bool gen_packed = !A_cache && bf && s.rank == 1 && s.d_out % 2 == 0 && s.d_in % 2 == 0;
     const void* A_src = A_cache;
     const void* B_src = B_cache;
-    if (!A_src) {
+    if (!A_src && !gen_packed) {
         const size_t na = (size_t)s.member_count * s.d_out * s.rank * esz, nb = (size_t)s.member_count * s.d_in * s.rank * esz;
         if ((st = reserve(c, c->a_buf, na)) != EGG_OK) return st;
         if ((st = reserve(c, c->b_buf, nb)) != EGG_OK) return st;
@@ -255,8 +302,18 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
                 else hipLaunchKernelGGL(pack_kernel<false>, g, b, 0, c->stream, src, fit, fnorm, s.member_count, d, s.rank, kgroups, dst);
             }
         };
-        pack(A_src, fitness, s.d_out, c->pack_a.p);
-        pack(B_src, nullptr, s.d_in, c->pack_b.p);
+        auto gen_pack = [&](const StreamKey& k, const float* fit, int d, void* dst) {
+            const int64_t n = kgroups * (d / 2);
+            hipLaunchKernelGGL(gen_pack_r1_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, k,
+                               (uint32_t)s.member_begin, fit, fnorm, s.member_count, d, kgroups, (u32x4*)dst);
+        };
+        if (gen_packed) {
+            gen_pack(ka, fitness, s.d_out, c->pack_a.p);
+            gen_pack(kb, nullptr, s.d_in, c->pack_b.p);
+        } else {
+            pack(A_src, fitness, s.d_out, c->pack_a.p);
+            pack(B_src, nullptr, s.d_in, c->pack_b.p);
+        }
         if ((st = check_hip(c, hipGetLastError(), "pack launch")) != EGG_OK) return st;
     }
 
