@@ -97,8 +97,9 @@ def linear_workload(args):
 
     if args.workload == "cfg1":
         wl = inputs.config1()
-    elif args.workload == "p0":   # the paper's own speed benchmark shape: bf16 8192x8192, batch 1024
-        wl = inputs.make_linear("p0_bf16_8192_N1024", "bf16", 8192, 8192, 1024, 1, 1, 1e-3, 1100)
+    elif args.workload.startswith("p0"):   # the paper's own speed benchmark shape: bf16 8192x8192, batch 1024
+        rank = int(args.workload[4:]) if args.workload.startswith("p0_r") else 1   # p0_r2, p0_r4, p0_r8: rank sweep
+        wl = inputs.make_linear("p0_bf16_8192_N1024_r%d" % rank, "bf16", 8192, 8192, 1024, 1, rank, 1e-3, 1100)
     elif args.workload in ("mlp_up", "mlp_down", "ffn_up", "attn_proj"):
         # single layers of the MLP-stack / decoder configurations at full population; inputs are drawn
         # on the device (too large to stage through the host), so these lines have no oracle leg

@@ -324,6 +324,12 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
         if (big_tiles >= 192) {
             return launch_gemm<MmaBf16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
         }
+        // few rows against a large layer (the paper's own benchmark shape, batch 1024 on 8192 x 8192): tall
+        // tiles keep one workgroup per CU busy where 256 x 256 tiles would leave half the chip idle
+        const int64_t tall_tiles = ((s.d_out + 255) / 256) * ((R + 127) / 128);
+        if (tall_tiles >= 192) {
+            return launch_gemm<MmaBf16, 256, 128, 4, 2, Epi>(c, "forward_gemm_bf16_tall", P, Q, kchunks, ea);
+        }
         return launch_gemm<MmaBf16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
     } else {
         return launch_gemm<MmaF32, 128, 128, 2, 2, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);

@@ -116,6 +116,10 @@ def test_config3_full_size_integer_recurrence(ctx):
     ("mlp_down", 2048, 8192, 512, 64, 4, eb.EGG_ACT_NONE),        # config 4, W2
     ("decoder_ffn_up", 8192, 2048, 256, 256, 1, eb.EGG_ACT_GELU),  # config 5 ffn-up: 256 tokens per member
     ("decoder_attn_proj", 2048, 2048, 512, 256, 1, eb.EGG_ACT_NONE),
+    # few rows against a tall layer, like the paper's own speed benchmark (batch 1024 on 8192 x 8192): the
+    # 256 x 128 tile route, regenerating epilogue; and a ragged rank-2 case on the same route
+    ("paper_bench_tall", 8192, 1024, 1000, 1, 1, eb.EGG_ACT_NONE),
+    ("tall_ragged_r2", 6280, 520, 1001, 1, 2, eb.EGG_ACT_NONE),
 ])
 def test_layer_shapes_of_configs_4_and_5(ctx, name, d_out, d_in, N, S, r, act):
     """Real layer shapes of the MLP-stack and decoder configurations at a reduced population: forward
