@@ -73,6 +73,8 @@ def _load():
         lib.oracle_forward_antithetic.restype = i32
         lib.oracle_forward_i8_antithetic.argtypes = lib.oracle_forward_i8.argtypes
         lib.oracle_forward_i8_antithetic.restype = None
+        lib.oracle_matmul_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+        lib.oracle_matmul_i8.restype = None
         lib.oracle_update_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         lib.oracle_update_i8.restype = i32
         lib.oracle_int_threshold.argtypes = [dbl, i64, dbl]
@@ -191,6 +193,18 @@ def forward_i8(seed, step, layer, member_begin, member_count, d, bound, corr_shi
     fn = _load().oracle_forward_i8_antithetic if antithetic else _load().oracle_forward_i8
     fn(seed, step, layer, member_begin, member_count, d, bound, corr_shift,
                               out_shift, steps, _ptr(W), _ptr(H), _ptr(out))
+    return out
+
+
+def matmul_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, corr_shift, out_shift,
+              W, H_in, antithetic=False) -> np.ndarray:
+    """One perturbed integer matmul with a rectangular theta [d_out, d_in]: int8 [count, d_in] -> [count, d_out]."""
+    W = _c(W, np.int8)
+    H = _c(H_in, np.int8)
+    assert W.shape == (d_out, d_in) and H.shape == (member_count, d_in)
+    out = np.empty((member_count, d_out), np.int8)
+    _load().oracle_matmul_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, corr_shift,
+                             out_shift, int(bool(antithetic)), _ptr(W), _ptr(H), _ptr(out))
     return out
 
 

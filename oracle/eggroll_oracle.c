@@ -345,41 +345,43 @@ static int32_t shr_floor(int64_t v, int s) /* arithmetic shift: floor(v / 2^s) *
  * rank 1, square W (d x d), noise on {-bound..bound}.  H_in/H_out: [count][d].
  */
 static void forward_i8_worker(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin,
-                              int64_t member_count, int d, int bound, int corr_shift, int out_shift,
+                              int64_t member_count, int d_out, int d_in, int bound, int corr_shift, int out_shift,
                               int steps, int antithetic, const int8_t* W, const int8_t* H_in, int8_t* H_out)
 {
+    /* theta is d_out x d_in ("m x n"); more than one step feeds h' back in and needs d_out == d_in */
+    const int dmax = d_out > d_in ? d_out : d_in;
 #pragma omp parallel
     {
-        int8_t* A = (int8_t*)malloc((size_t)d);
-        int8_t* B = (int8_t*)malloc((size_t)d);
-        int32_t* h = (int32_t*)malloc(sizeof(int32_t) * (size_t)d);
-        int32_t* hn = (int32_t*)malloc(sizeof(int32_t) * (size_t)d);
+        int8_t* A = (int8_t*)malloc((size_t)d_out);
+        int8_t* B = (int8_t*)malloc((size_t)d_in);
+        int32_t* h = (int32_t*)malloc(sizeof(int32_t) * (size_t)dmax);
+        int32_t* hn = (int32_t*)malloc(sizeof(int32_t) * (size_t)dmax);
 #pragma omp for schedule(dynamic, 4)
         for (int64_t m = 0; m < member_count; ++m) {
             const int64_t member = member_begin + m;
             const int64_t noise_id = antithetic ? member / 2 : member;
-            oracle_noise_int(seed, step, layer, 0, noise_id, 0, (uint64_t)d, bound, A);
-            oracle_noise_int(seed, step, layer, 1, noise_id, 0, (uint64_t)d, bound, B);
+            oracle_noise_int(seed, step, layer, 0, noise_id, 0, (uint64_t)d_out, bound, A);
+            oracle_noise_int(seed, step, layer, 1, noise_id, 0, (uint64_t)d_in, bound, B);
             /* the negative member of a pair carries the perturbation A (-B)^T: one formula for both signs */
             if (antithetic && (member & 1))
-                for (int k = 0; k < d; ++k) B[k] = (int8_t)(-B[k]);
-            for (int k = 0; k < d; ++k) h[k] = H_in[(size_t)m * d + k];
+                for (int k = 0; k < d_in; ++k) B[k] = (int8_t)(-B[k]);
+            for (int k = 0; k < d_in; ++k) h[k] = H_in[(size_t)m * d_in + k];
             for (int t = 0; t < steps; ++t) {
                 int32_t dot = 0;
-                for (int k = 0; k < d; ++k) dot += h[k] * (int32_t)B[k];
-                for (int j = 0; j < d; ++j) {
+                for (int k = 0; k < d_in; ++k) dot += h[k] * (int32_t)B[k];
+                for (int j = 0; j < d_out; ++j) {
                     int32_t acc = 0;
-                    const int8_t* w = W + (size_t)j * d;
-                    for (int k = 0; k < d; ++k) acc += h[k] * (int32_t)w[k];
+                    const int8_t* w = W + (size_t)j * d_in;
+                    for (int k = 0; k < d_in; ++k) acc += h[k] * (int32_t)w[k];
                     const int32_t corr = shr_floor((int64_t)dot * (int64_t)A[j], corr_shift);
                     int32_t v = shr_floor((int64_t)acc + (int64_t)corr, out_shift);
                     if (v > 127) v = 127;
                     if (v < -127) v = -127;
                     hn[j] = v;
                 }
-                for (int k = 0; k < d; ++k) h[k] = hn[k];
+                for (int k = 0; k < d_out; ++k) h[k] = hn[k];
             }
-            for (int k = 0; k < d; ++k) H_out[(size_t)m * d + k] = (int8_t)h[k];
+            for (int k = 0; k < d_out; ++k) H_out[(size_t)m * d_out + k] = (int8_t)h[k];
         }
         free(A); free(B); free(h); free(hn);
     }
@@ -389,7 +391,7 @@ void oracle_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t mem
                        int64_t member_count, int d, int bound, int corr_shift, int out_shift,
                        int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
 {
-    forward_i8_worker(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift, steps, 0,
+    forward_i8_worker(seed, step, layer, member_begin, member_count, d, d, bound, corr_shift, out_shift, steps, 0,
                       W, H_in, H_out);
 }
 
@@ -398,8 +400,17 @@ void oracle_forward_i8_antithetic(uint64_t seed, uint32_t step, uint32_t layer, 
                                   int64_t member_count, int d, int bound, int corr_shift, int out_shift,
                                   int steps, const int8_t* W, const int8_t* H_in, int8_t* H_out)
 {
-    forward_i8_worker(seed, step, layer, member_begin, member_count, d, bound, corr_shift, out_shift, steps, 1,
+    forward_i8_worker(seed, step, layer, member_begin, member_count, d, d, bound, corr_shift, out_shift, steps, 1,
                       W, H_in, H_out);
+}
+
+/* one application of a rectangular theta (d_out x d_in), e.g. the 4D x D and D x 4D matrices of the integer MLP */
+void oracle_matmul_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin, int64_t member_count,
+                      int d_out, int d_in, int bound, int corr_shift, int out_shift, int antithetic,
+                      const int8_t* W, const int8_t* H_in, int8_t* H_out)
+{
+    forward_i8_worker(seed, step, layer, member_begin, member_count, d_out, d_in, bound, corr_shift, out_shift, 1,
+                      antithetic, W, H_in, H_out);
 }
 
 /* ------------------------------------------------------------------------------------------ */

@@ -182,3 +182,20 @@ def test_antithetic_integer_recurrence_over_steps_matches_single_steps():
     for _ in range(3):
         h = oracle.forward_i8(SEED, STEP, LAYER, 0, 2 * pairs, d, bound, 3, 5, 1, W, h, antithetic=True)
     assert (three == h).all()
+
+
+@pytest.mark.parametrize("d_out,d_in", [(48, 12), (12, 48), (20, 20)])
+def test_rectangular_integer_matmul_follows_the_printed_formula(d_out, d_in):
+    # theta in I8^{m x n}: I8((u theta^T + ((u . B) I32(A) >> s_c)) >> s_o) with A in I8^m, B in I8^n
+    N, bound, cs, os_ = 7, 8, 3, 5
+    rng = np.random.default_rng(d_out)
+    W = rng.integers(-127, 128, (d_out, d_in)).astype(np.int8)
+    H = rng.integers(-127, 128, (N, d_in)).astype(np.int8)
+    got = oracle.matmul_i8(SEED, STEP, LAYER, 2, N, d_out, d_in, bound, cs, os_, W, H)
+    for m in range(N):
+        A, B = int_factors(2 + m, d_out, d_in, bound)
+        h = H[m].astype(np.int64)
+        want = np.clip((W.astype(np.int64) @ h + (((h @ B) * A) >> cs)) >> os_, -127, 127)
+        assert (got[m] == want).all()
+    if d_out == d_in:   # the square case is the recurrence's single step
+        assert (got == oracle.forward_i8(SEED, STEP, LAYER, 2, N, d_in, bound, cs, os_, 1, W, H)).all()
