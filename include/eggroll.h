@@ -111,12 +111,14 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* ctx, egg_key key, const egg_sh
                                      const void* W, const void* X, void* Y, void* A_cache, void* B_cache);
 
 /*
- * (2') Integer form (App. "Matrix Multiplication", "Adding EGGROLL Perturbations"), rank 1, square
- * W[d][d] int8 (d = d_out = d_in, multiple of 16), one row per member, repeated `steps` times:
+ * (2') Integer form (App. "Matrix Multiplication", "Adding EGGROLL Perturbations"), rank 1, one row per
+ * member, W[d_out][d_in] int8 (both multiples of 16), applied `steps` times (steps > 1 feeds h' back in
+ * and needs d_out == d_in; one step with a rectangular W is the integer MLP's matmul):
  *   acc  = h W^T (int32);  dot = h . B_i (int32)
  *   h'_j = clamp( (acc_j + ((dot * int32(A_i[j])) >> corr_shift)) >> out_shift, -127, 127 )
- * Shifts are arithmetic (floor).  H_in, H_out: int8 [member_count][d]; may alias.  The factors are
- * integers on {-int_bound..int_bound}, fixed over the `steps` applications.  Bit-exact.
+ * Shifts are arithmetic (floor).  H_in: int8 [member_count][d_in], H_out: int8 [member_count][d_out]; they
+ * may alias when the matrix is square.  The factors are integers on {-int_bound..int_bound}, fixed over
+ * the `steps` applications.  Bit-exact.
  */
 egg_status eggroll_perturbed_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound,
                                         int corr_shift, int out_shift, int steps, const int8_t* W,

@@ -231,8 +231,9 @@ egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_s
     if (!W || !H_in || !H_out) return fail(c, EGG_EINVAL, "W, H_in, H_out must be non-NULL");
     if (!aligned16(W) || !aligned16(H_in) || !aligned16(H_out)) return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
     if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
-    if (shape->d_out != shape->d_in) return fail(c, EGG_EUNSUPPORTED, "integer recurrence needs a square matrix");
-    if (shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "d must be a multiple of 16");
+    if (shape->d_out != shape->d_in && steps > 1) return fail(c, EGG_EUNSUPPORTED, "more than one step needs a square matrix");
+    if (shape->d_out != shape->d_in && H_in == H_out) return fail(c, EGG_EINVAL, "H_in and H_out may alias only for a square matrix");
+    if (shape->d_in % 16 || shape->d_out % 16) return fail(c, EGG_EUNSUPPORTED, "d_out and d_in must be multiples of 16");
     if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
     if (corr_shift < 0 || corr_shift > 31 || out_shift < 0 || out_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
     if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");

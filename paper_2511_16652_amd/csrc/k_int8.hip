@@ -213,57 +213,58 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out)
 {
-    const int d = s.d_in;
+    const int d_in = s.d_in, d_out = s.d_out;  // more than one step feeds h' back in: the API checks d_out == d_in
     const int64_t rows = s.member_count;
     const int anti = s.antithetic ? 1 : 0;
     const int64_t noise_ids = anti ? rows / 2 : rows;
     const uint32_t first_id = (uint32_t)(anti ? s.member_begin / 2 : s.member_begin);
-    const size_t hbytes = (size_t)rows * d;
+    const size_t obytes = (size_t)rows * d_out;
     egg_status st;
-    if ((st = reserve(c, c->i8_a, hbytes)) != EGG_OK) return st;
-    if ((st = reserve(c, c->i8_b, hbytes)) != EGG_OK) return st;
-    if ((st = reserve(c, c->i8_h, 2 * ((hbytes + 255) & ~size_t(255)))) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_a, (size_t)noise_ids * d_out)) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_b, (size_t)noise_ids * d_in)) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_h, 2 * ((obytes + 255) & ~size_t(255)))) != EGG_OK) return st;
     // one row of dot products per step: step t reads row t (filled by the dot kernel for t = 0, by the
     // previous step's epilogue otherwise) and accumulates row t+1
     const size_t dot_row = ((size_t)rows * sizeof(int) + 255) & ~size_t(255);
     if ((st = reserve(c, c->t_buf, dot_row * (size_t)(steps + 1))) != EGG_OK) return st;
     int8_t* A = (int8_t*)c->i8_a.p;
     int8_t* B = (int8_t*)c->i8_b.p;
-    int8_t* scratch[2] = {(int8_t*)c->i8_h.p, (int8_t*)c->i8_h.p + ((hbytes + 255) & ~size_t(255))};
+    int8_t* scratch[2] = {(int8_t*)c->i8_h.p, (int8_t*)c->i8_h.p + ((obytes + 255) & ~size_t(255))};
     char* dots_base = (char*)c->t_buf.p;
 
-    if ((st = launch_noise(c, ka, first_id, noise_ids, d, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
-    if ((st = launch_noise(c, kb, first_id, noise_ids, d, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
-    {   // a fill kernel rather than a memset node, so that the call can sit inside a captured graph
+    if ((st = launch_noise(c, ka, first_id, noise_ids, d_out, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
+    if ((st = launch_noise(c, kb, first_id, noise_ids, d_in, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
+    if (steps > 1) {   // a fill kernel rather than a memset node, so that the call can sit inside a captured graph
         const int64_t nz = (int64_t)(dot_row / sizeof(int)) * (steps + 1);
         KernelScope ks(c, "zero_dots");
         hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, c->stream, (int*)dots_base, nz);
     }
     {
         KernelScope ks(c, "dot_i8");
-        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, H_in, B, rows, d, anti, (int*)dots_base);
+        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, H_in, B, rows, d_in, anti, (int*)dots_base);
     }
     if ((st = check_hip(c, hipGetLastError(), "dot_i8 launch")) != EGG_OK) return st;
 
-    const int64_t big_tiles = ((d + 255) / 256) * ((rows + 255) / 256);
-    // |u . B_i| <= d * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
-    const bool dot24 = (int64_t)d * 127 * int_bound < (int64_t(1) << 23);
+    const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
+    // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
+    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
     const int8_t* src = H_in;
     for (int t = 0; t < steps; ++t) {
         int8_t* dst = (t == steps - 1) ? H_out : scratch[t & 1];
         const bool alias = (dst == src);  // only possible for steps == 1 with H_out == H_in
         if (alias) dst = scratch[0];
-        Operand P{(const char*)W, (int64_t)d, 16, d};
-        Operand Q{(const char*)src, (int64_t)d, 16, (int)rows};
+        Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
+        Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
+        // the epilogue's row length is d_out (rows of A_i and of h'); with a next step d_out == d_in, so B_i fits too
         I8Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
-                       dst, d, corr_shift, out_shift, anti};
+                       dst, d_out, corr_shift, out_shift, anti};
         if (big_tiles >= 192)
-            st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d / 16, ea);
+            st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
         else
-            st = dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d / 16, ea);
+            st = dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
         if (st != EGG_OK) return st;
         if (alias) {
-            if ((st = check_hip(c, hipMemcpyAsync(H_out, dst, hbytes, hipMemcpyDeviceToDevice, c->stream), "copy back")) != EGG_OK) return st;
+            if ((st = check_hip(c, hipMemcpyAsync(H_out, dst, obytes, hipMemcpyDeviceToDevice, c->stream), "copy back")) != EGG_OK) return st;
         }
         src = dst;
     }

@@ -73,3 +73,23 @@ def test_int8_errors(ctx):
     with pytest.raises(eb.EggrollError) as e:
         ctx.eggroll_perturbed_forward_i8(eb.make_key(0, 0, 0), eb.make_shape(0, 4, 1, 24, 24, 1), 8, 4, 8, 1, W, H, H)
     assert e.value.status == eb.EGG_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("d_out,d_in,N,anti", [(1024, 256, 300, 0), (256, 1024, 130, 0), (48, 272, 70, 1), (2064, 64, 38, 1)])
+def test_rectangular_single_step_bit_exact(ctx, d_out, d_in, N, anti):
+    """One application of a d_out x d_in integer theta (the 4D x D and D x 4D matrices of the integer MLP)."""
+    import torch
+    rng = np.random.default_rng(d_out + d_in)
+    W = rng.integers(-20, 21, (d_out, d_in)).astype(np.int8)
+    H = rng.integers(-127, 128, (N, d_in)).astype(np.int8)
+    out = torch.empty((N, d_out), dtype=torch.int8, device="cuda")
+    ctx.eggroll_perturbed_forward_i8(eb.make_key(3, 1, 4), eb.make_shape(6, N, 1, d_out, d_in, 1, antithetic=anti), 8, 4, 7, 1,
+                                     torch.from_numpy(W).cuda(), torch.from_numpy(H).cuda(), out)
+    torch.cuda.synchronize()
+    want = oracle.matmul_i8(3, 1, 4, 6, N, d_out, d_in, 8, 4, 7, W, H, antithetic=bool(anti))
+    got = out.cpu().numpy()
+    assert (got == want).all()
+    assert 0.01 < (np.abs(want) == 127).mean() < 0.99 or np.abs(want).max() < 127
+    with pytest.raises(eb.EggrollError):   # a rectangular matrix cannot be iterated
+        ctx.eggroll_perturbed_forward_i8(eb.make_key(3, 1, 4), eb.make_shape(6, N, 1, d_out, d_in, 1), 8, 4, 7, 2,
+                                         torch.from_numpy(W).cuda(), torch.from_numpy(H).cuda(), out)
