@@ -79,6 +79,13 @@ def test_config2_full_size_forward_and_update(ctx):
         assert (err <= 1e-2 * (np.abs(tile) + rms)).all()
         assert (err > 2e-3 * (np.abs(tile) + rms)).mean() < 1e-3
 
+    # the update without caches (factors regenerated straight into the packed panels -- the other flow
+    # bench.py times): the same bits as the update from the forward's caches
+    G2 = torch.empty_like(G)
+    ctx.eggroll_update(key, shape, eb.EGG_BF16, torch.from_numpy(fit).cuda(), scale, 0, G2, None, 0.0, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(G2, G)
+
     # unperturbed pass at the same size: plain GEMM on sampled rows, and the perturbed run is deterministic
     Y0 = torch.empty_like(Y)
     ctx.eggroll_perturbed_forward(key, shape, 0.0, eb.EGG_ACT_NONE, W, X, Y0, None, None)
