@@ -75,6 +75,8 @@ def _load():
         lib.oracle_forward_i8_antithetic.restype = None
         lib.oracle_matmul_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp]
         lib.oracle_matmul_i8.restype = None
+        lib.oracle_gru_step_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.oracle_gru_step_i8.restype = None
         lib.oracle_update_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         lib.oracle_update_i8.restype = i32
         lib.oracle_int_threshold.argtypes = [dbl, i64, dbl]
@@ -206,6 +208,22 @@ def matmul_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound,
     _load().oracle_matmul_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, corr_shift,
                              out_shift, int(bool(antithetic)), _ptr(W), _ptr(H), _ptr(out))
     return out
+
+
+def gru_step_i8(seed, step, layer, member_begin, member_count, D, bound, corr_shift, out_shift,
+                Wf, Uf, Wh, Uh, bf, bh, U, S, antithetic=False) -> np.ndarray:
+    """One time step of the integer GRU cell for a population: returns the new state int8 [count, D].
+    The four matrices use noise layers layer .. layer+3."""
+    mats = [_c(m, np.int8) for m in (Wf, Uf, Wh, Uh)]
+    vecs = [_c(v, np.int8) for v in (bf, bh)]
+    U, S = _c(U, np.int8), _c(S, np.int8)
+    assert all(m.shape == (D, D) for m in mats) and all(v.shape == (D,) for v in vecs)
+    assert U.shape == (member_count, D) and S.shape == (member_count, D)
+    H = np.empty_like(S)
+    _load().oracle_gru_step_i8(seed, step, layer, member_begin, member_count, D, bound, corr_shift, out_shift,
+                               int(bool(antithetic)), *[_ptr(m) for m in mats], *[_ptr(v) for v in vecs],
+                               _ptr(U), _ptr(S), _ptr(H))
+    return H
 
 
 def update_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound, F, threshold, theta):

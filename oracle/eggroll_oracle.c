@@ -414,6 +414,48 @@ void oracle_matmul_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t memb
 }
 
 /* ------------------------------------------------------------------------------------------ */
+/* integer GRU cell (App. "GRU" of the EGG architecture), one time step for a population       */
+/* ------------------------------------------------------------------------------------------ */
+static int32_t sat127(int64_t v) { return (int32_t)(v > 127 ? 127 : (v < -127 ? -127 : v)); }
+
+/*
+ *   f     = I8( I32(u @ Wf^T) + I32(s @ Uf^T) + I32(bf) )                 sigma = identity
+ *   f^    = I8( ((I32(f) + 127) * I32(s)) >> 8 )
+ *   h^    = I8( I32(u @ Wh^T) + I32(f^ @ Uh^T) + I32(bh) )                phi = identity
+ *   h     = s + I8( ((I32(f) + 127) * (I32(h^) - I32(s))) >> 8 )
+ * "@" is the perturbed scaled matmul of forward_i8_worker (one application, square D x D); the four
+ * matrices are perturbed independently: Wf, Uf, Wh, Uh use noise layers layer, layer+1, layer+2, layer+3.
+ * I8 clips to [-127, 127]; shifts are arithmetic.  Reading: the final sum s + I8(.) is clipped to
+ * [-127, 127] as well (h is the next state, an I8 vector).  U, S, H: [count][D].
+ */
+void oracle_gru_step_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin, int64_t member_count,
+                        int D, int bound, int corr_shift, int out_shift, int antithetic,
+                        const int8_t* Wf, const int8_t* Uf, const int8_t* Wh, const int8_t* Uh,
+                        const int8_t* bf, const int8_t* bh, const int8_t* U, const int8_t* S, int8_t* H)
+{
+    const size_t n = (size_t)member_count * (size_t)D;
+    int8_t* a1 = (int8_t*)malloc(n); int8_t* a2 = (int8_t*)malloc(n);
+    int8_t* a3 = (int8_t*)malloc(n); int8_t* a4 = (int8_t*)malloc(n);
+    int8_t* f = (int8_t*)malloc(n); int8_t* fh = (int8_t*)malloc(n);
+    forward_i8_worker(seed, step, layer + 0, member_begin, member_count, D, D, bound, corr_shift, out_shift, 1, antithetic, Wf, U, a1);
+    forward_i8_worker(seed, step, layer + 1, member_begin, member_count, D, D, bound, corr_shift, out_shift, 1, antithetic, Uf, S, a2);
+    for (size_t i = 0; i < n; ++i) {
+        const int j = (int)(i % (size_t)D);
+        f[i] = (int8_t)sat127((int64_t)a1[i] + a2[i] + bf[j]);
+        fh[i] = (int8_t)sat127(shr_floor(((int64_t)f[i] + 127) * (int64_t)S[i], 8));
+    }
+    forward_i8_worker(seed, step, layer + 2, member_begin, member_count, D, D, bound, corr_shift, out_shift, 1, antithetic, Wh, U, a3);
+    forward_i8_worker(seed, step, layer + 3, member_begin, member_count, D, D, bound, corr_shift, out_shift, 1, antithetic, Uh, fh, a4);
+    for (size_t i = 0; i < n; ++i) {
+        const int j = (int)(i % (size_t)D);
+        const int32_t hh = sat127((int64_t)a3[i] + a4[i] + bh[j]);
+        const int32_t delta = sat127(shr_floor(((int64_t)f[i] + 127) * ((int64_t)hh - (int64_t)S[i]), 8));
+        H[i] = (int8_t)sat127((int64_t)S[i] + delta);
+    }
+    free(a1); free(a2); free(a3); free(a4); free(f); free(fh);
+}
+
+/* ------------------------------------------------------------------------------------------ */
 /* integer parameter update (App. "Parameter Update" of the integer pretraining section)       */
 /* ------------------------------------------------------------------------------------------ */
 /*
