@@ -125,6 +125,21 @@ egg_status eggroll_perturbed_forward_i8(eggroll_ctx* ctx, egg_key key, const egg
                                         const int8_t* H_in, int8_t* H_out);
 
 /*
+ * (2'') Integer GRU cell (App. "GRU" of the EGG architecture), a population of states advanced over
+ * `steps` inputs; "@" is the perturbed scaled matmul of (2'), I8 clips to [-127, 127], shifts are arithmetic:
+ *   f  = I8( I32(u @ Wf^T) + I32(s @ Uf^T) + I32(bf) )          f^ = I8( ((I32(f) + 127) * I32(s)) >> 8 )
+ *   h^ = I8( I32(u @ Wh^T) + I32(f^ @ Uh^T) + I32(bh) )         h  = I8( s + I8( ((I32(f) + 127) * (I32(h^) - I32(s))) >> 8 ) )
+ * (sigma and phi are the identity, as the paper sets them).  Wf, Uf, Wh, Uh: int8 [D][D] (D = d_out = d_in,
+ * a multiple of 16), perturbed independently with the noise of layers key.layer .. key.layer + 3, fixed over
+ * the steps; bf, bh: int8 [D], not perturbed.  U: int8 [steps][member_count][D] inputs, S_in / S_out:
+ * int8 [member_count][D] (may alias).  One row per member; antithetic pairs as in (2').  Bit-exact.
+ */
+egg_status eggroll_gru_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound, int corr_shift,
+                          int out_shift, int steps, const int8_t* Wf, const int8_t* Uf, const int8_t* Wh,
+                          const int8_t* Uh, const int8_t* bf, const int8_t* bh, const int8_t* U,
+                          const int8_t* S_in, int8_t* S_out);
+
+/*
  * (3) Update direction (EGGROLL UPDATE box; Sec. 4.2 "(diag(f)A)^T B"):
  *   G[j][k] = (accumulate ? G[j][k] : 0) + scale * sum_i fitness[i] sum_l A_i[j][l] B_i[k][l]
  * G: fp32 [d_out][d_in].  fitness: fp32 [member_count], used as given (centring / z-scoring /

@@ -19,7 +19,7 @@ EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
            "eggroll_default_scale", "eggroll_noise_gen", "eggroll_perturbed_forward",
-           "eggroll_perturbed_forward_i8", "eggroll_update", "eggroll_update_i8",
+           "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
 
 
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_perturbed_forward_i8.restype = i32
     lib.eggroll_update.argtypes = [vp, EggKey, P(EggShape), i32, vp, f32, i32, vp, vp, i32, f32, vp, vp]
     lib.eggroll_update.restype = i32
+    lib.eggroll_gru_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.eggroll_gru_i8.restype = i32
     lib.eggroll_update_i8.argtypes = [vp, EggKey, P(EggShape), i32, vp, ctypes.c_int32, vp, vp]
     lib.eggroll_update_i8.restype = i32
     lib.eggroll_int_threshold.argtypes = [ctypes.c_double, i64, ctypes.c_double]
@@ -152,6 +154,11 @@ class Context:
         self._check(self._lib.eggroll_perturbed_forward_i8(
             self._h, key, ctypes.byref(shape), int_bound, corr_shift, out_shift, steps,
             _ptr(W), _ptr(H_in), _ptr(H_out)))
+
+    def eggroll_gru_i8(self, key, shape, int_bound, corr_shift, out_shift, steps, Wf, Uf, Wh, Uh, bf, bh, U, S_in, S_out):
+        self._check(self._lib.eggroll_gru_i8(
+            self._h, key, ctypes.byref(shape), int_bound, corr_shift, out_shift, steps,
+            _ptr(Wf), _ptr(Uf), _ptr(Wh), _ptr(Uh), _ptr(bf), _ptr(bh), _ptr(U), _ptr(S_in), _ptr(S_out)))
 
     def eggroll_update(self, key, shape, noise_dtype, fitness, scale, accumulate, G, W=None, lr=0.0,
                        A_cache=None, B_cache=None):

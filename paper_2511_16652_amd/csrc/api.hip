@@ -126,7 +126,7 @@ egg_status eggroll_destroy(eggroll_ctx* c)
     if (!c) return EGG_EINVAL;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->zero_page};
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page};
     for (auto* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& r : c->recs) {
@@ -245,6 +245,33 @@ egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_s
     return launch_forward_i8(c, make_stream_key(key.seed, key.step, key.layer, 0),
                              make_stream_key(key.seed, key.step, key.layer, 1), *shape, int_bound, corr_shift,
                              out_shift, steps, W, H_in, H_out);
+}
+
+egg_status eggroll_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound, int corr_shift, int out_shift,
+                          int steps, const int8_t* Wf, const int8_t* Uf, const int8_t* Wh, const int8_t* Uh, const int8_t* bf,
+                          const int8_t* bh, const int8_t* U, const int8_t* S_in, int8_t* S_out)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, false, true);
+    if (s != EGG_OK) return s;
+    if (key.layer > 0x7FFFFFFFu - 3u) return fail(c, EGG_EINVAL, "layer + 3 must be < 2^31");
+    const void* ptrs[] = {Wf, Uf, Wh, Uh, bf, bh, U, S_in, S_out};
+    for (const void* p : ptrs) {
+        if (!p) return fail(c, EGG_EINVAL, "NULL pointer argument");
+        if (!aligned16(p)) return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
+    }
+    if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
+    if (shape->d_out != shape->d_in) return fail(c, EGG_EUNSUPPORTED, "the cell's matrices are square");
+    if (shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "D must be a multiple of 16");
+    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (corr_shift < 0 || corr_shift > 31 || out_shift < 0 || out_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
+    if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");
+    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+        return fail(c, EGG_EUNSUPPORTED, "D too large for int32 accumulation");
+    if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    const int8_t* W[4] = {Wf, Uf, Wh, Uh};
+    return launch_gru_i8(c, key, *shape, int_bound, corr_shift, out_shift, steps, W, bf, bh, U, S_in, S_out);
 }
 
 egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype noise_dtype,

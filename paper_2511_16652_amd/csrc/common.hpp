@@ -30,6 +30,7 @@ struct eggroll_ctx {
     Buf pack_b;       // update: K-packed B panel
     Buf i8_a, i8_b;   // int8 path: factors, generated once per episode
     Buf i8_h;         // int8 path: ping-pong state
+    Buf gru;          // integer GRU cell: factors of its four matrices, gate and matmul intermediates
     Buf zero_page;    // 256 zero bytes (K-tail loads of the GEMM core)
 
     // profiling
@@ -76,6 +77,12 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out);
 
+egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
+                            int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
+                            int* dots);
+egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, int out_shift,
+                         int steps, const int8_t* const W[4], const int8_t* bf, const int8_t* bh, const int8_t* U,
+                         const int8_t* S_in, int8_t* S_out);
 egg_status launch_update_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                             int int_bound, const int8_t* F, int32_t threshold, int8_t* theta, int32_t* E_out);
 

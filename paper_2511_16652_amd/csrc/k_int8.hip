@@ -209,6 +209,28 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     return check_hip(c, hipGetLastError(), "forward_gemm_i8");
 }
 
+// One perturbed integer matmul on factor buffers that already exist:  dst = I8((src W^T + ((src . B) A >> cs)) >> os).
+// dots: scratch for `rows` int32.  Used by the GRU cell, whose factors are generated once per call.
+egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
+                            int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
+                            int* dots)
+{
+    {
+        KernelScope ks(c, "dot_i8");
+        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, src, B, rows, d_in, anti, dots);
+    }
+    egg_status st = check_hip(c, hipGetLastError(), "dot_i8 launch");
+    if (st != EGG_OK) return st;
+    const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
+    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
+    Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
+    Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
+    I8Args ea{A, B, dots, nullptr, dst, d_out, corr_shift, out_shift, anti};
+    if (big_tiles >= 192)
+        return dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+    return dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+}
+
 egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out)
