@@ -372,13 +372,88 @@ def int8_workload(args):
     return res
 
 
+def gru_workload(args):
+    """Integer GRU cell at the integer model's width: D = 256, 2^18 members, 16 inputs per call."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_16652_amd import binding as eb
+
+    D, N, T, bound, cs, os_ = 256, 1 << 18, 16, 8, 4, 8
+    g = torch.Generator(device="cuda").manual_seed(7)
+    mats = [torch.randint(-16, 17, (D, D), generator=g, device="cuda", dtype=torch.int8) for _ in range(4)]
+    bf = torch.zeros(D, dtype=torch.int8, device="cuda")
+    bh = torch.zeros(D, dtype=torch.int8, device="cuda")
+    U = torch.randint(-127, 128, (T, N, D), generator=g, device="cuda", dtype=torch.int8)
+    S = torch.randint(-127, 128, (N, D), generator=g, device="cuda", dtype=torch.int8)
+    out = torch.empty_like(S)
+    ctx = eb.Context(0)
+    key, shape = eb.make_key(0, 0, 0), eb.make_shape(0, N, 1, D, D, 1)
+
+    def step():
+        ctx.eggroll_gru_i8(key, shape, bound, cs, os_, T, mats[0], mats[1], mats[2], mats[3], bf, bh, U, S, out)
+
+    prewarm(step)
+    t_step = timed(step, args.steps, args.warmup)
+    ctx.profile_enable(True)
+    for _ in range(min(args.steps, 20)):
+        step()
+    kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in ctx.profile_read().items()}
+    ctx.profile_enable(False)
+    # per member and input: 4 D^2 MACs; HBM bytes the method needs: u, s in, h out, 8 factor rows = 11 D
+    ops = 2.0 * 4 * D * D * N * T
+    bytes_alg = 11.0 * D * N * T
+    res = {
+        "metric": "population tokens/sec (integer GRU cell), 1 GPU",
+        "value": N * T / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+        "data": "synthetic", "config": {"workload": "gru_D256_N262144_T16", "D": D, "population": N, "inputs": T, "bound": bound},
+        "roofline": {"bound": "hbm", "achieved": bytes_alg / t_step / 1e9, "peak": 8000.0, "unit": "GB/s",
+                     "frac": bytes_alg / t_step / 8e12, "traffic": None},
+        "int8_TOPs": ops / t_step / 1e12,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        w = [x.cpu().numpy() for x in mats]
+        bfh, bhh = bf.cpu().numpy(), bh.cpu().numpy()
+
+        def run(m):
+            u, h = U[:, :m].cpu().numpy(), S[:m].cpu().numpy()
+            t0 = time.perf_counter()
+            for t in range(T):
+                h = oracle.gru_step_i8(0, 0, 0, 0, m, D, bound, cs, os_, w[0], w[1], w[2], w[3], bfh, bhh, u[t], h)
+            return time.perf_counter() - t0
+
+        th = oracle.threads()
+        m = 16 * th
+        dt = run(m)
+        for _ in range(2):  # size the sample to about 12 s of oracle time (the cost is linear in members)
+            if dt >= 8.0 or m >= N:
+                break
+            want = min(N, max(m, int(12.0 * m / max(dt, 1e-6)) // th * th))
+            if want == m:
+                break
+            m = want
+            dt = run(m)
+        res["cpu_baseline"] = {"value": m * T / dt, "unit": "tokens/s", "cores": th, "kind": "oracle",
+                               "sample": "%d of %d members, all %d inputs (%.2f s)" % (m, N, T, dt)}
+    ctx.close()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU (the hot path of one MI355X); --gpus %d is not "
                          "supported -- population sharding across GPUs is described in DESIGN.md only.\n" % args.gpus)
         sys.exit(2)
-    res = int8_workload(args) if args.workload == "cfg3" else linear_workload(args)
+    if args.workload == "cfg3":
+        res = int8_workload(args)
+    elif args.workload == "gru":
+        res = gru_workload(args)
+    else:
+        res = linear_workload(args)
     print(json.dumps(res))
 
 

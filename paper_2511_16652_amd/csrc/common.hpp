@@ -77,9 +77,17 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out);
 
+// GRU gating fused into the epilogue of an integer matmul (see I8Args in k_int8.hip)
+struct I8Gate {
+    int mode;  // 1: f and f^,  2: h
+    const int8_t *other, *state, *f, *bias;
+    int8_t* out2;
+};
 egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
                             int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
-                            int* dots);
+                            int* dots, bool dots_ready, const I8Gate* gate);
+egg_status launch_dots_i8(eggroll_ctx* c, const int8_t* X0, const int8_t* B0, const int8_t* B1, const int8_t* X1, const int8_t* B2,
+                          int64_t rows, int d, int anti, int* d0, int* d1, int* d2);
 egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, int out_shift,
                          int steps, const int8_t* const W[4], const int8_t* bf, const int8_t* bh, const int8_t* U,
                          const int8_t* S_in, int8_t* S_out);

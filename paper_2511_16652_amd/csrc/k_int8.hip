@@ -12,32 +12,62 @@
 
 namespace egg {
 
-// dots[row] = sum_k H[row][k] * B[row][k]   (int8 x int8 -> int32), one wave per row
-// anti: rows 2p, 2p+1 share the factors of pair p, and the odd row uses -B_p
-__global__ __launch_bounds__(256) void dot_i8_kernel(const int8_t* __restrict__ H, const int8_t* __restrict__ B,
-                                                     int64_t rows, int d, int anti, int* __restrict__ dots)
+// Row dot products  d0 = X0 . B0,  d1 = X0 . B1 (optional),  d2 = X1 . B2 (optional)   (int8 x int8 -> int32):
+// G lanes per row (16 for short rows, so that every lane has a 16-byte chunk to read; a whole wave otherwise),
+// v_dot4 on packed bytes.  Several products in one pass share the loads of X0 (the GRU cell needs three).
+// anti: rows 2p, 2p+1 share the factors of pair p, and the odd row uses -B_p.
+template <int G>
+__global__ __launch_bounds__(256) void dots_i8_kernel(const int8_t* __restrict__ X0, const int8_t* __restrict__ B0,
+                                                      const int8_t* __restrict__ B1, const int8_t* __restrict__ X1,
+                                                      const int8_t* __restrict__ B2, int64_t rows, int d, int anti,
+                                                      int* __restrict__ d0, int* __restrict__ d1, int* __restrict__ d2)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const u32x4* h = (const u32x4*)(H + row * d);
-    const u32x4* b = (const u32x4*)(B + (anti ? row >> 1 : row) * d);
-    int acc = 0;
-    for (int ch = lane; ch < (d >> 4); ch += 64) {
-        const u32x4 hv = h[ch], bv = b[ch];
+    const int lig = threadIdx.x % G;
+    const int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+    int acc0 = 0, acc1 = 0, acc2 = 0;
+    if (row < rows) {
+        const int64_t frow = (anti ? row >> 1 : row) * d;
+        const u32x4* x0 = (const u32x4*)(X0 + row * d);
+        const u32x4* b0 = (const u32x4*)(B0 + frow);
+        for (int ch = lig; ch < (d >> 4); ch += G) {
+            const u32x4 xv = x0[ch], bv = b0[ch];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < 4; ++w) acc0 = __builtin_amdgcn_sdot4((int)xv[w], (int)bv[w], acc0, false);
+            if (B1) {
+                const u32x4 cv = ((const u32x4*)(B1 + frow))[ch];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int x = (int)(int8_t)(hv[w] >> (8 * q));
-                const int y = (int)(int8_t)(bv[w] >> (8 * q));
-                acc += x * y;
+                for (int w = 0; w < 4; ++w) acc1 = __builtin_amdgcn_sdot4((int)xv[w], (int)cv[w], acc1, false);
+            }
+            if (B2) {
+                const u32x4 yv = ((const u32x4*)(X1 + row * d))[ch], ev = ((const u32x4*)(B2 + frow))[ch];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) acc2 = __builtin_amdgcn_sdot4((int)yv[w], (int)ev[w], acc2, false);
             }
         }
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) dots[row] = (anti && (row & 1)) ? -acc : acc;
+    for (int off = G / 2; off >= 1; off >>= 1) {
+        acc0 += __shfl_xor(acc0, off, 64);
+        acc1 += __shfl_xor(acc1, off, 64);
+        acc2 += __shfl_xor(acc2, off, 64);
+    }
+    if (lig == 0 && row < rows) {
+        const bool neg = anti && (row & 1);
+        d0[row] = neg ? -acc0 : acc0;
+        if (B1) d1[row] = neg ? -acc1 : acc1;
+        if (B2) d2[row] = neg ? -acc2 : acc2;
+    }
+}
+
+egg_status launch_dots_i8(eggroll_ctx* c, const int8_t* X0, const int8_t* B0, const int8_t* B1, const int8_t* X1, const int8_t* B2,
+                          int64_t rows, int d, int anti, int* d0, int* d1, int* d2)
+{
+    KernelScope ks(c, "dot_i8");
+    if (d <= 1024)
+        hipLaunchKernelGGL(dots_i8_kernel<16>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c->stream, X0, B0, B1, X1, B2, rows, d, anti, d0, d1, d2);
+    else
+        hipLaunchKernelGGL(dots_i8_kernel<64>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, X0, B0, B1, X1, B2, rows, d, anti, d0, d1, d2);
+    return check_hip(c, hipGetLastError(), "dot_i8 launch");
 }
 
 __global__ __launch_bounds__(256) void zero_i32_kernel(int* __restrict__ p, int64_t n)
@@ -63,6 +93,15 @@ struct I8Args {
     int8_t* H_out;    // [rows][d]
     int d, corr_shift, out_shift;
     int anti;  // antithetic pairs: rows 2p, 2p+1 read the factors of pair p; the odd row uses -B_p
+    // GRU gating fused behind the matmul (App. "GRU"); y = this matmul's I8 result, all operands [rows][d]:
+    //   gate 1:  f = I8(other + y + bias)  -> H_out,   f^ = I8(((f + 127) state) >> 8)  -> out2
+    //   gate 2:  h^ = I8(other + y + bias),  h = I8(state + I8(((f + 127)(h^ - state)) >> 8))  -> H_out
+    int gate;
+    const int8_t* g_other;
+    const int8_t* g_state;
+    const int8_t* g_f;
+    const int8_t* g_bias;  // [d]
+    int8_t* g_out2;
 };
 
 template <bool DOT24>
@@ -137,6 +176,14 @@ struct I8Epi {
         const int n = nb0 + row, m = mw0 + mc;
         const bool ok = n < n_rows && m < a.d;
         const char* src = stage + row * P + mc * 4;
+        const int64_t idx = (int64_t)min(n, n_rows - 1) * a.d + min(m, a.d - 16);
+        u32x4 gv_o = {0u, 0u, 0u, 0u}, gv_s = gv_o, gv_f = gv_o, gv_b = gv_o, out2 = gv_o;
+        if (a.gate) {  // issued first: their latency hides under the accumulator arithmetic below
+            gv_o = *(const u32x4*)(a.g_other + idx);
+            gv_s = *(const u32x4*)(a.g_state + idx);
+            gv_b = *(const u32x4*)(a.g_bias + min(m, a.d - 16));
+            if (a.gate == 2) gv_f = *(const u32x4*)(a.g_f + idx);
+        }
         u32x4 out;
         int part = 0;
 #pragma unroll
@@ -151,6 +198,25 @@ struct I8Epi {
                 const int corr = prod >> a.corr_shift;  // arithmetic shift: floor
                 y[e] = min(127, max(-127, (acc4[e] + corr) >> a.out_shift));
             }
+            if (a.gate) {
+                int y2[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int sj = (int)(int8_t)(gv_s[w] >> (8 * e));
+                    const int sum = min(127, max(-127, (int)(int8_t)(gv_o[w] >> (8 * e)) + y[e] + (int)(int8_t)(gv_b[w] >> (8 * e))));
+                    if (a.gate == 1) {
+                        y[e] = sum;                                                   // f
+                        y2[e] = min(127, max(-127, ((sum + 127) * sj) >> 8));         // f^
+                    } else {
+                        const int fj = (int)(int8_t)(gv_f[w] >> (8 * e));
+                        const int delta = min(127, max(-127, ((fj + 127) * (sum - sj)) >> 8));
+                        y[e] = min(127, max(-127, sj + delta));                      // h
+                        y2[e] = 0;
+                    }
+                }
+                out2[w] = __builtin_amdgcn_perm((uint32_t)y2[1], (uint32_t)y2[0], 0x0c0c0400u) |
+                          __builtin_amdgcn_perm((uint32_t)y2[3], (uint32_t)y2[2], 0x04000c0cu);
+            }
             // low bytes of y[0..3] -> one word (byte selectors 0-3: second operand, 4-7: first, 0x0c: zero)
             const uint32_t o = __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
                                __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu);
@@ -158,6 +224,7 @@ struct I8Epi {
             part = __builtin_amdgcn_sdot4((int)o, (int)bv[w], part, false);
         }
         if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
+        if (ok && a.gate == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
         if (a.dots_next) {
             if (!ok) part = 0;
             if (a.anti && (n & 1)) part = -part;  // h' . (-B_p)
@@ -210,22 +277,22 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
 }
 
 // One perturbed integer matmul on factor buffers that already exist:  dst = I8((src W^T + ((src . B) A >> cs)) >> os).
-// dots: scratch for `rows` int32.  Used by the GRU cell, whose factors are generated once per call.
+// dots: `rows` int32, computed here unless dots_ready.  Used by the GRU cell, whose factors are generated once per call.
 egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
                             int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
-                            int* dots)
+                            int* dots, bool dots_ready, const I8Gate* gate)
 {
-    {
-        KernelScope ks(c, "dot_i8");
-        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, src, B, rows, d_in, anti, dots);
-    }
-    egg_status st = check_hip(c, hipGetLastError(), "dot_i8 launch");
-    if (st != EGG_OK) return st;
+    egg_status st;
+    if (!dots_ready && (st = launch_dots_i8(c, src, B, nullptr, nullptr, nullptr, rows, d_in, anti, dots, nullptr, nullptr)) != EGG_OK) return st;
     const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
     const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
     Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
     Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
-    I8Args ea{A, B, dots, nullptr, dst, d_out, corr_shift, out_shift, anti};
+    I8Args ea{A, B, dots, nullptr, dst, d_out, corr_shift, out_shift, anti, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (gate) {
+        ea.gate = gate->mode;
+        ea.g_other = gate->other; ea.g_state = gate->state; ea.g_f = gate->f; ea.g_bias = gate->bias; ea.g_out2 = gate->out2;
+    }
     if (big_tiles >= 192)
         return dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
     return dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
@@ -261,11 +328,7 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
         KernelScope ks(c, "zero_dots");
         hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, c->stream, (int*)dots_base, nz);
     }
-    {
-        KernelScope ks(c, "dot_i8");
-        hipLaunchKernelGGL(dot_i8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, H_in, B, rows, d_in, anti, (int*)dots_base);
-    }
-    if ((st = check_hip(c, hipGetLastError(), "dot_i8 launch")) != EGG_OK) return st;
+    if ((st = launch_dots_i8(c, H_in, B, nullptr, nullptr, nullptr, rows, d_in, anti, (int*)dots_base, nullptr, nullptr)) != EGG_OK) return st;
 
     const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
     // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
@@ -279,7 +342,7 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
         Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
         // the epilogue's row length is d_out (rows of A_i and of h'); with a next step d_out == d_in, so B_i fits too
         I8Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
-                       dst, d_out, corr_shift, out_shift, anti};
+                       dst, d_out, corr_shift, out_shift, anti, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
         if (big_tiles >= 192)
             st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
         else
