@@ -6,13 +6,16 @@
 //   - the update contraction (diag(f)A)^T B over K = N*r (P, Q = K-packed factor panels), Sec. 4.2
 //   - the int8 x int8 -> int32 matmul of the integer model, App. "Matrix Multiplication".
 // A workgroup owns a BM x BN tile of C; 64-wide waves own 32x32 MFMA blocks of it.  K advances in
-// stages of 8 chunks (128 bytes per row) double-buffered in LDS; the global loads of stage kt+2 are
-// in flight in registers while stage kt is multiplied and stage kt+1 sits in the other LDS buffer.
-// (Deeper register prefetch was measured on the short-K int8 problem: no gain, that loop is bound by
-// L2-to-CU bandwidth, not by latency.)
-// Rows of an LDS stage are 128 bytes with the chunk slot XOR-swizzled by (row>>1)&7, which makes
-// the 16-byte fragment reads of any 16 neighbouring rows hit distinct banks (measured: zero bank
-// conflicts).
+// stages of 8 chunks (128 bytes per row) double-buffered in LDS and filled by direct-to-LDS loads
+// (global_load_lds, 16 bytes per lane): the loads of stage kt+2 are issued right behind the barrier
+// that retires stage kt's buffer and land while stage kt+1 is multiplied.  Nothing is staged in
+// registers and no ds_write is issued.  (Measured at 4096^3 bf16: 103 us against 117 us for the earlier
+// register-staged form -- global_load_dwordx4 one stage ahead, ds_write_b128 -- whose LDS instruction
+// count and LDS wait cycles were twice those of the vendor library's kernel; the stage-synchronous form
+// of the direct load alone already streams 16.8 TB/s from L2 into LDS.)
+// Stage layouts: row-major operands keep 128-byte rows with the chunk slot XOR-swizzled by (row>>1)&7,
+// which makes the 16-byte fragment reads of any 16 neighbouring rows hit distinct banks; K-packed
+// operands use a chunk-major stage ([chunk][row][16 B]) whose fragment reads are 32 consecutive slots.
 // The epilogue is a functor that receives, per lane, 4 consecutive rows m..m+3 of one column n:
 // that is exactly one aligned group of factor entries A_i[m..m+3][:] for the member of column n.
 #pragma once
@@ -90,63 +93,41 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     tn = in_group / gsz;
 }
 
-// Global -> LDS movement of one K-stage (ROWS rows of 128 bytes), staged through registers:
-// global_load_dwordx4 into `regs` one whole stage ahead of its use, then ds_write_b128 into the LDS
-// buffer that the last barrier retired.  (The LDS-DMA form of the global load was measured at less
-// than half the L2 streaming rate of plain 16-byte loads on gfx950, so it is not used.)
-// Chunk (row, k) of a stage lives at LDS offset row*128 + ((k ^ ((row>>1)&7)) << 4).  Which chunk a
-// load covers is chosen so that a wave's 64 loads are contiguous in global memory:
-//   row-major operands (KPACK = false): idx = it*NT + tid -> row = idx/8, LDS slot = idx%8
-//                                       (8 lanes read the 128 contiguous bytes of a row);
-//   K-packed operands  (KPACK = true) : idx -> row = idx % ROWS, k = idx / ROWS
-//                                       (64 lanes read 64 consecutive rows of one k: 1 KB).
-// Addresses are a wave-uniform 64-bit base (tile origin + K offset, kept in scalar registers) plus
-// a loop-invariant 32-bit per-lane offset.
-template <int ROWS, int NT, bool KPACK>
-struct Loader {
+// Global -> LDS movement of one K-stage (ROWS rows x 8 chunks of 16 bytes) by direct-to-LDS loads: lane i
+// of a wave's load lands at LDS base + 16 i, so slot idx = it*NT + tid sits at byte 16 idx of the operand's
+// half of the stage, and the lane fetches the chunk that belongs there:
+//   row-major operands (KMAJOR = false): row idx/8, position idx%8 holds chunk k = (idx%8) ^ swizzle(row);
+//                                        8 neighbouring lanes cover the 128 contiguous bytes of one row;
+//   K-packed operands  (KMAJOR = true) : row idx % ROWS of chunk idx / ROWS;
+//                                        64 lanes read 64 consecutive rows of one chunk plane: 1 KB.
+// Addresses are a wave-uniform 64-bit base (tile origin + K offset, kept in scalar registers) plus a
+// loop-invariant 32-bit per-lane offset.
+typedef __attribute__((address_space(3))) void egg_lds_void;
+typedef __attribute__((address_space(1))) const void egg_glb_void;
+template <int ROWS, int NT, bool KMAJOR>
+struct DmaLoader {
     static constexpr int L = ROWS * 8 / NT;
     uint32_t off[L];
-    int chunk[L];  // global chunk index (0..7) of each load, for the K tail
-
-    static __device__ __forceinline__ void coords(int it, int tid, int& row, int& k)
-    {
-        const int idx = it * NT + tid;
-        if constexpr (KPACK) {
-            row = idx % ROWS;
-            k = idx / ROWS;
-        } else {
-            row = idx >> 3;
-            k = (idx & 7) ^ ((row >> 1) & 7);
-        }
-    }
+    int chunk[L];
     __device__ __forceinline__ void init(const Operand& o, int row0, int tid)
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
-            int row;
-            coords(it, tid, row, chunk[it]);
+            const int idx = it * NT + tid;
+            const int row = KMAJOR ? idx % ROWS : idx >> 3;
+            chunk[it] = KMAJOR ? idx / ROWS : (idx & 7) ^ ((row >> 1) & 7);
             const int rl = min(row, o.rows - 1 - row0);  // rows past the end re-read the last valid row
             off[it] = (uint32_t)((int64_t)rl * o.row_stride + (int64_t)chunk[it] * o.kc_stride);
         }
     }
     // chunks past the end of K (only possible in the last stage) read the zero page instead
-    __device__ __forceinline__ void load(u32x4 (&regs)[L], const char* base, int kfirst, int kchunks,
-                                         const char* zero_page) const
+    __device__ __forceinline__ void load(const char* base, int kfirst, int kchunks, const char* zero_page, char* sdst, int wave) const
     {
 #pragma unroll
         for (int it = 0; it < L; ++it) {
             const char* g = base + (uint64_t)off[it];
             if (kfirst + chunk[it] >= kchunks) g = zero_page;
-            regs[it] = *(const u32x4*)g;
-        }
-    }
-    __device__ __forceinline__ void store(const u32x4 (&regs)[L], char* sdst, int tid) const
-    {
-#pragma unroll
-        for (int it = 0; it < L; ++it) {
-            int row, k;
-            coords(it, tid, row, k);
-            *(u32x4*)(sdst + row * 128 + ((k ^ ((row >> 1) & 7)) << 4)) = regs[it];
+            __builtin_amdgcn_global_load_lds((egg_glb_void*)g, (egg_lds_void*)(sdst + (it * NT + wave * 64) * 16), 16, 0, 0);
         }
     }
 };
@@ -175,11 +156,11 @@ constexpr size_t gemm_lds_bytes()
 //       called by all threads before the per-wave part; returns whether a barrier is needed
 //
 // Main loop, per K-stage (4 MFMA k-steps): the fragments of k-step s+1 are read from LDS while the
-// MFMAs of k-step s run (two fragment register sets).  During k-steps 0..2 the registers holding
-// stage kt+1 are written to the free LDS buffer and the loads of stage kt+2 are issued into them
-// (most of a stage of MFMA work to land); the single barrier of the stage sits in the middle of
-// k-step 3, after which the first fragments of stage kt+1 are read.
-template <class MT, int BM, int BN, int WM, int WN, bool KPACK, class Epi, int WG_PER_CU = 1>
+// MFMAs of k-step s run (two fragment register sets).  The single barrier of the stage sits in the
+// middle of k-step 3; right behind it the direct-to-LDS loads of stage kt+2 go out into the buffer the
+// barrier retired, and the first fragments of stage kt+1 are read.
+// KMAJOR: both operands are K-packed panels (chunk-major stages); otherwise row-major operands.
+template <class MT, int BM, int BN, int WM, int WN, bool KMAJOR, class Epi, int WG_PER_CU = 1>
 __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, int ksplit, const char* zero_page,
                                                                    typename Epi::Args ea)
@@ -200,7 +181,7 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
     const int wm = wave % WM, wn = wave / WM;
 
     // split-K (ksplit > 0): consecutive groups of tiles_m * tiles_n workgroups own consecutive ranges of
-    // ksplit K-chunks; the epilogue then has to combine the partial tiles (integer atomics)
+    // ksplit K-chunks; the epilogue stores partial tiles that a later pass combines
     int tile_id = blockIdx.x, kbeg = 0;
     if (ksplit > 0) {
         const int tiles = tiles_m * tiles_n;
@@ -214,15 +195,14 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
     const int m0 = tm * BM, n0 = tn * BN;
 
     // The epilogue may fetch small per-tile side data ahead of time instead of paying global-memory
-    // latency behind the last MFMA: its prefetch hook runs where the main loop issues its last stage
-    // load, so the registers it fills are the ones the staged loads no longer need.
+    // latency behind the last MFMA: its prefetch hook runs before the last K-stage.
     Epi epi(ea, lds + wave * Epi::lds_per_wave(WTM), lane);
 #define EGG_EPI_PREFETCH epi.template prefetch<MB, NB>(m0 + wm * WTM, n0 + wn * WTN, lane, Q.rows);
 
     const char* pb = P.base + (int64_t)m0 * P.row_stride + (int64_t)kbeg * P.kc_stride;
     const char* qb = Q.base + (int64_t)n0 * Q.row_stride + (int64_t)kbeg * Q.kc_stride;
-    Loader<BM, NT, KPACK> lp;
-    Loader<BN, NT, KPACK> lq;
+    DmaLoader<BM, NT, KMAJOR> lp;
+    DmaLoader<BN, NT, KMAJOR> lq;
     lp.init(P, m0, tid);
     lq.init(Q, n0, tid);
     const int64_t pstep = 8 * P.kc_stride, qstep = 8 * Q.kc_stride;
@@ -237,6 +217,8 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
     for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * PITCH + (((2 * ks + (lane >> 5)) ^ fsw) << 4);
     const int a_base = wm * WTM * PITCH;
     const int b_base = BM * PITCH + wn * WTN * PITCH;
+    // chunk-major stages: chunk c of row r at (c * ROWS + r) * 16 inside the operand's half of the stage
+    const int a_row16 = (wm * WTM + frow) * 16, b_row16 = BM * PITCH + (wn * WTN + frow) * 16;
 
     typename MT::acc_t acc[MB][NB];
 #pragma unroll
@@ -248,14 +230,15 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
 
     const int KT = (kchunks + 7) >> 3;
     u32x4 fa[2][MB], fb[2][NB];
-    constexpr int LP_ = Loader<BM, NT, KPACK>::L, LQ_ = Loader<BN, NT, KPACK>::L;
 
 #define EGG_READ_FRAGS(BUF, STAGE, KS_)                                                                        \
     {                                                                                                          \
-        const char* sa_ = lds + (STAGE)*STAGE_BYTES + a_base + foff[KS_];                                      \
-        const char* sb_ = lds + (STAGE)*STAGE_BYTES + b_base + foff[KS_];                                      \
-        _Pragma("unroll") for (int i = 0; i < MB; ++i) fa[BUF][i] = *(const u32x4*)(sa_ + i * 32 * PITCH);     \
-        _Pragma("unroll") for (int j = 0; j < NB; ++j) fb[BUF][j] = *(const u32x4*)(sb_ + j * 32 * PITCH);     \
+        const int c_ = 2 * (KS_) + (lane >> 5);                                                                \
+        const char* sa_ = lds + (STAGE)*STAGE_BYTES + (KMAJOR ? a_row16 + c_ * BM * 16 : a_base + foff[KS_]);  \
+        const char* sb_ = lds + (STAGE)*STAGE_BYTES + (KMAJOR ? b_row16 + c_ * BN * 16 : b_base + foff[KS_]);  \
+        constexpr int BLK_ = KMAJOR ? 32 * 16 : 32 * PITCH;                                                    \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) fa[BUF][i] = *(const u32x4*)(sa_ + i * BLK_);           \
+        _Pragma("unroll") for (int j = 0; j < NB; ++j) fb[BUF][j] = *(const u32x4*)(sb_ + j * BLK_);           \
     }
 #define EGG_MMA_ROWS(BUF, I0, I1)                                                                              \
     _Pragma("unroll") for (int i = I0; i < I1; ++i) _Pragma("unroll") for (int j = 0; j < NB; ++j)             \
@@ -275,68 +258,48 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
             if ((N_B) > 0 && r_ * PB_ < (N_B)) __builtin_amdgcn_sched_group_barrier(MASK_B, PB_, 0);           \
         }                                                                                                      \
     }
-// Stage kt+1 travels registers -> LDS and stage kt+2 global -> registers in two halves (P rows,
-// then Q rows) spread over k-steps 0..2, so that no k-step carries the whole 64 KB LDS write burst:
-//   k-step 0: ds_write P(kt+1)            k-step 1: load P(kt+2), ds_write Q(kt+1)
-//   k-step 2: load Q(kt+2)                k-step 3: barrier in the middle, then first fragments of kt+1
-#define EGG_ITER(KT_, DO_STORE, DO_LOAD, MORE)                                                                 \
+// One K-stage.  The barrier in k-step 3 retires this stage's buffer (every wave has read its last
+// fragments from it), so the loads of stage kt+2 are issued right behind it, straight into that buffer,
+// and have a whole stage of MFMA work to land: the next barrier waits for them.
+#define EGG_ITER(KT_, NEXT, LOAD2)                                                                         \
     {                                                                                                          \
         const int cur_ = (KT_)&1;                                                                              \
-        char* nxt_ = lds + (cur_ ^ 1) * STAGE_BYTES;                                                           \
         const int lk_ = (KT_) + 2;                                                                             \
         EGG_READ_FRAGS(1, cur_, 1)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
-        if (DO_STORE) {                                                                                        \
-            lp.store(rp, nxt_, tid);                                                                       \
-            EGG_SCHED(0x200, LP_, 0, 0)                                                                        \
-        } else {                                                                                               \
-            EGG_SCHED(0, 0, 0, 0)                                                                              \
-        }                                                                                                      \
+        EGG_SCHED(0, 0, 0, 0)                                                                                  \
         EGG_READ_FRAGS(0, cur_, 2)                                                                             \
         EGG_MMA_ROWS(1, 0, MB)                                                                                 \
-        if (DO_LOAD) lp.load(rp, pb + (int64_t)lk_ * pstep, lk_ * 8, kchunks, zero_page);                  \
-        if (DO_STORE) lq.store(rq, nxt_ + BM * PITCH, tid);                                                \
-        if (DO_LOAD) {                                                                                         \
-            EGG_SCHED(0x020, LP_, 0x200, LQ_)                                                                  \
-        } else if (DO_STORE) {                                                                                 \
-            EGG_SCHED(0x200, LQ_, 0, 0)                                                                        \
-        } else {                                                                                               \
-            EGG_SCHED(0, 0, 0, 0)                                                                              \
-        }                                                                                                      \
+        EGG_SCHED(0, 0, 0, 0)                                                                                  \
         EGG_READ_FRAGS(1, cur_, 3)                                                                             \
         EGG_MMA_ROWS(0, 0, MB)                                                                                 \
-        if (DO_LOAD) {                                                                                         \
-            lq.load(rq, qb + (int64_t)lk_ * qstep, lk_ * 8, kchunks, zero_page);                           \
-            EGG_SCHED(0x020, LQ_, 0, 0)                                                                        \
-        } else {                                                                                               \
-            EGG_SCHED(0, 0, 0, 0)                                                                              \
-        }                                                                                                      \
+        EGG_SCHED(0, 0, 0, 0)                                                                                  \
         EGG_MMA_ROWS(1, 0, MB / 2)                                                                             \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's direct-to-LDS loads have landed */        \
         __syncthreads();                                                                                       \
-        if (MORE) EGG_READ_FRAGS(0, cur_ ^ 1, 0)                                                               \
+        if (LOAD2) {                                                                                           \
+            lp.load(pb + (int64_t)lk_ * pstep, lk_ * 8, kchunks, zero_page, lds + cur_ * STAGE_BYTES, wave);   \
+            lq.load(qb + (int64_t)lk_ * qstep, lk_ * 8, kchunks, zero_page, lds + cur_ * STAGE_BYTES + BM * PITCH, wave); \
+        }                                                                                                      \
+        if (NEXT) EGG_READ_FRAGS(0, cur_ ^ 1, 0)                                                               \
         EGG_MMA_ROWS(1, MB / 2, MB)                                                                            \
     }
-#define EGG_LOAD_STAGE(KT_)                                                                                    \
-    {                                                                                                          \
-        lp.load(rp, pb + (int64_t)(KT_)*pstep, (KT_)*8, kchunks, zero_page);                               \
-        lq.load(rq, qb + (int64_t)(KT_)*qstep, (KT_)*8, kchunks, zero_page);                               \
-    }
 
-    // prologue: stage 0 goes to LDS, stage 1 waits in the registers
-    u32x4 rp[LP_], rq[LQ_];
-    EGG_LOAD_STAGE(0)
-    lp.store(rp, lds, tid);
-    lq.store(rq, lds + BM * PITCH, tid);
-    if (KT > 1) EGG_LOAD_STAGE(1)
+    // prologue: stages 0 and 1 straight into the two buffers
+    lp.load(pb, 0, kchunks, zero_page, lds, wave);
+    lq.load(qb, 0, kchunks, zero_page, lds + BM * PITCH, wave);
+    if (KT > 1) {
+        lp.load(pb + pstep, 8, kchunks, zero_page, lds + STAGE_BYTES, wave);
+        lq.load(qb + qstep, 8, kchunks, zero_page, lds + STAGE_BYTES + BM * PITCH, wave);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     EGG_READ_FRAGS(0, 0, 0)
     int kt = 0;
-    for (; kt + 2 < KT; ++kt) EGG_ITER(kt, true, true, true)      // steady state
+    for (; kt + 2 < KT; ++kt) EGG_ITER(kt, true, true)           // steady state
+    if (kt + 1 < KT) { EGG_ITER(kt, true, false) ++kt; }          // the last stage is already on its way
     EGG_EPI_PREFETCH
-    if (kt + 1 < KT) { EGG_ITER(kt, true, false, true) ++kt; }    // last stage is in registers
-    EGG_ITER(kt, false, false, false)                             // last stage
-#undef EGG_EPI_PREFETCH
-#undef EGG_LOAD_STAGE
+    EGG_ITER(kt, false, false)                                    // last stage
 #undef EGG_ITER
 #undef EGG_SCHED
 #undef EGG_READ_FRAGS
