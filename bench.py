@@ -6,7 +6,10 @@ shared GEMM with the fused low-rank correction (perturbed forward), then the fit
 G = scale * sum_i f_i A_i B_i^T computed as one MFMA contraction over K = N*r.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3|p0] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload W] [--no-cpu-baseline]
+
+Workloads: cfg2 (default), cfg1, cfg3 (int8 recurrence + integer update), gru (integer GRU cell),
+p0, p0_r2, p0_r4, p0_r8, mlp_up, mlp_down, ffn_up, attn_proj.
 """
 from __future__ import annotations
 
@@ -446,7 +449,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU (the hot path of one MI355X); --gpus %d is not "
-                         "supported -- population sharding across GPUs is described in DESIGN.md only.\n" % args.gpus)
+                         "supported: every figure here is one GPU's throughput.\n" % args.gpus)
         sys.exit(2)
     if args.workload == "cfg3":
         res = int8_workload(args)
