@@ -81,6 +81,12 @@ def _load():
         lib.oracle_update_i8.restype = i32
         lib.oracle_int_threshold.argtypes = [dbl, i64, dbl]
         lib.oracle_int_threshold.restype = i64
+        lib.oracle_layernorm_i8.argtypes = [i64, i32, vp, vp, vp]
+        lib.oracle_layernorm_i8.restype = None
+        lib.oracle_embed_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, vp, vp, vp]
+        lib.oracle_embed_i8.restype = None
+        lib.oracle_egg_forward_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, i32] + [vp] * 13
+        lib.oracle_egg_forward_i8.restype = i32
         lib.oracle_threads.argtypes = []
         lib.oracle_threads.restype = i32
         _lib = lib
@@ -241,6 +247,57 @@ def update_i8(seed, step, layer, member_begin, member_count, d_out, d_in, bound,
     if rc == -2:
         raise OverflowError("oracle_update_i8: |E| exceeds int32")
     return out, E
+
+
+def layernorm_i8(ln, U) -> np.ndarray:
+    """Mean-absolute-value layer normalisation of int8 rows [rows, D] with weight ln [D]."""
+    ln, U = _c(ln, np.int8), _c(U, np.int8)
+    rows, D = U.shape
+    assert ln.shape == (D,) and D & (D - 1) == 0
+    out = np.empty_like(U)
+    _load().oracle_layernorm_i8(rows, D, _ptr(ln), _ptr(U), _ptr(out))
+    return out
+
+
+def embed_i8(seed, step, layer, member_begin, member_count, D, bound, corr_shift, emb, tokens,
+             antithetic=False) -> np.ndarray:
+    """Perturbed embedding lookup: tokens uint8 [count] -> int8 [count, D]; emb int8 [256, D]."""
+    emb, tokens = _c(emb, np.int8), _c(tokens, np.uint8)
+    assert emb.shape == (256, D) and tokens.shape == (member_count,)
+    out = np.empty((member_count, D), np.int8)
+    _load().oracle_embed_i8(seed, step, layer, member_begin, member_count, D, bound, corr_shift,
+                            int(bool(antithetic)), _ptr(emb), _ptr(tokens), _ptr(out))
+    return out
+
+
+EGG_PARAM_NAMES = ("emb", "ln1", "gru_w", "gru_b", "ln2", "mlp1", "mlp2", "ln_out", "head")
+
+
+def egg_param_shapes(D, L):
+    """Shapes of the integer model's parameter arrays, in the order of EGG_PARAM_NAMES."""
+    return {"emb": (256, D), "ln1": (L, D), "gru_w": (L, 4, D, D), "gru_b": (L, 2, D), "ln2": (L, D),
+            "mlp1": (L, 4 * D, D), "mlp2": (L, D, 4 * D), "ln_out": (D,), "head": (256, D)}
+
+
+def egg_forward_i8(seed, step, layer, member_begin, member_count, D, L, bound, corr_shift, params, tokens, S_in,
+                   antithetic=False):
+    """The integer model's forward pass for a population: tokens uint8 [T, count], S_in int8 [L, count, D]
+    -> (logits int8 [T, count, 256], S_out int8 [L, count, D]).  params: dict of EGG_PARAM_NAMES."""
+    shapes = egg_param_shapes(D, L)
+    arrs = [_c(params[k], np.int8) for k in EGG_PARAM_NAMES]
+    for k, a in zip(EGG_PARAM_NAMES, arrs):
+        assert a.shape == shapes[k], (k, a.shape, shapes[k])
+    tokens, S_in = _c(tokens, np.uint8), _c(S_in, np.int8)
+    T = tokens.shape[0]
+    assert tokens.shape == (T, member_count) and S_in.shape == (L, member_count, D)
+    S_out = np.empty_like(S_in)
+    logits = np.empty((T, member_count, 256), np.int8)
+    rc = _load().oracle_egg_forward_i8(seed, step, layer, member_begin, member_count, D, L, bound, corr_shift,
+                                       int(bool(antithetic)), T, *[_ptr(a) for a in arrs], _ptr(tokens),
+                                       _ptr(S_in), _ptr(S_out), _ptr(logits))
+    if rc != 0:
+        raise MemoryError("oracle_egg_forward_i8")
+    return logits, S_out
 
 
 def int_threshold(alpha: float, n_terms: int, noise_std: float) -> int:

@@ -534,6 +534,131 @@ int64_t oracle_int_threshold(double alpha, int64_t n_terms, double noise_std)
     return first * second;
 }
 
+/* ------------------------------------------------------------------------------------------ */
+/* integer model around the cell (App. "EGG architecture": Embedding, Layer Normalisation,     */
+/* MLP, Alg. "EGG forward pass")                                                               */
+/* ------------------------------------------------------------------------------------------ */
+/*
+ * Layer normalisation of rows u in I8^D, D a power of two:
+ *     u_mav = (sum_k |u_k|) >> log2(D)                            mean absolute value, fraction dropped
+ *     out_k = I8( DIVIDE( I16(u_k) * I16(ln_k), u_mav ) )
+ * Readings: DIVIDE is the integer quotient rounded toward zero (symmetric in the sign of the product,
+ * like the rest of the integer model); a row whose mean absolute value truncates to 0 divides by 1;
+ * the quotient is clipped to [-127, 127] (the result feeds an int8 matmul).
+ */
+void oracle_layernorm_i8(int64_t rows, int D, const int8_t* ln, const int8_t* U, int8_t* out)
+{
+    int lg = 0;
+    while ((1 << lg) < D) ++lg;
+    for (int64_t r = 0; r < rows; ++r) {
+        const int8_t* u = U + (size_t)r * D;
+        int64_t sum = 0;
+        for (int k = 0; k < D; ++k) sum += u[k] < 0 ? -(int64_t)u[k] : (int64_t)u[k];
+        int64_t mav = sum >> lg;
+        if (mav == 0) mav = 1;
+        for (int k = 0; k < D; ++k) {
+            const int64_t prod = (int64_t)u[k] * (int64_t)ln[k];
+            const int64_t mag = (prod < 0 ? -prod : prod) / mav;
+            out[(size_t)r * D + k] = (int8_t)sat127(prod < 0 ? -mag : mag);
+        }
+    }
+}
+
+/*
+ * Perturbed embedding: y = I8( emb[t] + ((A_i[t] * I32(B_i)) >> corr_shift) ), emb in I8^{256 x D}.
+ * The lookup is one_hot(t) applied to the table, so the dot product of the input with the token-side
+ * factor is that factor's entry t ("replacing u.B with B[t]").  Readings: the factor indexed by the
+ * token is drawn from stream A (length 256) and the one along the width from stream B (length D), so
+ * the perturbation A B^T has the table's own [256][D] layout; the output scaling 1/(16 sqrt n) of a
+ * matmul does not apply to a lookup (it would erase the table entry).  tokens: [count]; Y: [count][D].
+ */
+void oracle_embed_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin, int64_t member_count,
+                     int D, int bound, int corr_shift, int antithetic, const int8_t* emb, const uint8_t* tokens,
+                     int8_t* Y)
+{
+    int8_t A[256];
+    int8_t* B = (int8_t*)malloc((size_t)D);
+    for (int64_t m = 0; m < member_count; ++m) {
+        const int64_t member = member_begin + m;
+        const int64_t noise_id = antithetic ? member / 2 : member;
+        oracle_noise_int(seed, step, layer, 0, noise_id, 0, 256, bound, A);
+        oracle_noise_int(seed, step, layer, 1, noise_id, 0, (uint64_t)D, bound, B);
+        const int sign = (antithetic && (member & 1)) ? -1 : 1;
+        const int t = tokens[m];
+        for (int j = 0; j < D; ++j) {
+            const int64_t corr = shr_floor((int64_t)A[t] * (int64_t)(sign * B[j]), corr_shift);
+            Y[(size_t)m * D + j] = (int8_t)sat127((int64_t)emb[(size_t)t * D + j] + corr);
+        }
+    }
+    free(B);
+}
+
+/* 4 + log2(sqrt n): the division by 16 sqrt(n) of the scaled matmul as a shift; n must be a power of 4 */
+static int scaled_shift(int n)
+{
+    int lg = 0;
+    while ((1 << lg) < n) ++lg;
+    return 4 + lg / 2;
+}
+
+/*
+ * Alg. "EGG forward pass" for a population, T tokens per member, state carried from token to token:
+ *     y = EMBED(emb, t)
+ *     for each layer i:  y', s'_i = GRU(LN(ln1_i, y), s_i);  y = I8(y' + y)
+ *                        y' = MLP(LN(ln2_i, y)) = (u @ mlp1_i^T) @ mlp2_i^T;  y = I8(y' + y)
+ *     logits = LN(ln_out, y) @ head^T
+ * Every "@" is the perturbed scaled matmul with out shift 4 + log2(sqrt d_in); D is a power of 4.
+ * Noise layers: layer + 0 embedding; layer + 1 + 6 i + {0,1,2,3: Wf, Uf, Wh, Uh; 4: mlp1; 5: mlp2};
+ * layer + 1 + 6 L the head.  Layer-norm weights and the two GRU biases are not perturbed.
+ * Layouts: gru_w [L][4][D][D], gru_b [L][2][D] (bf, bh), ln1/ln2 [L][D], mlp1 [L][4D][D], mlp2 [L][D][4D],
+ * tokens [T][count], S_in/S_out [L][count][D], logits [T][count][256].  Returns 0, or -1 (allocation).
+ */
+int oracle_egg_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t member_begin, int64_t member_count,
+                          int D, int L, int bound, int corr_shift, int antithetic, int T,
+                          const int8_t* emb, const int8_t* ln1, const int8_t* gru_w, const int8_t* gru_b,
+                          const int8_t* ln2, const int8_t* mlp1, const int8_t* mlp2, const int8_t* ln_out,
+                          const int8_t* head, const uint8_t* tokens, const int8_t* S_in, int8_t* S_out,
+                          int8_t* logits)
+{
+    const size_t n = (size_t)member_count * (size_t)D;
+    const size_t DD = (size_t)D * D;
+    int8_t* y = (int8_t*)malloc(n);
+    int8_t* u = (int8_t*)malloc(n);
+    int8_t* yp = (int8_t*)malloc(n);
+    int8_t* hid = (int8_t*)malloc(4 * n);
+    int8_t* state = (int8_t*)malloc((size_t)L * n);
+    if (!y || !u || !yp || !hid || !state) { free(y); free(u); free(yp); free(hid); free(state); return -1; }
+    memcpy(state, S_in, (size_t)L * n);
+    const int os_d = scaled_shift(D), os_4d = scaled_shift(4 * D);
+    for (int t = 0; t < T; ++t) {
+        oracle_embed_i8(seed, step, layer, member_begin, member_count, D, bound, corr_shift, antithetic, emb,
+                        tokens + (size_t)t * member_count, y);
+        for (int i = 0; i < L; ++i) {
+            const uint32_t base = layer + 1u + 6u * (uint32_t)i;
+            const int8_t* w = gru_w + (size_t)i * 4 * DD;
+            int8_t* s = state + (size_t)i * n;
+            oracle_layernorm_i8(member_count, D, ln1 + (size_t)i * D, y, u);
+            oracle_gru_step_i8(seed, step, base, member_begin, member_count, D, bound, corr_shift, os_d, antithetic,
+                               w, w + DD, w + 2 * DD, w + 3 * DD, gru_b + (size_t)i * 2 * D,
+                               gru_b + (size_t)i * 2 * D + D, u, s, yp);
+            memcpy(s, yp, n);                                        /* the cell's output is the new state */
+            for (size_t e = 0; e < n; ++e) y[e] = (int8_t)sat127((int64_t)yp[e] + y[e]);
+            oracle_layernorm_i8(member_count, D, ln2 + (size_t)i * D, y, u);
+            forward_i8_worker(seed, step, base + 4, member_begin, member_count, 4 * D, D, bound, corr_shift, os_d, 1,
+                              antithetic, mlp1 + (size_t)i * 4 * DD, u, hid);
+            forward_i8_worker(seed, step, base + 5, member_begin, member_count, D, 4 * D, bound, corr_shift, os_4d, 1,
+                              antithetic, mlp2 + (size_t)i * 4 * DD, hid, yp);
+            for (size_t e = 0; e < n; ++e) y[e] = (int8_t)sat127((int64_t)yp[e] + y[e]);
+        }
+        oracle_layernorm_i8(member_count, D, ln_out, y, u);
+        forward_i8_worker(seed, step, layer + 1u + 6u * (uint32_t)L, member_begin, member_count, 256, D, bound,
+                          corr_shift, os_d, 1, antithetic, head, u, logits + (size_t)t * member_count * 256);
+    }
+    memcpy(S_out, state, (size_t)L * n);
+    free(y); free(u); free(yp); free(hid); free(state);
+    return 0;
+}
+
 int oracle_threads(void)
 {
 #ifdef _OPENMP
