@@ -140,6 +140,61 @@ egg_status eggroll_gru_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape,
                           const int8_t* S_in, int8_t* S_out);
 
 /*
+ * (2c) The integer model around the cell (App. "EGG architecture": Embedding, Layer Normalisation, MLP;
+ * Alg. "EGG forward pass").  All arrays are device pointers, 16-byte aligned, owned by the caller.
+ *
+ * Layer normalisation of int8 rows U[rows][D] with weight ln[D], D a power of two in [16, 1024]:
+ *   mav = max((sum_k |u_k|) >> log2 D, 1);   out_k = I8( trunc( I16(u_k) * I16(ln_k) / mav ) )
+ * (quotient toward zero; a row whose mean absolute value truncates to 0 divides by 1; I8 clips to
+ * [-127, 127]).  Not perturbed.  out may alias U.
+ */
+egg_status eggroll_layernorm_i8(eggroll_ctx* ctx, int64_t rows, int D, const int8_t* ln, const int8_t* U,
+                                int8_t* out);
+
+/*
+ * Perturbed embedding lookup (App. "Embedding"; "Adding EGGROLL Perturbations", last paragraph):
+ *   Y[m] = I8( emb[t_m] + ((A_i[t_m] * I32(B_i)) >> corr_shift) ),   emb: int8 [256][D], tokens: uint8 [member_count]
+ * A_i (length 256, indexed by the token) and B_i (length D) are the rank-1 factors of key.layer, so the
+ * perturbation A_i B_i^T has the table's layout and eggroll_update_i8 with d_out = 256, d_in = D updates the
+ * table.  shape: d_out = d_in = D (a power of two in [16, 1024]), rank 1, rows_per_member 1; antithetic as
+ * in (2').  No output scaling (a lookup is not a sum over n terms).  Y: int8 [member_count][D].
+ */
+egg_status eggroll_embed_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound, int corr_shift,
+                            const int8_t* emb, const uint8_t* tokens, int8_t* Y);
+
+/* Parameters of the integer model, L layers of width D (device pointers, int8). */
+typedef struct {
+    const int8_t* emb;    /* [256][D] */
+    const int8_t* ln1;    /* [L][D]         weight of the normalisation in front of the GRU */
+    const int8_t* gru_w;  /* [L][4][D][D]   Wf, Uf, Wh, Uh */
+    const int8_t* gru_b;  /* [L][2][D]      bf, bh */
+    const int8_t* ln2;    /* [L][D]         weight of the normalisation in front of the MLP */
+    const int8_t* mlp1;   /* [L][4D][D] */
+    const int8_t* mlp2;   /* [L][D][4D] */
+    const int8_t* ln_out; /* [D] */
+    const int8_t* head;   /* [256][D] */
+} egg_model_i8;
+
+/*
+ * Forward pass of the integer model for a population, `steps` tokens per member, state carried over:
+ *   y = EMBED(emb, t);  per layer i:  y', s'_i = GRU(LN(ln1_i, y), s_i),  y = I8(y' + y),
+ *                                     y' = (LN(ln2_i, y) @ mlp1_i^T) @ mlp2_i^T,  y = I8(y' + y);
+ *   logits = LN(ln_out, y) @ head^T
+ * Every "@" is the perturbed scaled matmul of (2') with out_shift = 4 + log2(sqrt d_in) (the division by
+ * 16 sqrt n), so D must be a power of 4: 16, 64, 256 or 1024.  Noise layers: key.layer the embedding,
+ * key.layer + 1 + 6 i + {0, 1, 2, 3: Wf, Uf, Wh, Uh; 4: mlp1; 5: mlp2}, key.layer + 1 + 6 L the head; the
+ * factors are generated once per call.  Normalisation weights and GRU biases are not perturbed.
+ * shape: d_out = d_in = D, rank 1, rows_per_member 1; antithetic as in (2').  layers >= 0.
+ * tokens: uint8 [steps][member_count]; S_in, S_out: int8 [layers][member_count][D], must not overlap
+ * (both may be NULL when layers == 0); logits: int8 [steps][member_count][256].  Scratch held by the
+ * context: about (18 layers + 2) D + 512 bytes per noise id for the factors, 11 D + 16 bytes per member for
+ * one step's activations and, when steps > 1, one more copy of the state.  Bit-exact.
+ */
+egg_status eggroll_egg_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int int_bound,
+                                  int corr_shift, int steps, const egg_model_i8* model, const uint8_t* tokens,
+                                  const int8_t* S_in, int8_t* S_out, int8_t* logits);
+
+/*
  * (3) Update direction (EGGROLL UPDATE box; Sec. 4.2 "(diag(f)A)^T B"):
  *   G[j][k] = (accumulate ? G[j][k] : 0) + scale * sum_i fitness[i] sum_l A_i[j][l] B_i[k][l]
  * G: fp32 [d_out][d_in].  fitness: fp32 [member_count], used as given (centring / z-scoring /

@@ -19,12 +19,20 @@ EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
            "eggroll_default_scale", "eggroll_noise_gen", "eggroll_perturbed_forward",
-           "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_update", "eggroll_update_i8",
+           "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
+           "eggroll_egg_forward_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
 
 
 class EggKey(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("step", ctypes.c_uint32), ("layer", ctypes.c_uint32)]
+
+
+EGG_MODEL_FIELDS = ("emb", "ln1", "gru_w", "gru_b", "ln2", "mlp1", "mlp2", "ln_out", "head")
+
+
+class EggModelI8(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in EGG_MODEL_FIELDS]
 
 
 class EggShape(ctypes.Structure):
@@ -74,6 +82,12 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_update.restype = i32
     lib.eggroll_gru_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.eggroll_gru_i8.restype = i32
+    lib.eggroll_layernorm_i8.argtypes = [vp, i64, i32, vp, vp, vp]
+    lib.eggroll_layernorm_i8.restype = i32
+    lib.eggroll_embed_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, vp, vp, vp]
+    lib.eggroll_embed_i8.restype = i32
+    lib.eggroll_egg_forward_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, P(EggModelI8), vp, vp, vp, vp]
+    lib.eggroll_egg_forward_i8.restype = i32
     lib.eggroll_update_i8.argtypes = [vp, EggKey, P(EggShape), i32, vp, ctypes.c_int32, vp, vp]
     lib.eggroll_update_i8.restype = i32
     lib.eggroll_int_threshold.argtypes = [ctypes.c_double, i64, ctypes.c_double]
@@ -159,6 +173,20 @@ class Context:
         self._check(self._lib.eggroll_gru_i8(
             self._h, key, ctypes.byref(shape), int_bound, corr_shift, out_shift, steps,
             _ptr(Wf), _ptr(Uf), _ptr(Wh), _ptr(Uh), _ptr(bf), _ptr(bh), _ptr(U), _ptr(S_in), _ptr(S_out)))
+
+    def eggroll_layernorm_i8(self, rows, D, ln, U, out):
+        self._check(self._lib.eggroll_layernorm_i8(self._h, int(rows), int(D), _ptr(ln), _ptr(U), _ptr(out)))
+
+    def eggroll_embed_i8(self, key, shape, int_bound, corr_shift, emb, tokens, Y):
+        self._check(self._lib.eggroll_embed_i8(
+            self._h, key, ctypes.byref(shape), int_bound, corr_shift, _ptr(emb), _ptr(tokens), _ptr(Y)))
+
+    def eggroll_egg_forward_i8(self, key, shape, layers, int_bound, corr_shift, steps, model, tokens, S_in, S_out, logits):
+        """model: mapping from the names in EGG_MODEL_FIELDS to int8 device tensors."""
+        m = EggModelI8(*[_ptr(model[name]) for name in EGG_MODEL_FIELDS])
+        self._check(self._lib.eggroll_egg_forward_i8(
+            self._h, key, ctypes.byref(shape), int(layers), int_bound, corr_shift, int(steps), ctypes.byref(m),
+            _ptr(tokens), _ptr(S_in), _ptr(S_out), _ptr(logits)))
 
     def eggroll_update(self, key, shape, noise_dtype, fitness, scale, accumulate, G, W=None, lr=0.0,
                        A_cache=None, B_cache=None):

@@ -274,6 +274,78 @@ egg_status eggroll_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, i
     return launch_gru_i8(c, key, *shape, int_bound, corr_shift, out_shift, steps, W, bf, bh, U, S_in, S_out);
 }
 
+static bool pow2_in(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
+
+egg_status eggroll_layernorm_i8(eggroll_ctx* c, int64_t rows, int D, const int8_t* ln, const int8_t* U, int8_t* out)
+{
+    if (!c) return EGG_EINVAL;
+    if (rows < 0) return fail(c, EGG_EINVAL, "rows must be >= 0");
+    if (!pow2_in(D, 16, 1024)) return fail(c, EGG_EUNSUPPORTED, "D must be a power of two in [16, 1024]");
+    if (!ln || !U || !out) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    if (!aligned16(ln) || !aligned16(U) || !aligned16(out)) return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
+    if (rows > (int64_t(1) << 31)) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    // with no residual to add the kernel only reads its y argument
+    return launch_layernorm_i8(c, nullptr, const_cast<int8_t*>(U), ln, out, rows, D);
+}
+
+static egg_status validate_model_shape(eggroll_ctx* c, egg_key key, const egg_shape* shape, uint32_t noise_layers,
+                                       int int_bound, int corr_shift)
+{
+    egg_status s = validate_shape(c, shape, false, true);
+    if (s != EGG_OK) return s;
+    if ((uint64_t)key.layer + noise_layers > 0x80000000ull) return fail(c, EGG_EINVAL, "noise layers must stay below 2^31");
+    if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
+    if (shape->d_out != shape->d_in) return fail(c, EGG_EINVAL, "d_out and d_in must both be the width D");
+    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (corr_shift < 0 || corr_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
+    if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
+    return EGG_OK;
+}
+
+egg_status eggroll_embed_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound, int corr_shift,
+                            const int8_t* emb, const uint8_t* tokens, int8_t* Y)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_model_shape(c, key, shape, 1, int_bound, corr_shift);
+    if (s != EGG_OK) return s;
+    if (!pow2_in(shape->d_in, 16, 1024)) return fail(c, EGG_EUNSUPPORTED, "D must be a power of two in [16, 1024]");
+    if (!emb || !tokens || !Y) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    if (!aligned16(emb) || !aligned16(Y)) return fail(c, EGG_EINVAL, "emb and Y must be 16-byte aligned");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_embed_i8(c, key, *shape, int_bound, corr_shift, emb, tokens, Y);
+}
+
+egg_status eggroll_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int layers, int int_bound,
+                                  int corr_shift, int steps, const egg_model_i8* model, const uint8_t* tokens,
+                                  const int8_t* S_in, int8_t* S_out, int8_t* logits)
+{
+    if (!c) return EGG_EINVAL;
+    if (layers < 0 || layers > 4096) return fail(c, EGG_EINVAL, "layers outside [0, 4096]");
+    egg_status s = validate_model_shape(c, key, shape, 2u + 6u * (uint32_t)layers, int_bound, corr_shift);
+    if (s != EGG_OK) return s;
+    const int D = shape->d_in;
+    if (D != 16 && D != 64 && D != 256 && D != 1024) return fail(c, EGG_EUNSUPPORTED, "D must be 16, 64, 256 or 1024 (a power of 4)");
+    if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");
+    if (!model || !tokens || !logits) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    const void* always[] = {model->emb, model->ln_out, model->head, logits};
+    for (const void* p : always)
+        if (!p || !aligned16(p)) return fail(c, EGG_EINVAL, "model and output pointers must be non-NULL and 16-byte aligned");
+    if (layers > 0) {
+        const void* per_layer[] = {model->ln1, model->gru_w, model->gru_b, model->ln2, model->mlp1, model->mlp2, S_in, S_out};
+        for (const void* p : per_layer)
+            if (!p || !aligned16(p)) return fail(c, EGG_EINVAL, "model and state pointers must be non-NULL and 16-byte aligned");
+        const size_t state_bytes = (size_t)layers * (size_t)shape->member_count * (size_t)D;
+        const uintptr_t a = reinterpret_cast<uintptr_t>(S_in), b = reinterpret_cast<uintptr_t>(S_out);
+        if (a < b + state_bytes && b < a + state_bytes) return fail(c, EGG_EINVAL, "S_in and S_out must not overlap");
+    }
+    // int32 accumulators of the widest contraction (4 D terms)
+    if ((int64_t)4 * D * 127 * 127 + (int64_t)4 * D * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+        return fail(c, EGG_EUNSUPPORTED, "D too large for int32 accumulation");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_egg_forward_i8(c, key, *shape, layers, int_bound, corr_shift, steps, *model, tokens, S_in, S_out, logits);
+}
+
 egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype noise_dtype,
                           const float* fitness, float scale, int accumulate, float* G, void* W, egg_dtype w_dtype,
                           float lr, const void* A_cache, const void* B_cache)

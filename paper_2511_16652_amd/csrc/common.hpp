@@ -88,9 +88,24 @@ egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, in
                             int* dots, bool dots_ready, const I8Gate* gate);
 egg_status launch_dots_i8(eggroll_ctx* c, const int8_t* X0, const int8_t* B0, const int8_t* B1, const int8_t* X1, const int8_t* B2,
                           int64_t rows, int d, int anti, int* d0, int* d1, int* d2);
+// factors, weights and intermediates of one GRU cell (matrix order: Wf, Uf, Wh, Uh)
+struct GruStep {
+    const int8_t *A[4], *B[4], *W[4];
+    const int8_t *bf, *bh;
+    int8_t *a1, *a3, *f, *fh;  // [rows][D] each
+    int* dot[4];               // [rows] each
+};
+egg_status launch_gru_step(eggroll_ctx* c, const GruStep& g, int anti, int64_t rows, int D, int int_bound, int corr_shift,
+                           int out_shift, const int8_t* u, const int8_t* state, int8_t* next);
 egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, int out_shift,
                          int steps, const int8_t* const W[4], const int8_t* bf, const int8_t* bh, const int8_t* U,
                          const int8_t* S_in, int8_t* S_out);
+egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D);
+egg_status launch_embed_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, const int8_t* emb,
+                           const uint8_t* tokens, int8_t* Y);
+egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int int_bound, int corr_shift, int T,
+                                 const egg_model_i8& P, const uint8_t* tokens, const int8_t* S_in, int8_t* S_out,
+                                 int8_t* logits);
 egg_status launch_update_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                             int int_bound, const int8_t* F, int32_t threshold, int8_t* theta, int32_t* E_out);
 

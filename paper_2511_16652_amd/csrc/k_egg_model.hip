@@ -1,0 +1,229 @@
+// The integer model around the GRU cell (App. "EGG architecture": Embedding, Layer Normalisation, MLP,
+// Alg. "EGG forward pass"), for a population of members with one token each per time step, bit-exact:
+//     y = EMBED(emb, t)
+//     per layer:  y', s' = GRU(LN(ln1, y), s);  y = I8(y' + y);   y' = (LN(ln2, y) @ mlp1^T) @ mlp2^T;  y = I8(y' + y)
+//     logits = LN(ln_out, y) @ head^T
+// "@" is the perturbed scaled int8 matmul (MFMA kernels of the integer path); the row-wise pieces here
+// are bandwidth work: a lane owns 16 consecutive bytes of a row, D/16 adjacent lanes own the row.
+//   * the residual add is fused with the layer normalisation that follows it (one read of y and of the
+//     block's output, one write each of y and of the normalised row);
+//   * DIVIDE(x, mav): |x| <= 127^2 < 2^14 and mav < 2^7, so floor(|x| / mav) = (|x| * ceil(2^21 / mav)) >> 21
+//     exactly (the multiplier's excess (mav - 1) * |x| stays below 2^21); one integer division per lane
+//     for the multiplier, a multiply-high per element -- no table.
+#include "common.hpp"
+
+namespace egg {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int sat127(int v) { return min(127, max(-127, v)); }
+__device__ __forceinline__ int sbyte(uint32_t w, int b) { return (int)(int8_t)(w >> (8 * b)); }
+
+// y[row] = I8(y[row] + add[row]) when add != nullptr (written back), then u[row] = LN(ln, y[row]).
+__global__ __launch_bounds__(256) void resid_ln_kernel(const int8_t* __restrict__ add, int8_t* __restrict__ y,
+                                                       const int8_t* __restrict__ ln, int8_t* __restrict__ u,
+                                                       int64_t rows, int lpr_log2, int d_log2)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = gid >> lpr_log2;
+    const int part = (int)(gid & ((1 << lpr_log2) - 1));
+    const bool live = row < rows;   // dead lanes run the shuffles with zeros
+    const size_t off = ((size_t)row << d_log2) + (size_t)part * 16;
+    u32x4 yv = {0, 0, 0, 0};
+    if (live) {
+        yv = *(const u32x4*)(y + off);
+        if (add) {
+            const u32x4 av = *(const u32x4*)(add + off);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t yw = yv[w], aw = av[w];
+                uint32_t o = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) o |= (uint32_t)(sat127(sbyte(yw, b) + sbyte(aw, b)) & 0xFF) << (8 * b);
+                yv[w] = o;
+            }
+            *(u32x4*)(y + off) = yv;
+        }
+    }
+    int sum = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t yw = yv[w];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) sum += abs(sbyte(yw, b));
+    }
+    for (int o = 1; o < (1 << lpr_log2); o <<= 1) sum += __shfl_xor(sum, o, 64);
+    if (!live) return;
+    const uint32_t mav = (uint32_t)max(sum >> d_log2, 1);
+    const uint32_t magic = ((1u << 21) + mav - 1u) / mav;
+    const u32x4 lv = *(const u32x4*)(ln + (size_t)part * 16);
+    u32x4 ov;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t yw = yv[w], lw = lv[w];
+        uint32_t o = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int prod = sbyte(yw, b) * sbyte(lw, b);
+            const int q = (int)__umulhi((uint32_t)abs(prod) << 11, magic);
+            o |= (uint32_t)((prod < 0 ? -min(q, 127) : min(q, 127)) & 0xFF) << (8 * b);
+        }
+        ov[w] = o;
+    }
+    *(u32x4*)(u + off) = ov;
+}
+
+// y[row] = I8(emb[t] + ((A[id][t] * +-B[id]) >> corr_shift)), t = tokens[row]; the odd member of an
+// antithetic pair carries the negated B.
+__global__ __launch_bounds__(256) void embed_i8_kernel(const int8_t* __restrict__ emb, const uint8_t* __restrict__ tokens,
+                                                       const int8_t* __restrict__ A, const int8_t* __restrict__ B,
+                                                       int8_t* __restrict__ y, int64_t rows, int lpr_log2, int d_log2,
+                                                       int anti, int corr_shift)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = gid >> lpr_log2;
+    if (row >= rows) return;
+    const int part = (int)(gid & ((1 << lpr_log2) - 1));
+    const int64_t id = anti ? (row >> 1) : row;
+    const int t = tokens[row];
+    int a = A[(size_t)id * 256 + t];
+    if (anti && (row & 1)) a = -a;
+    const u32x4 bv = *(const u32x4*)(B + ((size_t)id << d_log2) + (size_t)part * 16);
+    const u32x4 ev = *(const u32x4*)(emb + ((size_t)t << d_log2) + (size_t)part * 16);
+    u32x4 ov;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t bw = bv[w], ew = ev[w];
+        uint32_t o = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) o |= (uint32_t)(sat127(sbyte(ew, b) + ((a * sbyte(bw, b)) >> corr_shift)) & 0xFF) << (8 * b);
+        ov[w] = o;
+    }
+    *(u32x4*)(y + ((size_t)row << d_log2) + (size_t)part * 16) = ov;
+}
+
+static int ilog2(int v)
+{
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D)
+{
+    if (rows == 0) return EGG_OK;
+    KernelScope ks(c, "resid_layernorm_i8");
+    const int lpr = ilog2(D / 16);
+    const int64_t threads = rows << lpr;
+    hipLaunchKernelGGL(resid_ln_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, add, y, ln, u, rows, lpr, ilog2(D));
+    return check_hip(c, hipGetLastError(), "resid_layernorm_i8 launch");
+}
+
+static egg_status launch_embed(eggroll_ctx* c, const int8_t* emb, const uint8_t* tokens, const int8_t* A, const int8_t* B,
+                               int8_t* y, int64_t rows, int D, int anti, int corr_shift)
+{
+    if (rows == 0) return EGG_OK;
+    KernelScope ks(c, "embed_i8");
+    const int lpr = ilog2(D / 16);
+    const int64_t threads = rows << lpr;
+    hipLaunchKernelGGL(embed_i8_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, emb, tokens, A, B, y, rows, lpr,
+                       ilog2(D), anti, corr_shift);
+    return check_hip(c, hipGetLastError(), "embed_i8 launch");
+}
+
+egg_status launch_embed_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, const int8_t* emb,
+                           const uint8_t* tokens, int8_t* Y)
+{
+    const int D = s.d_in;
+    const int64_t rows = s.member_count;
+    const int anti = s.antithetic ? 1 : 0;
+    const int64_t ids = anti ? rows / 2 : rows;
+    const uint32_t first_id = (uint32_t)(anti ? s.member_begin / 2 : s.member_begin);
+    egg_status st;
+    if ((st = reserve(c, c->i8_a, (size_t)ids * 256)) != EGG_OK) return st;
+    if ((st = reserve(c, c->i8_b, (size_t)ids * D)) != EGG_OK) return st;
+    int8_t *A = (int8_t*)c->i8_a.p, *B = (int8_t*)c->i8_b.p;
+    if ((st = launch_noise(c, make_stream_key(key.seed, key.step, key.layer, 0), first_id, ids, 256, EGG_I8, EGG_UNIFORM_INT, int_bound, A)) != EGG_OK) return st;
+    if ((st = launch_noise(c, make_stream_key(key.seed, key.step, key.layer, 1), first_id, ids, D, EGG_I8, EGG_UNIFORM_INT, int_bound, B)) != EGG_OK) return st;
+    return launch_embed(c, emb, tokens, A, B, Y, rows, D, anti, corr_shift);
+}
+
+// Scratch of one forward call: the rank-1 factors of all 6 L + 2 perturbed parameters (generated once per
+// call: a member's perturbation is fixed while it is evaluated, Alg. 1), the activations of one time
+// step, and a second copy of the recurrent state to ping-pong with S_out.
+egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int int_bound, int corr_shift, int T,
+                                 const egg_model_i8& P, const uint8_t* tokens, const int8_t* S_in, int8_t* S_out,
+                                 int8_t* logits)
+{
+    const int D = s.d_in;
+    const int64_t rows = s.member_count;
+    const int anti = s.antithetic ? 1 : 0;
+    const int64_t ids = anti ? rows / 2 : rows;
+    const uint32_t first_id = (uint32_t)(anti ? s.member_begin / 2 : s.member_begin);
+    const int os_d = 4 + ilog2(D) / 2, os_4d = os_d + 1;   // 16 sqrt(n) as a shift, n = D and 4 D
+    auto pad = [](size_t b) { return (b + 255) & ~size_t(255); };
+    const size_t fD = pad((size_t)ids * D), f4D = pad((size_t)ids * 4 * D), f256 = pad((size_t)ids * 256);
+    const size_t act = pad((size_t)rows * D), dots = pad((size_t)rows * sizeof(int));
+    const size_t per_layer = 8 * fD + 2 * (f4D + fD);
+    const size_t total = 2 * (f256 + fD) + (size_t)L * per_layer   // factors
+                         + 7 * act + 4 * act                        // y, u, y', a1, a3, f, f^; MLP hidden
+                         + 4 * dots + (T > 1 ? (size_t)L * act : 0);
+    egg_status st;
+    if ((st = reserve(c, c->gru, total)) != EGG_OK) return st;
+    char* p = (char*)c->gru.p;
+    auto take = [&](size_t b) { char* q = p; p += b; return (int8_t*)q; };
+    auto gen = [&](uint32_t layer, int which, int n, int8_t* out) {
+        return launch_noise(c, make_stream_key(key.seed, key.step, layer, which), first_id, ids, n, EGG_I8, EGG_UNIFORM_INT, int_bound, out);
+    };
+    int8_t* embA = take(f256); int8_t* embB = take(fD);
+    int8_t* headA = take(f256); int8_t* headB = take(fD);
+    const uint32_t head_layer = key.layer + 1u + 6u * (uint32_t)L;
+    if ((st = gen(key.layer, 0, 256, embA)) != EGG_OK || (st = gen(key.layer, 1, D, embB)) != EGG_OK) return st;
+    if ((st = gen(head_layer, 0, 256, headA)) != EGG_OK || (st = gen(head_layer, 1, D, headB)) != EGG_OK) return st;
+    struct LayerFactors { int8_t *A[4], *B[4], *A1, *B1, *A2, *B2; };
+    std::vector<LayerFactors> F((size_t)L);
+    for (int i = 0; i < L; ++i) {
+        const uint32_t base = key.layer + 1u + 6u * (uint32_t)i;
+        for (int m = 0; m < 4; ++m) {
+            F[i].A[m] = take(fD); F[i].B[m] = take(fD);
+            if ((st = gen(base + m, 0, D, F[i].A[m])) != EGG_OK || (st = gen(base + m, 1, D, F[i].B[m])) != EGG_OK) return st;
+        }
+        F[i].A1 = take(f4D); F[i].B1 = take(fD); F[i].A2 = take(fD); F[i].B2 = take(f4D);
+        if ((st = gen(base + 4, 0, 4 * D, F[i].A1)) != EGG_OK || (st = gen(base + 4, 1, D, F[i].B1)) != EGG_OK) return st;
+        if ((st = gen(base + 5, 0, D, F[i].A2)) != EGG_OK || (st = gen(base + 5, 1, 4 * D, F[i].B2)) != EGG_OK) return st;
+    }
+    int8_t *y = take(act), *u = take(act), *yp = take(act), *a1 = take(act), *a3 = take(act), *f = take(act), *fh = take(act);
+    int8_t* hid = take(4 * act);
+    int* dot[4];
+    for (int m = 0; m < 4; ++m) dot[m] = (int*)take(dots);
+    int8_t* S_alt = T > 1 ? take((size_t)L * act) : nullptr;
+    const size_t DD = (size_t)D * D, state_stride = (size_t)rows * D;
+
+    for (int t = 0; t < T; ++t) {
+        // the last time step writes S_out; the ones before it alternate so that no step reads what it writes
+        const int8_t* s_from = t == 0 ? S_in : (((T - t) & 1) ? S_alt : S_out);
+        int8_t* s_to = ((T - 1 - t) & 1) ? S_alt : S_out;
+        const size_t from_stride = t == 0 ? state_stride : (s_from == S_alt ? act : state_stride);
+        const size_t to_stride = s_to == S_alt ? act : state_stride;
+        if ((st = launch_embed(c, P.emb, tokens + (size_t)t * rows, embA, embB, y, rows, D, anti, corr_shift)) != EGG_OK) return st;
+        const int8_t* add = nullptr;
+        for (int i = 0; i < L; ++i) {
+            if ((st = launch_layernorm_i8(c, add, y, P.ln1 + (size_t)i * D, u, rows, D)) != EGG_OK) return st;
+            GruStep g;
+            for (int m = 0; m < 4; ++m) { g.A[m] = F[i].A[m]; g.B[m] = F[i].B[m]; g.W[m] = P.gru_w + ((size_t)i * 4 + m) * DD; g.dot[m] = dot[m]; }
+            g.bf = P.gru_b + (size_t)i * 2 * D; g.bh = g.bf + D;
+            g.a1 = a1; g.a3 = a3; g.f = f; g.fh = fh;
+            int8_t* h = s_to + (size_t)i * to_stride;
+            if ((st = launch_gru_step(c, g, anti, rows, D, int_bound, corr_shift, os_d, u, s_from + (size_t)i * from_stride, h)) != EGG_OK) return st;
+            if ((st = launch_layernorm_i8(c, h, y, P.ln2 + (size_t)i * D, u, rows, D)) != EGG_OK) return st;
+            if ((st = launch_i8_matmul(c, F[i].A1, F[i].B1, anti, rows, 4 * D, D, int_bound, corr_shift, os_d, P.mlp1 + (size_t)i * 4 * DD, u, hid, dot[0], false, nullptr)) != EGG_OK) return st;
+            if ((st = launch_i8_matmul(c, F[i].A2, F[i].B2, anti, rows, D, 4 * D, int_bound, corr_shift, os_4d, P.mlp2 + (size_t)i * 4 * DD, hid, yp, dot[1], false, nullptr)) != EGG_OK) return st;
+            add = yp;
+        }
+        if ((st = launch_layernorm_i8(c, add, y, P.ln_out, u, rows, D)) != EGG_OK) return st;
+        if ((st = launch_i8_matmul(c, headA, headB, anti, rows, 256, D, int_bound, corr_shift, os_d, P.head, u, logits + (size_t)t * rows * 256, dot[0], false, nullptr)) != EGG_OK) return st;
+    }
+    return EGG_OK;
+}
+
+}  // namespace egg

@@ -12,6 +12,25 @@
 
 namespace egg {
 
+// One time step of the cell for all rows: u and the old state in, the new state out.
+egg_status launch_gru_step(eggroll_ctx* c, const GruStep& g, int anti, int64_t rows, int D, int int_bound, int corr_shift,
+                           int out_shift, const int8_t* u, const int8_t* state, int8_t* next)
+{
+    egg_status st;
+    // u . B_Wf, u . B_Wh and s . B_Uf in one pass over u and s; f^ . B_Uh once f^ exists
+    if ((st = launch_dots_i8(c, u, g.B[0], g.B[2], state, g.B[1], rows, D, anti, g.dot[0], g.dot[2], g.dot[1])) != EGG_OK) return st;
+    // the gates ride in the epilogues of the second matmul of each pair: a2 and a4 never reach memory
+    const I8Gate g1{1, g.a1, state, nullptr, g.bf, g.fh}, g2{2, g.a3, state, g.f, g.bh, nullptr};
+#define EGG_MM(M, SRC, DST, READY, GATE) \
+    if ((st = launch_i8_matmul(c, g.A[M], g.B[M], anti, rows, D, D, int_bound, corr_shift, out_shift, g.W[M], SRC, DST, g.dot[M], READY, GATE)) != EGG_OK) return st;
+    EGG_MM(0, u, g.a1, true, nullptr)
+    EGG_MM(2, u, g.a3, true, nullptr)
+    EGG_MM(1, state, g.f, true, &g1)   // writes f and f^
+    EGG_MM(3, g.fh, next, false, &g2)  // computes f^ . B_Uh first; writes h
+#undef EGG_MM
+    return EGG_OK;
+}
+
 egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, int out_shift,
                          int steps, const int8_t* const W[4], const int8_t* bf, const int8_t* bh, const int8_t* U,
                          const int8_t* S_in, int8_t* S_out)
@@ -37,25 +56,16 @@ egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int in
     }
     int8_t* buf[6];
     for (int b = 0; b < 6; ++b) buf[b] = (int8_t*)(base + 8 * fac + b * act);
-    int8_t *a1 = buf[0], *a3 = buf[1], *f = buf[2], *fh = buf[3];
     int* dot[4];
     for (int m = 0; m < 4; ++m) dot[m] = (int*)(base + 8 * fac + 6 * act + m * dots);
 
+    GruStep g;
+    for (int m = 0; m < 4; ++m) { g.A[m] = A[m]; g.B[m] = B[m]; g.W[m] = W[m]; g.dot[m] = dot[m]; }
+    g.a1 = buf[0]; g.a3 = buf[1]; g.f = buf[2]; g.fh = buf[3]; g.bf = bf; g.bh = bh;
     const int8_t* state = S_in;
     for (int t = 0; t < steps; ++t) {
-        const int8_t* u = U + (size_t)t * rows * D;
         int8_t* next = (t == steps - 1) ? S_out : buf[4 + (t & 1)];
-        // u . B_Wf, u . B_Wh and s . B_Uf in one pass over u and s; f^ . B_Uh once f^ exists
-        if ((st = launch_dots_i8(c, u, B[0], B[2], state, B[1], rows, D, anti, dot[0], dot[2], dot[1])) != EGG_OK) return st;
-        // the gates ride in the epilogues of the second matmul of each pair: a2 and a4 never reach memory
-        const I8Gate g1{1, a1, state, nullptr, bf, fh}, g2{2, a3, state, f, bh, nullptr};
-#define EGG_MM(M, SRC, DST, READY, GATE) \
-        if ((st = launch_i8_matmul(c, A[M], B[M], anti, rows, D, D, int_bound, corr_shift, out_shift, W[M], SRC, DST, dot[M], READY, GATE)) != EGG_OK) return st;
-        EGG_MM(0, u, a1, true, nullptr)
-        EGG_MM(2, u, a3, true, nullptr)
-        EGG_MM(1, state, f, true, &g1)     // writes f and f^
-        EGG_MM(3, fh, next, false, &g2)    // computes f^ . B_Uh first; writes h
-#undef EGG_MM
+        if ((st = launch_gru_step(c, g, anti, rows, D, int_bound, corr_shift, out_shift, U + (size_t)t * rows * D, state, next)) != EGG_OK) return st;
         state = next;
     }
     return EGG_OK;

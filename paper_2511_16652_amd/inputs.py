@@ -110,3 +110,33 @@ def make_int8(name, d, N, steps, data_seed, bound=8, corr_shift=4, out_shift=8) 
 
 def config3(N: int = 8192, d: int = 1024, steps: int = 64) -> Int8Workload:
     return make_int8("cfg3_i8_%d_N%d_T%d" % (d, N, steps), d, N, steps, 1003)
+
+
+EGG_PARAM_SHAPES = lambda D, L: {  # noqa: E731  (layouts of the integer model's parameter arrays)
+    "emb": (256, D), "ln1": (L, D), "gru_w": (L, 4, D, D), "gru_b": (L, 2, D), "ln2": (L, D),
+    "mlp1": (L, 4 * D, D), "mlp2": (L, D, 4 * D), "ln_out": (D,), "head": (256, D)}
+
+
+def egg_model(D: int, L: int, data_seed: int, weight_std: float = 16.0, ln_weight: int = 16) -> dict:
+    """Synthetic parameters of the integer model: matrices and the embedding table are 16 * N(0, 1)
+    rounded to the nearest integer and clipped to [-127, 127] (the initialisation the paper's scaled
+    matmul is designed around), normalisation weights a constant, biases zero."""
+    rng = np.random.default_rng(data_seed)
+    out = {}
+    for name, shape in EGG_PARAM_SHAPES(D, L).items():
+        if name in ("ln1", "ln2", "ln_out"):
+            out[name] = np.full(shape, ln_weight, np.int8)
+        elif name == "gru_b":
+            out[name] = np.zeros(shape, np.int8)
+        else:
+            out[name] = np.clip(np.rint(weight_std * rng.standard_normal(shape)), -127, 127).astype(np.int8)
+    return out
+
+
+def egg_tokens(T: int, N: int, data_seed: int) -> np.ndarray:
+    """Synthetic byte tokens [T, N] standing in for a character-level corpus: a skewed distribution over
+    the printable range (frequent letters, space), independent per member and time step."""
+    rng = np.random.default_rng(data_seed)
+    alphabet = np.arange(32, 127)
+    weights = 1.0 / (1.0 + np.arange(alphabet.size))      # Zipf-like
+    return rng.choice(rng.permutation(alphabet), size=(T, N), p=weights / weights.sum()).astype(np.uint8)

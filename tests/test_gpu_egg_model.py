@@ -1,0 +1,145 @@
+"""GPU parity: the integer model around the GRU cell -- layer normalisation, perturbed embedding lookup and
+the composed forward pass -- bit for bit against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_16652_amd import binding as eb
+from paper_2511_16652_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+SEED, STEP, LAYER = 12, 1, 7
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    c = eb.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("D,rows", [(16, 1), (16, 1000), (64, 333), (128, 77), (256, 4099), (512, 65), (1024, 130)])
+def test_layernorm_bit_exact(ctx, D, rows):
+    rng = np.random.default_rng(D + rows)
+    ln = rng.integers(-127, 128, D).astype(np.int8)
+    U = rng.integers(-127, 128, (rows, D)).astype(np.int8)
+    k = rows // 3
+    U[:k] = rng.integers(-3, 4, (k, D))                     # small rows: divisor 0 -> 1, 1, 2
+    out = dev(np.zeros_like(U))
+    ctx.eggroll_layernorm_i8(rows, D, dev(ln), dev(U), out)
+    assert (out.cpu().numpy() == oracle.layernorm_i8(ln, U)).all()
+
+
+def test_layernorm_every_divisor_and_every_product(ctx):
+    # row m has |u| <= 127 arranged so that its mean absolute value is m (m = 0 .. 127); weights and
+    # entries sweep their whole range, so every (|product| bucket, divisor) pair of the divide occurs
+    D = 256
+    rng = np.random.default_rng(0)
+    rows = []
+    for m in range(128):
+        for rep in range(8):
+            mag = np.clip(m + rng.integers(-min(m, 127 - m), min(m, 127 - m) + 1, D), 0, 127)
+            rows.append(mag * rng.choice([-1, 1], D))
+    U = np.array(rows, np.int8)
+    for w in (127, -127, 1, 64):
+        ln = np.full(D, w, np.int8)
+        ln[1::2] = rng.integers(-127, 128, D // 2)
+        out = dev(np.zeros_like(U))
+        ctx.eggroll_layernorm_i8(U.shape[0], D, dev(ln), dev(U), out)
+        assert (out.cpu().numpy() == oracle.layernorm_i8(ln, U)).all()
+    mav = np.abs(U.astype(np.int64)).sum(1) >> 8
+    assert set(mav.tolist()) >= set(range(1, 127))
+
+
+def test_layernorm_in_place(ctx):
+    D, rows = 256, 513
+    rng = np.random.default_rng(3)
+    ln = rng.integers(-127, 128, D).astype(np.int8)
+    U = rng.integers(-127, 128, (rows, D)).astype(np.int8)
+    buf = dev(U)
+    ctx.eggroll_layernorm_i8(rows, D, dev(ln), buf, buf)
+    assert (buf.cpu().numpy() == oracle.layernorm_i8(ln, U)).all()
+
+
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("D,N,mb,anti,cs", [(16, 50, 3, 0, 0), (64, 1026, 4, 1, 2), (256, 700, 0, 0, 4), (1024, 66, 10, 1, 3)])
+def test_embedding_bit_exact(ctx, D, N, mb, anti, cs):
+    rng = np.random.default_rng(D + N)
+    emb = rng.integers(-127, 128, (256, D)).astype(np.int8)
+    tok = rng.integers(0, 256, N).astype(np.uint8)
+    out = dev(np.zeros((N, D), np.int8))
+    ctx.eggroll_embed_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(mb, N, 1, D, D, 1, antithetic=anti), 8, cs, dev(emb), dev(tok), out)
+    want = oracle.embed_i8(SEED, STEP, LAYER, mb, N, D, 8, cs, emb, tok, antithetic=bool(anti))
+    got = out.cpu().numpy()
+    assert (got == want).all() and (got != emb[tok]).any()
+
+
+# ---------------------------------------------------------------------------------------------------
+def run_model(ctx, P, D, L, N, T, mb, anti, tok, S, bound=8, cs=4):
+    import torch
+    model = {k: dev(v) for k, v in P.items()}
+    S_out = torch.empty((L, N, D), dtype=torch.int8, device="cuda")
+    logits = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+    ctx.eggroll_egg_forward_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(mb, N, 1, D, D, 1, antithetic=anti), L, bound, cs, T,
+                               model, dev(tok), dev(S), S_out, logits)
+    torch.cuda.synchronize()
+    return logits.cpu().numpy(), S_out.cpu().numpy()
+
+
+@pytest.mark.parametrize("D,L,N,T,mb,anti", [(64, 2, 130, 1, 0, 0), (256, 2, 300, 3, 4, 1), (16, 3, 70, 2, 1, 0),
+                                              (256, 6, 258, 2, 0, 0), (64, 0, 40, 2, 0, 0), (1024, 1, 40, 2, 0, 1)])
+def test_forward_bit_exact(ctx, D, L, N, T, mb, anti):
+    P = inputs.egg_model(D, L, 100 + D + L)
+    rng = np.random.default_rng(N)
+    for k in ("ln1", "ln2", "ln_out"):
+        P[k] = rng.integers(8, 25, P[k].shape).astype(np.int8)
+    P["gru_b"] = rng.integers(-20, 21, P["gru_b"].shape).astype(np.int8)
+    tok = inputs.egg_tokens(T, N, 5)
+    S = rng.integers(-60, 61, (L, N, D)).astype(np.int8)
+    logits, S_out = run_model(ctx, P, D, L, N, T, mb, anti, tok, S)
+    want, S_want = oracle.egg_forward_i8(SEED, STEP, LAYER, mb, N, D, L, 8, 4, P, tok, S, antithetic=bool(anti))
+    assert (S_out == S_want).all()
+    assert (logits == want).all()
+    assert want.std() > 3 and (np.abs(want) == 127).mean() < 0.5      # the logits carry information
+    if L:
+        assert (S_want != S).mean() > 0.5
+
+
+def test_forward_noise_matters_and_pairs_mirror(ctx):
+    # without noise members with the same token history agree; with antithetic noise the two members of
+    # a pair differ from each other and from the unperturbed run
+    D, L, N, T = 64, 2, 64, 3
+    P = inputs.egg_model(D, L, 9)
+    tok = np.repeat(inputs.egg_tokens(T, 1, 6), N, axis=1)
+    S = np.zeros((L, N, D), np.int8)
+    quiet, _ = run_model(ctx, P, D, L, N, T, 0, 0, tok, S, bound=0)
+    assert (quiet == quiet[:, :1]).all()
+    noisy, _ = run_model(ctx, P, D, L, N, T, 0, 1, tok, S, bound=8, cs=2)
+    assert (noisy[:, 0::2] != noisy[:, 1::2]).any() and (noisy != quiet).any()
+    want, _ = oracle.egg_forward_i8(SEED, STEP, LAYER, 0, N, D, L, 8, 2, P, tok, S, antithetic=True)
+    assert (noisy == want).all()
+
+
+def test_forward_rejects_bad_arguments(ctx):
+    import torch
+    D, L, N, T = 64, 1, 16, 1
+    P = {k: dev(v) for k, v in inputs.egg_model(D, L, 1).items()}
+    tok = dev(inputs.egg_tokens(T, N, 1))
+    S = torch.zeros((L, N, D), dtype=torch.int8, device="cuda")
+    lg = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+    key = eb.make_key(SEED, STEP, LAYER)
+    with pytest.raises(eb.EggrollError):       # state in place
+        ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N, 1, D, D, 1), L, 8, 4, T, P, tok, S, S, lg)
+    with pytest.raises(eb.EggrollError):       # width not a power of 4
+        ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N, 1, 128, 128, 1), L, 8, 4, T, P, tok, S, torch.empty_like(S), lg)
+    with pytest.raises(eb.EggrollError):       # odd population with pairs
+        ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N - 1, 1, D, D, 1, antithetic=1), L, 8, 4, T, P, tok, S, torch.empty_like(S), lg)
