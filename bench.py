@@ -8,7 +8,7 @@ in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload W] [--no-cpu-baseline]
 
-Workloads: cfg2 (default), cfg1, cfg3 (int8 recurrence + integer update), gru (integer GRU cell),
+Workloads: cfg2 (default), cfg1, cfg3 (int8 recurrence + integer update), gru (integer GRU cell), egg (integer model forward),
 p0, p0_r2, p0_r4, p0_r8, mlp_up, mlp_down, ffn_up, attn_proj.
 """
 from __future__ import annotations
@@ -445,6 +445,77 @@ def gru_workload(args):
     return res
 
 
+def egg_workload(args):
+    """The integer model's forward pass at the paper's pretraining shape: D = 256, 6 layers, 2^18 members,
+    16 tokens per member and call, antithetic pairs."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_16652_amd import binding as eb
+    from paper_2511_16652_amd import inputs
+
+    D, L, N, T, bound, cs, anti = 256, 6, 1 << 18, 16, 8, 4, 1
+    P = inputs.egg_model(D, L, 1006)
+    tok = inputs.egg_tokens(T, N, 1007)
+    model = {k: torch.from_numpy(v).cuda() for k, v in P.items()}
+    tokens = torch.from_numpy(tok).cuda()
+    S = torch.zeros((L, N, D), dtype=torch.int8, device="cuda")
+    S_out = torch.empty_like(S)
+    logits = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+    ctx = eb.Context(0)
+    key, shape = eb.make_key(0, 0, 0), eb.make_shape(0, N, 1, D, D, 1, antithetic=anti)
+
+    def step():
+        ctx.eggroll_egg_forward_i8(key, shape, L, bound, cs, T, model, tokens, S, S_out, logits)
+
+    prewarm(step)
+    t_step = timed(step, args.steps, args.warmup)
+    ctx.profile_enable(True)
+    for _ in range(min(args.steps, 5)):
+        step()
+    kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms} for k, (n, ms) in ctx.profile_read().items()}
+    ctx.profile_enable(False)
+    # per member and token: 12 D^2 MACs per layer (4 D^2 GRU, 8 D^2 MLP) + 256 D for the head;
+    # HBM bytes the method needs with the factors kept in memory for the episode: the token, the state in
+    # and out (2 L D), the logits (256), each factor row once ((18 L + 2) D + 512 per noise id)
+    ops = 2.0 * (12 * L * D * D + 256 * D) * N * T
+    bytes_alg = (1 + 2 * L * D + 256 + ((18 * L + 2) * D + 512) / (2 if anti else 1)) * N * T
+    res = {
+        "metric": "population tokens/sec (integer model forward), 1 GPU",
+        "value": N * T / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+        "data": "synthetic",
+        "config": {"workload": "egg_D256_L6_N262144_T16", "D": D, "layers": L, "population": N, "tokens_per_member": T,
+                   "bound": bound, "antithetic": bool(anti)},
+        "roofline": {"bound": "hbm", "achieved": bytes_alg / t_step / 1e9, "peak": 8000.0, "unit": "GB/s",
+                     "frac": bytes_alg / t_step / 8e12, "traffic": None},
+        "int8_TOPs": ops / t_step / 1e12,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        def run(m):
+            t0 = time.perf_counter()
+            oracle.egg_forward_i8(0, 0, 0, 0, m, D, L, bound, cs, P, tok[:, :m], np.zeros((L, m, D), np.int8), antithetic=bool(anti))
+            return time.perf_counter() - t0
+
+        th = oracle.threads()
+        m = 2 * th
+        dt = run(m)
+        for _ in range(2):  # size the sample to about 12 s of oracle time (the cost is linear in members)
+            if dt >= 8.0 or m >= N:
+                break
+            want = min(N, max(m, int(12.0 * m / max(dt, 1e-6)) // (2 * th) * (2 * th)))
+            if want == m:
+                break
+            m = want
+            dt = run(m)
+        res["cpu_baseline"] = {"value": m * T / dt, "unit": "tokens/s", "cores": th, "kind": "oracle",
+                               "sample": "%d of %d members, all %d tokens (%.2f s)" % (m, N, T, dt)}
+    ctx.close()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -455,6 +526,8 @@ def main():
         res = int8_workload(args)
     elif args.workload == "gru":
         res = gru_workload(args)
+    elif args.workload == "egg":
+        res = egg_workload(args)
     else:
         res = linear_workload(args)
     print(json.dumps(res))

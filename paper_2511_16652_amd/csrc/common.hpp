@@ -85,7 +85,8 @@ struct I8Gate {
 };
 egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
                             int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
-                            int* dots, bool dots_ready, const I8Gate* gate);
+                            int* dots, bool dots_ready, const I8Gate* gate, const int8_t* B_next = nullptr, int* dots_next = nullptr);
+egg_status launch_zero_i32(eggroll_ctx* c, int* p0, int* p1, int64_t n);  // clears one or two int32 vectors (p1 may be NULL)
 egg_status launch_dots_i8(eggroll_ctx* c, const int8_t* X0, const int8_t* B0, const int8_t* B1, const int8_t* X1, const int8_t* B2,
                           int64_t rows, int d, int anti, int* d0, int* d1, int* d2);
 // factors, weights and intermediates of one GRU cell (matrix order: Wf, Uf, Wh, Uh)
@@ -93,14 +94,27 @@ struct GruStep {
     const int8_t *A[4], *B[4], *W[4];
     const int8_t *bf, *bh;
     int8_t *a1, *a3, *f, *fh;  // [rows][D] each
-    int* dot[4];               // [rows] each
+    int* dot[4];               // [rows] each: u.B_Wf, s.B_Uf, u.B_Wh, f^.B_Uh
+    bool u_dots_ready = false; // dot[0] and dot[2] were filled by whoever produced u
+    bool s_dot_ready = false;  // dot[1] was filled by the previous step's last epilogue
+    bool fh_dot_zeroed = false;// dot[3] is zero: the first gate's epilogue accumulates f^.B_Uh there
+    int* dot_s_next = nullptr; // zeroed [rows]: the last epilogue accumulates h.B_Uf for the next step there
 };
 egg_status launch_gru_step(eggroll_ctx* c, const GruStep& g, int anti, int64_t rows, int D, int int_bound, int corr_shift,
                            int out_shift, const int8_t* u, const int8_t* state, int8_t* next);
 egg_status launch_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, int out_shift,
                          int steps, const int8_t* const W[4], const int8_t* bf, const int8_t* bh, const int8_t* U,
                          const int8_t* S_in, int8_t* S_out);
-egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D);
+// optional by-products of the normalisation pass: dot products of the normalised rows with up to two factor
+// arrays (what the matmuls that consume u need), and up to two int32 vectors cleared for later accumulation
+struct LnExtras {
+    const int8_t* B[2] = {nullptr, nullptr};  // [ids][D]
+    int* dot[2] = {nullptr, nullptr};         // [rows]
+    int* zero[2] = {nullptr, nullptr};        // [rows]
+    int anti = 0;
+};
+egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D,
+                               const LnExtras* extras = nullptr);
 egg_status launch_embed_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int int_bound, int corr_shift, const int8_t* emb,
                            const uint8_t* tokens, int8_t* Y);
 egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int int_bound, int corr_shift, int T,

@@ -20,9 +20,12 @@ __device__ __forceinline__ int sat127(int v) { return min(127, max(-127, v)); }
 __device__ __forceinline__ int sbyte(uint32_t w, int b) { return (int)(int8_t)(w >> (8 * b)); }
 
 // y[row] = I8(y[row] + add[row]) when add != nullptr (written back), then u[row] = LN(ln, y[row]).
+// By-products (LnExtras): dot products of the normalised row with the row of up to two factor arrays (the
+// u . B of the matmuls that read u; the odd member of an antithetic pair uses -B), and two int32 vectors
+// cleared for epilogues that accumulate into them later.
 __global__ __launch_bounds__(256) void resid_ln_kernel(const int8_t* __restrict__ add, int8_t* __restrict__ y,
                                                        const int8_t* __restrict__ ln, int8_t* __restrict__ u,
-                                                       int64_t rows, int lpr_log2, int d_log2)
+                                                       int64_t rows, int lpr_log2, int d_log2, LnExtras ex)
 {
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t row = gid >> lpr_log2;
@@ -71,6 +74,32 @@ __global__ __launch_bounds__(256) void resid_ln_kernel(const int8_t* __restrict_
         ov[w] = o;
     }
     *(u32x4*)(u + off) = ov;
+    if (ex.dot[0]) {
+        const size_t foff = ((size_t)(ex.anti ? row >> 1 : row) << d_log2) + (size_t)part * 16;
+        const u32x4 b0 = *(const u32x4*)(ex.B[0] + foff);
+        int d0 = 0, d1 = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) d0 = __builtin_amdgcn_sdot4((int)ov[w], (int)b0[w], d0, false);
+        if (ex.dot[1]) {
+            const u32x4 b1 = *(const u32x4*)(ex.B[1] + foff);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) d1 = __builtin_amdgcn_sdot4((int)ov[w], (int)b1[w], d1, false);
+        }
+        // every lane of a live row is live (rows are whole groups of lanes), so the shuffles stay inside the row
+        for (int o = 1; o < (1 << lpr_log2); o <<= 1) {
+            d0 += __shfl_xor(d0, o, 64);
+            d1 += __shfl_xor(d1, o, 64);
+        }
+        if (part == 0) {
+            const bool neg = ex.anti && (row & 1);
+            ex.dot[0][row] = neg ? -d0 : d0;
+            if (ex.dot[1]) ex.dot[1][row] = neg ? -d1 : d1;
+        }
+    }
+    if (part == 0) {
+        if (ex.zero[0]) ex.zero[0][row] = 0;
+        if (ex.zero[1]) ex.zero[1][row] = 0;
+    }
 }
 
 // y[row] = I8(emb[t] + ((A[id][t] * +-B[id]) >> corr_shift)), t = tokens[row]; the odd member of an
@@ -109,13 +138,15 @@ static int ilog2(int v)
     return l;
 }
 
-egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D)
+egg_status launch_layernorm_i8(eggroll_ctx* c, const int8_t* add, int8_t* y, const int8_t* ln, int8_t* u, int64_t rows, int D,
+                               const LnExtras* extras)
 {
     if (rows == 0) return EGG_OK;
     KernelScope ks(c, "resid_layernorm_i8");
     const int lpr = ilog2(D / 16);
     const int64_t threads = rows << lpr;
-    hipLaunchKernelGGL(resid_ln_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, add, y, ln, u, rows, lpr, ilog2(D));
+    hipLaunchKernelGGL(resid_ln_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, add, y, ln, u, rows, lpr, ilog2(D),
+                       extras ? *extras : LnExtras());
     return check_hip(c, hipGetLastError(), "resid_layernorm_i8 launch");
 }
 
@@ -165,9 +196,10 @@ egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s
     const size_t fD = pad((size_t)ids * D), f4D = pad((size_t)ids * 4 * D), f256 = pad((size_t)ids * 256);
     const size_t act = pad((size_t)rows * D), dots = pad((size_t)rows * sizeof(int));
     const size_t per_layer = 8 * fD + 2 * (f4D + fD);
+    const size_t n_dots = 4 + 2 * (size_t)L;   // u.B_Wf, u.B_Wh, f^.B_Uh, one for the MLP and the head; s.B_Uf twice per layer
     const size_t total = 2 * (f256 + fD) + (size_t)L * per_layer   // factors
                          + 7 * act + 4 * act                        // y, u, y', a1, a3, f, f^; MLP hidden
-                         + 4 * dots + (T > 1 ? (size_t)L * act : 0);
+                         + n_dots * dots + (T > 1 ? (size_t)L * act : 0);
     egg_status st;
     if ((st = reserve(c, c->gru, total)) != EGG_OK) return st;
     char* p = (char*)c->gru.p;
@@ -196,9 +228,15 @@ egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s
     int8_t* hid = take(4 * act);
     int* dot[4];
     for (int m = 0; m < 4; ++m) dot[m] = (int*)take(dots);
+    std::vector<int*> dot_s(2 * (size_t)L);   // [layer][parity of the time step that reads it]
+    for (auto& d : dot_s) d = (int*)take(dots);
     int8_t* S_alt = T > 1 ? take((size_t)L * act) : nullptr;
     const size_t DD = (size_t)D * D, state_stride = (size_t)rows * D;
 
+    // Every dot product u . B that a matmul needs is a by-product of whatever wrote u: the normalisation
+    // pass (u . B_Wf, u . B_Wh, u . B_mlp1, u . B_head), the first gate's epilogue (f^ . B_Uh), the last GRU
+    // epilogue (h . B_Uf for the next time step) and the first MLP matmul's epilogue (hidden . B_mlp2).
+    // Only s . B_Uf of the state the caller passes in is computed by a pass of its own, at the first time step.
     for (int t = 0; t < T; ++t) {
         // the last time step writes S_out; the ones before it alternate so that no step reads what it writes
         const int8_t* s_from = t == 0 ? S_in : (((T - t) & 1) ? S_alt : S_out);
@@ -208,20 +246,36 @@ egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s
         if ((st = launch_embed(c, P.emb, tokens + (size_t)t * rows, embA, embB, y, rows, D, anti, corr_shift)) != EGG_OK) return st;
         const int8_t* add = nullptr;
         for (int i = 0; i < L; ++i) {
-            if ((st = launch_layernorm_i8(c, add, y, P.ln1 + (size_t)i * D, u, rows, D)) != EGG_OK) return st;
+            int* ds_now = dot_s[2 * (size_t)i + (t & 1)];
+            int* ds_next = t + 1 < T ? dot_s[2 * (size_t)i + ((t + 1) & 1)] : nullptr;
+            LnExtras e1;
+            e1.anti = anti;
+            e1.B[0] = F[i].B[0]; e1.dot[0] = dot[0];   // u . B_Wf
+            e1.B[1] = F[i].B[2]; e1.dot[1] = dot[2];   // u . B_Wh
+            e1.zero[0] = dot[3]; e1.zero[1] = ds_next;
+            if ((st = launch_layernorm_i8(c, add, y, P.ln1 + (size_t)i * D, u, rows, D, &e1)) != EGG_OK) return st;
             GruStep g;
             for (int m = 0; m < 4; ++m) { g.A[m] = F[i].A[m]; g.B[m] = F[i].B[m]; g.W[m] = P.gru_w + ((size_t)i * 4 + m) * DD; g.dot[m] = dot[m]; }
+            g.dot[1] = ds_now;
             g.bf = P.gru_b + (size_t)i * 2 * D; g.bh = g.bf + D;
             g.a1 = a1; g.a3 = a3; g.f = f; g.fh = fh;
+            g.u_dots_ready = true; g.s_dot_ready = t > 0; g.fh_dot_zeroed = true; g.dot_s_next = ds_next;
             int8_t* h = s_to + (size_t)i * to_stride;
             if ((st = launch_gru_step(c, g, anti, rows, D, int_bound, corr_shift, os_d, u, s_from + (size_t)i * from_stride, h)) != EGG_OK) return st;
-            if ((st = launch_layernorm_i8(c, h, y, P.ln2 + (size_t)i * D, u, rows, D)) != EGG_OK) return st;
-            if ((st = launch_i8_matmul(c, F[i].A1, F[i].B1, anti, rows, 4 * D, D, int_bound, corr_shift, os_d, P.mlp1 + (size_t)i * 4 * DD, u, hid, dot[0], false, nullptr)) != EGG_OK) return st;
-            if ((st = launch_i8_matmul(c, F[i].A2, F[i].B2, anti, rows, D, 4 * D, int_bound, corr_shift, os_4d, P.mlp2 + (size_t)i * 4 * DD, hid, yp, dot[1], false, nullptr)) != EGG_OK) return st;
+            LnExtras e2;
+            e2.anti = anti;
+            e2.B[0] = F[i].B1; e2.dot[0] = dot[0];     // u . B_mlp1
+            e2.zero[0] = dot[1];                        // hidden . B_mlp2, accumulated by the first MLP matmul
+            if ((st = launch_layernorm_i8(c, h, y, P.ln2 + (size_t)i * D, u, rows, D, &e2)) != EGG_OK) return st;
+            if ((st = launch_i8_matmul(c, F[i].A1, F[i].B1, anti, rows, 4 * D, D, int_bound, corr_shift, os_d, P.mlp1 + (size_t)i * 4 * DD, u, hid, dot[0], true, nullptr, F[i].B2, dot[1])) != EGG_OK) return st;
+            if ((st = launch_i8_matmul(c, F[i].A2, F[i].B2, anti, rows, D, 4 * D, int_bound, corr_shift, os_4d, P.mlp2 + (size_t)i * 4 * DD, hid, yp, dot[1], true, nullptr)) != EGG_OK) return st;
             add = yp;
         }
-        if ((st = launch_layernorm_i8(c, add, y, P.ln_out, u, rows, D)) != EGG_OK) return st;
-        if ((st = launch_i8_matmul(c, headA, headB, anti, rows, 256, D, int_bound, corr_shift, os_d, P.head, u, logits + (size_t)t * rows * 256, dot[0], false, nullptr)) != EGG_OK) return st;
+        LnExtras eo;
+        eo.anti = anti;
+        eo.B[0] = headB; eo.dot[0] = dot[0];
+        if ((st = launch_layernorm_i8(c, add, y, P.ln_out, u, rows, D, &eo)) != EGG_OK) return st;
+        if ((st = launch_i8_matmul(c, headA, headB, anti, rows, 256, D, int_bound, corr_shift, os_d, P.head, u, logits + (size_t)t * rows * 256, dot[0], true, nullptr)) != EGG_OK) return st;
     }
     return EGG_OK;
 }

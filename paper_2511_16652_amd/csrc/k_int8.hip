@@ -76,6 +76,23 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int* __restrict__ p, int6
     if (i < n) p[i] = 0;
 }
 
+__global__ __launch_bounds__(256) void zero2_i32_kernel(int* __restrict__ p0, int* __restrict__ p1, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) {
+        p0[i] = 0;
+        if (p1) p1[i] = 0;
+    }
+}
+
+// a fill kernel rather than a memset node, so that callers can sit inside a captured graph
+egg_status launch_zero_i32(eggroll_ctx* c, int* p0, int* p1, int64_t n)
+{
+    KernelScope ks(c, "zero_dots");
+    hipLaunchKernelGGL(zero2_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, p0, p1, n);
+    return check_hip(c, hipGetLastError(), "zero_dots launch");
+}
+
 // Epilogue of the integer step.  The MFMA layout gives a lane 4 consecutive outputs of one row of
 // h' at a time, i.e. 4-byte accesses 1 KB apart; instead the int32 accumulators of a 32-row block
 // are parked in the wave's LDS slice and re-read row-wise, so that a lane finishes 16 consecutive
@@ -87,9 +104,9 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int* __restrict__ p, int6
 // addition is associative, so the result does not depend on the order of the atomics.
 struct I8Args {
     const int8_t* A;  // [rows][d] factors
-    const int8_t* B;  // [rows][d] factors
+    const int8_t* B;  // [rows][d] factors that the NEXT matmul dots this one's output with (read only when dots_next)
     const int* dots;  // [rows]  u . B of this step
-    int* dots_next;   // [rows]  accumulates u' . B for the next step (zeroed by the host), or NULL
+    int* dots_next;   // [rows]  accumulates u' . B for the next matmul (zeroed beforehand), or NULL; with gate 1 u' is f^
     int8_t* H_out;    // [rows][d]
     int d, corr_shift, out_shift;
     int anti;  // antithetic pairs: rows 2p, 2p+1 read the factors of pair p; the odd row uses -B_p
@@ -109,9 +126,9 @@ struct I8Epi {
     typedef int value_t;
     typedef I8Args Args;
     static constexpr int MAX_PF_PASSES = 2;  // wave tiles up to 64 wide prefetch
-    const Args a;
-    char* const stage;
-    const int lane;
+    Args a;
+    char* stage;
+    int lane;
     u32x4 pa[2][MAX_PF_PASSES], pb[2][MAX_PF_PASSES];  // prefetched bytes of A_i and B_i: [row block][pass]
     int pdot[2][MAX_PF_PASSES];
     int cur_j;
@@ -221,7 +238,7 @@ struct I8Epi {
             const uint32_t o = __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
                                __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu);
             out[w] = o;
-            part = __builtin_amdgcn_sdot4((int)o, (int)bv[w], part, false);
+            part = __builtin_amdgcn_sdot4((int)(a.gate == 1 ? out2[w] : o), (int)bv[w], part, false);
         }
         if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
         if (ok && a.gate == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
@@ -276,26 +293,171 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     return check_hip(c, hipGetLastError(), "forward_gemm_i8");
 }
 
+// Row-streaming form of the matmul for d_in = 256 (the integer model's width): K is so short that a tile
+// of the general core is all prologue and epilogue, so here a workgroup is persistent instead.  Its four
+// waves keep the MFMA fragments of a 256-row slice of theta in registers for the whole kernel (64 rows x
+// 256 bytes per wave = 64 VGPRs), and blocks of 64 activation rows stream through a two-deep LDS ring
+// filled by direct-to-LDS loads: while block b is multiplied and finished, block b+1 is in LDS or landing,
+// and the load of block b+2 is issued as soon as the multiply of b has released its buffer.  The
+// factor bytes and dot products of block b+1 are fetched before block b's epilogue runs.  Two workgroups
+// per CU let one multiply while the other does its epilogue arithmetic.  Column slices of a wider theta
+// (the 4D x D matrix of the MLP) that read the same rows sit on the same XCD, next to each other in
+// launch order, so that the second to fourth read of a row block hits that XCD's L2.
+template <class Epi>
+__global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restrict__ W, int d_out, Operand Q, int tiles_m,
+                                                           int nstreams, int nblocks, typename Epi::Args ea)
+{
+    constexpr int BN = 64, NT = 256, WTM = 64, MB = 2, NB = 2, PITCH = 128;
+    constexpr int HALF = BN * PITCH;  // 64 rows x one 128-byte half of K
+    constexpr int BUF = 2 * HALF;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int tm = q % tiles_m;
+    const int stream = xcd * (nstreams >> 3) + q / tiles_m;
+    const int m0 = tm * 256, mw0 = m0 + wave * WTM;
+    char* const slice = lds + 2 * BUF + wave * Epi::lds_per_wave(WTM);
+
+    // theta fragments: lane reads row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5) of each K half
+    u32x4 wf[2][4][MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int row = min(mw0 + i * 32 + (lane & 31), d_out - 1);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) wf[h][ks][i] = *(const u32x4*)(W + (size_t)row * 256 + (h * 8 + 2 * ks + (lane >> 5)) * 16);
+    }
+    const int frow = lane & 31, fsw = (frow >> 1) & 7;
+    int foff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * PITCH + (((2 * ks + (lane >> 5)) ^ fsw) << 4);
+
+    DmaLoader<BN, NT, false> lq;
+    auto issue = [&](int nb, int buf) {
+        const int n0 = nb * BN;
+        lq.init(Q, n0, tid);
+        const char* g = Q.base + (int64_t)n0 * Q.row_stride;
+        lq.load(g, 0, 16, nullptr, lds + buf * BUF, wave);
+        lq.load(g + 128, 8, 16, nullptr, lds + buf * BUF + HALF, wave);
+    };
+
+    int nb = stream;
+    if (nb >= nblocks) return;
+    issue(nb, 0);
+    if (nb + nstreams < nblocks) issue(nb + nstreams, 1);
+    Epi epi(ea, slice, lane);
+    epi.template prefetch<MB, NB>(mw0, nb * BN, lane, Q.rows);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    for (int it = 0; nb < nblocks; nb += nstreams, ++it) {
+        const char* buf = lds + (it & 1) * BUF;   // block nb is in LDS (every wave confirmed its share before the last barrier)
+        i32x16 acc[MB][NB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                u32x4 fb[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) fb[j] = *(const u32x4*)(buf + h * HALF + j * 32 * PITCH + foff[ks]);
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) MmaI8::mma(wf[h][ks][i], fb[j], acc[i][j]);
+            }
+        __syncthreads();  // every wave has read block nb: its buffer is free
+        const int nb2 = nb + 2 * nstreams, nb1 = nb + nstreams;
+        // Loads complete in issue order among themselves, so once at most the four loads just issued are
+        // outstanding, this wave's share of block nb+1 (issued an iteration ago) has landed; the stores of the
+        // previous epilogue had the multiply above to drain and are not waited for behind the epilogue.
+        if (nb2 < nblocks) {
+            issue(nb2, it & 1);
+            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        }
+        Epi next(ea, slice, lane);
+        if (nb1 < nblocks) next.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);
+        const int n0 = nb * BN;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int n = n0 + j * 32 + (lane & 31);
+            const bool nvalid = n < Q.rows;
+            epi.column(n, nvalid);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int ml = i * 32 + qq * 8 + (lane >> 5) * 4;
+                    int v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * qq + e];
+                    epi.store4(mw0 + ml, n, v, nvalid, ml);
+                }
+            epi.template flush<WTM>(mw0, n0 + j * 32, Q.rows);
+        }
+        epi = next;
+        __syncthreads();  // all waves have confirmed their share of block nb+1
+    }
+}
+
+template <class Epi>
+static egg_status launch_i8_stream(eggroll_ctx* c, const int8_t* W, int d_out, const Operand& Q, const typename Epi::Args& ea)
+{
+    const int tiles_m = (d_out + 255) / 256;
+    const int nblocks = (Q.rows + 63) / 64;
+    int nstreams = std::max(8, (512 / tiles_m) & ~7);
+    nstreams = std::min(nstreams, (nblocks + 7) & ~7);
+    const size_t lds = 2 * 2 * 64 * 128 + 4 * Epi::lds_per_wave(64);
+    if (!operand_offsets_fit(Q, 64)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
+    auto kern = stream_i8_kernel<Epi>;
+    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "stream smem attr");
+    if (st != EGG_OK) return st;
+    KernelScope ks(c, "forward_stream_i8");
+    hipLaunchKernelGGL(kern, dim3((unsigned)(nstreams * tiles_m)), dim3(256), lds, c->stream, W, d_out, Q, tiles_m, nstreams, nblocks, ea);
+    return check_hip(c, hipGetLastError(), "forward_stream_i8");
+}
+
+// Kernel choice for one integer matmul: the row-streaming kernel at the integer model's width, otherwise the
+// general core with 256 x 256 tiles when those fill the chip, else 128 x 128 tiles (two workgroups per CU).
+static egg_status dispatch_i8(eggroll_ctx* c, const int8_t* W, int d_out, int d_in, int64_t rows, int int_bound, const Operand& Q,
+                              const I8Args& ea)
+{
+    // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
+    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
+    if (d_in == 256 && rows >= 2048)
+        return dot24 ? launch_i8_stream<I8Epi<true>>(c, W, d_out, Q, ea) : launch_i8_stream<I8Epi<false>>(c, W, d_out, Q, ea);
+    const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
+    Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
+    if (big_tiles >= 192)
+        return dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+    return dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+}
+
 // One perturbed integer matmul on factor buffers that already exist:  dst = I8((src W^T + ((src . B) A >> cs)) >> os).
-// dots: `rows` int32, computed here unless dots_ready.  Used by the GRU cell, whose factors are generated once per call.
+// dots: `rows` int32, computed here unless dots_ready.  With dots_next (zeroed by the caller) the epilogue also accumulates
+// the dot products of the output rows (of f^ under gate 1) with B_next, factors of the matmul that consumes them.  Used by the GRU cell, whose factors are generated once per call.
 egg_status launch_i8_matmul(eggroll_ctx* c, const int8_t* A, const int8_t* B, int anti, int64_t rows, int d_out, int d_in,
                             int int_bound, int corr_shift, int out_shift, const int8_t* W, const int8_t* src, int8_t* dst,
-                            int* dots, bool dots_ready, const I8Gate* gate)
+                            int* dots, bool dots_ready, const I8Gate* gate, const int8_t* B_next, int* dots_next)
 {
     egg_status st;
     if (!dots_ready && (st = launch_dots_i8(c, src, B, nullptr, nullptr, nullptr, rows, d_in, anti, dots, nullptr, nullptr)) != EGG_OK) return st;
-    const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
-    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
-    Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
     Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
-    I8Args ea{A, B, dots, nullptr, dst, d_out, corr_shift, out_shift, anti, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
+    I8Args ea{A, B_next, dots, dots_next, dst, d_out, corr_shift, out_shift, anti, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
     if (gate) {
         ea.gate = gate->mode;
         ea.g_other = gate->other; ea.g_state = gate->state; ea.g_f = gate->f; ea.g_bias = gate->bias; ea.g_out2 = gate->out2;
     }
-    if (big_tiles >= 192)
-        return dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
-    return dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+    return dispatch_i8(c, W, d_out, d_in, rows, int_bound, Q, ea);
 }
 
 egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
@@ -330,23 +492,16 @@ egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKe
     }
     if ((st = launch_dots_i8(c, H_in, B, nullptr, nullptr, nullptr, rows, d_in, anti, (int*)dots_base, nullptr, nullptr)) != EGG_OK) return st;
 
-    const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
-    // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
-    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
     const int8_t* src = H_in;
     for (int t = 0; t < steps; ++t) {
         int8_t* dst = (t == steps - 1) ? H_out : scratch[t & 1];
         const bool alias = (dst == src);  // only possible for steps == 1 with H_out == H_in
         if (alias) dst = scratch[0];
-        Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
         Operand Q{(const char*)src, (int64_t)d_in, 16, (int)rows};
         // the epilogue's row length is d_out (rows of A_i and of h'); with a next step d_out == d_in, so B_i fits too
         I8Args ea{A, B, (const int*)(dots_base + dot_row * t), t + 1 < steps ? (int*)(dots_base + dot_row * (t + 1)) : nullptr,
                        dst, d_out, corr_shift, out_shift, anti, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
-        if (big_tiles >= 192)
-            st = dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
-        else
-            st = dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+        st = dispatch_i8(c, W, d_out, d_in, rows, int_bound, Q, ea);
         if (st != EGG_OK) return st;
         if (alias) {
             if ((st = check_hip(c, hipMemcpyAsync(H_out, dst, obytes, hipMemcpyDeviceToDevice, c->stream), "copy back")) != EGG_OK) return st;

@@ -143,3 +143,30 @@ def test_forward_rejects_bad_arguments(ctx):
         ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N, 1, 128, 128, 1), L, 8, 4, T, P, tok, S, torch.empty_like(S), lg)
     with pytest.raises(eb.EggrollError):       # odd population with pairs
         ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N - 1, 1, D, D, 1, antithetic=1), L, 8, 4, T, P, tok, S, torch.empty_like(S), lg)
+
+
+def test_forward_real_shape_sampled(ctx):
+    """The benchmark's launch configuration (D = 256, 6 layers, 2^18 members in antithetic pairs) over 2 tokens:
+    sampled pairs against the oracle (a member's trajectory depends on no other member), plus the range
+    invariant of I8 over the whole output."""
+    import torch
+    D, L, N, T = 256, 6, 1 << 18, 2
+    P = inputs.egg_model(D, L, 1006)
+    tok = inputs.egg_tokens(T, N, 1007)
+    model = {k: dev(v) for k, v in P.items()}
+    g = torch.Generator(device="cuda").manual_seed(3)
+    S = torch.randint(-40, 41, (L, N, D), generator=g, device="cuda", dtype=torch.int8)
+    S_out = torch.empty_like(S)
+    logits = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+    ctx.eggroll_egg_forward_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(0, N, 1, D, D, 1, antithetic=1), L, 8, 4, T,
+                               model, dev(tok), S, S_out, logits)
+    torch.cuda.synchronize()
+    assert int(logits.min()) >= -127 and int(S_out.min()) >= -127
+    rng = np.random.default_rng(2)
+    for p in np.sort(rng.choice(N // 2, 12, replace=False)):
+        m = 2 * int(p)
+        want, S_want = oracle.egg_forward_i8(SEED, STEP, LAYER, m, 2, D, L, 8, 4, P, tok[:, m:m + 2],
+                                             S[:, m:m + 2].cpu().numpy(), antithetic=True)
+        assert (logits[:, m:m + 2].cpu().numpy() == want).all(), m
+        assert (S_out[:, m:m + 2].cpu().numpy() == S_want).all(), m
+    assert logits.float().std() > 3

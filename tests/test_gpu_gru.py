@@ -49,7 +49,8 @@ def ref(D, N, T, mats, bf, bh, U, S, mb, anti, bound=8, cs=4, os_=7):
 
 
 @pytest.mark.parametrize("D,N,T,mb,anti", [(64, 33, 1, 0, 0), (256, 300, 3, 5, 0), (144, 130, 2, 6, 1), (1024, 70, 2, 0, 0),
-                                            (256, 1026, 4, 2, 1)])
+                                            (256, 1026, 4, 2, 1),
+                                            (256, 2500, 3, 0, 0), (256, 4102, 2, 4, 1)])   # row-streaming matmul kernel
 def test_gru_cell_bit_exact(ctx, D, N, T, mb, anti):
     mats, bf, bh, U, S = make(D, N, T, D + N)
     got = run(ctx, D, N, T, mats, bf, bh, U, S, mb, anti)

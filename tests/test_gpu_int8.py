@@ -37,7 +37,8 @@ def ref(wl, member_begin=0):
 
 @pytest.mark.parametrize("d,N,steps,bound,cs,os_", [
     (64, 33, 1, 8, 4, 8), (144, 300, 3, 8, 4, 6), (256, 130, 5, 8, 0, 8), (1024, 70, 4, 8, 4, 8),
-    (48, 9, 2, 0, 4, 5), (128, 257, 2, 127, 9, 9), (272, 40, 1, 16, 2, 0)])
+    (48, 9, 2, 0, 4, 5), (128, 257, 2, 127, 9, 9), (272, 40, 1, 16, 2, 0),
+    (256, 2310, 3, 8, 4, 6), (256, 2048, 2, 127, 9, 9)])   # the row-streaming kernel, with the next step's dot products
 def test_int8_bit_exact(ctx, d, N, steps, bound, cs, os_):
     wl = inputs.make_int8("t", d, N, steps, 31, bound, cs, os_)
     wl.noise_seed, wl.step, wl.layer = 3, 1, 4
@@ -75,7 +76,9 @@ def test_int8_errors(ctx):
     assert e.value.status == eb.EGG_EUNSUPPORTED
 
 
-@pytest.mark.parametrize("d_out,d_in,N,anti", [(1024, 256, 300, 0), (256, 1024, 130, 0), (48, 272, 70, 1), (2064, 64, 38, 1)])
+@pytest.mark.parametrize("d_out,d_in,N,anti", [(1024, 256, 300, 0), (256, 1024, 130, 0), (48, 272, 70, 1), (2064, 64, 38, 1),
+                                                 # d_in = 256 with at least 2048 rows: the row-streaming kernel (ragged rows, ragged and multi-slice d_out)
+                                                 (256, 256, 2500, 0), (1024, 256, 2118, 1), (272, 256, 2049, 0), (48, 256, 4100, 1)])
 def test_rectangular_single_step_bit_exact(ctx, d_out, d_in, N, anti):
     """One application of a d_out x d_in integer theta (the 4D x D and D x 4D matrices of the integer MLP)."""
     import torch
@@ -90,6 +93,8 @@ def test_rectangular_single_step_bit_exact(ctx, d_out, d_in, N, anti):
     got = out.cpu().numpy()
     assert (got == want).all()
     assert 0.01 < (np.abs(want) == 127).mean() < 0.99 or np.abs(want).max() < 127
+    if d_out == d_in:
+        return
     with pytest.raises(eb.EggrollError):   # a rectangular matrix cannot be iterated
         ctx.eggroll_perturbed_forward_i8(eb.make_key(3, 1, 4), eb.make_shape(6, N, 1, d_out, d_in, 1), 8, 4, 7, 2,
                                          torch.from_numpy(W).cuda(), torch.from_numpy(H).cuda(), out)
