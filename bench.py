@@ -404,6 +404,8 @@ def gru_workload(args):
         step()
     kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in ctx.profile_read().items()}
     ctx.profile_enable(False)
+    if args.calibrate_copy:
+        calibration_copy()
     # per member and input: 4 D^2 MACs; HBM bytes the method needs: u, s in, h out, 8 factor rows = 11 D
     ops = 2.0 * 4 * D * D * N * T
     bytes_alg = 11.0 * D * N * T
@@ -476,6 +478,8 @@ def egg_workload(args):
         step()
     kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms} for k, (n, ms) in ctx.profile_read().items()}
     ctx.profile_enable(False)
+    if args.calibrate_copy:
+        calibration_copy()
     # per member and token: 12 D^2 MACs per layer (4 D^2 GRU, 8 D^2 MLP) + 256 D for the head;
     # HBM bytes the method needs with the factors kept in memory for the episode: the token, the state in
     # and out (2 L D), the logits (256), each factor row once ((18 L + 2) D + 512 per noise id)
