@@ -162,17 +162,18 @@ egg_status eggroll_layernorm_i8(eggroll_ctx* ctx, int64_t rows, int D, const int
 egg_status eggroll_embed_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound, int corr_shift,
                             const int8_t* emb, const uint8_t* tokens, int8_t* Y);
 
-/* Parameters of the integer model, L layers of width D (device pointers, int8). */
+/* Parameters of the integer model, L layers of width D (device pointers, int8).  The forward pass only
+ * reads them; eggroll_egg_update_i8 rewrites emb, gru_w, mlp1, mlp2 and head in place. */
 typedef struct {
-    const int8_t* emb;    /* [256][D] */
-    const int8_t* ln1;    /* [L][D]         weight of the normalisation in front of the GRU */
-    const int8_t* gru_w;  /* [L][4][D][D]   Wf, Uf, Wh, Uh */
-    const int8_t* gru_b;  /* [L][2][D]      bf, bh */
-    const int8_t* ln2;    /* [L][D]         weight of the normalisation in front of the MLP */
-    const int8_t* mlp1;   /* [L][4D][D] */
-    const int8_t* mlp2;   /* [L][D][4D] */
-    const int8_t* ln_out; /* [D] */
-    const int8_t* head;   /* [256][D] */
+    int8_t* emb;    /* [256][D] */
+    int8_t* ln1;    /* [L][D]         weight of the normalisation in front of the GRU */
+    int8_t* gru_w;  /* [L][4][D][D]   Wf, Uf, Wh, Uh */
+    int8_t* gru_b;  /* [L][2][D]      bf, bh */
+    int8_t* ln2;    /* [L][D]         weight of the normalisation in front of the MLP */
+    int8_t* mlp1;   /* [L][4D][D] */
+    int8_t* mlp2;   /* [L][D][4D] */
+    int8_t* ln_out; /* [D] */
+    int8_t* head;   /* [256][D] */
 } egg_model_i8;
 
 /*
@@ -193,6 +194,20 @@ typedef struct {
 egg_status eggroll_egg_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int int_bound,
                                   int corr_shift, int steps, const egg_model_i8* model, const uint8_t* tokens,
                                   const int8_t* S_in, int8_t* S_out, int8_t* logits);
+
+/*
+ * Integer update of every perturbed parameter of the model (App. "Parameter Update"), the counterpart of
+ * eggroll_egg_forward_i8 with the same key: for the embedding table, the four GRU matrices and the two MLP
+ * matrices of each layer, and the head, with that parameter's noise layer,
+ *   E = sum_i F_i A_i B_i^T (int32),   theta <- clamp(theta + sign(E) [|E| >= threshold], -127, 127)
+ * exactly as eggroll_update_i8 does for one matrix (one call of it per parameter, 6 layers + 2 launches of
+ * its kernels).  shape: member ids are noise ids (pair ids when the forward ran antithetic pairs; antithetic
+ * must be 0 here), d_out = d_in = D, rank 1.  fitness: int8 [member_count] in {-1, 0, 1}, one shaped value
+ * per noise id (for pairs sign(s+ - s-), "Fitness Shaping").  Normalisation weights and biases are left as
+ * they are (the paper perturbs and updates matrices and the embedding only).  Bit-exact.
+ */
+egg_status eggroll_egg_update_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int int_bound,
+                                 const int8_t* fitness, int32_t threshold, const egg_model_i8* model);
 
 /*
  * (3) Update direction (EGGROLL UPDATE box; Sec. 4.2 "(diag(f)A)^T B"):

@@ -346,6 +346,46 @@ egg_status eggroll_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* 
     return launch_egg_forward_i8(c, key, *shape, layers, int_bound, corr_shift, steps, *model, tokens, S_in, S_out, logits);
 }
 
+egg_status eggroll_egg_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int layers, int int_bound,
+                                 const int8_t* fitness, int32_t threshold, const egg_model_i8* model)
+{
+    if (!c) return EGG_EINVAL;
+    if (layers < 0 || layers > 4096) return fail(c, EGG_EINVAL, "layers outside [0, 4096]");
+    egg_status s = validate_shape(c, shape, false, false);
+    if (s != EGG_OK) return s;
+    if ((uint64_t)key.layer + 2u + 6u * (uint32_t)layers > 0x80000000ull) return fail(c, EGG_EINVAL, "noise layers must stay below 2^31");
+    if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
+    if (shape->d_out != shape->d_in) return fail(c, EGG_EINVAL, "d_out and d_in must both be the width D");
+    const int D = shape->d_in;
+    if (D % 16) return fail(c, EGG_EUNSUPPORTED, "D must be a multiple of 16");
+    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (threshold < 0) return fail(c, EGG_EINVAL, "threshold must be >= 0");
+    if (!fitness || !model || !model->emb || !model->head) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    if (layers > 0 && (!model->gru_w || !model->mlp1 || !model->mlp2)) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    if (!aligned16(model->emb) || !aligned16(model->head) || !aligned16(model->gru_w) || !aligned16(model->mlp1) || !aligned16(model->mlp2))
+        return fail(c, EGG_EINVAL, "model pointers must be 16-byte aligned");
+    if (shape->member_count * (int64_t)int_bound * int_bound > 0x7FFFFFFFLL)
+        return fail(c, EGG_EUNSUPPORTED, "population too large for int32 accumulation");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    auto one = [&](uint32_t layer, int d_out, int d_in, int8_t* theta) {
+        egg_shape sh = *shape;
+        sh.d_out = d_out;
+        sh.d_in = d_in;
+        return launch_update_i8(c, make_stream_key(key.seed, key.step, layer, 0), make_stream_key(key.seed, key.step, layer, 1), sh,
+                                int_bound, fitness, threshold, theta, nullptr);
+    };
+    if ((s = one(key.layer, 256, D, model->emb)) != EGG_OK) return s;
+    const size_t DD = (size_t)D * D;
+    for (int i = 0; i < layers; ++i) {
+        const uint32_t base = key.layer + 1u + 6u * (uint32_t)i;
+        for (int m = 0; m < 4; ++m)
+            if ((s = one(base + m, D, D, model->gru_w + ((size_t)i * 4 + m) * DD)) != EGG_OK) return s;
+        if ((s = one(base + 4, 4 * D, D, model->mlp1 + (size_t)i * 4 * DD)) != EGG_OK) return s;
+        if ((s = one(base + 5, D, 4 * D, model->mlp2 + (size_t)i * 4 * DD)) != EGG_OK) return s;
+    }
+    return one(key.layer + 1u + 6u * (uint32_t)layers, 256, D, model->head);
+}
+
 egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype noise_dtype,
                           const float* fitness, float scale, int accumulate, float* G, void* W, egg_dtype w_dtype,
                           float lr, const void* A_cache, const void* B_cache)

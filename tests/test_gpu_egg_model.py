@@ -170,3 +170,55 @@ def test_forward_real_shape_sampled(ctx):
         assert (logits[:, m:m + 2].cpu().numpy() == want).all(), m
         assert (S_out[:, m:m + 2].cpu().numpy() == S_want).all(), m
     assert logits.float().std() > 3
+
+
+@pytest.mark.parametrize("D,L,pairs,mb", [(64, 2, 300, 0), (256, 1, 1000, 6), (16, 0, 64, 2)])
+def test_model_update_bit_exact(ctx, D, L, pairs, mb):
+    """Every perturbed parameter against the oracle's integer update with that parameter's noise layer;
+    normalisation weights and biases stay as they are."""
+    rng = np.random.default_rng(D + pairs)
+    P = inputs.egg_model(D, L, 21)
+    F = rng.integers(-1, 2, pairs).astype(np.int8)
+    thr = oracle.int_threshold(0.3, pairs, np.sqrt(8 * 9 / 3.0))
+    model = {k: dev(v) for k, v in P.items()}
+    ctx.eggroll_egg_update_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(mb, pairs, 1, D, D, 1), L, 8, dev(F), thr, model)
+    got = {k: v.cpu().numpy() for k, v in model.items()}
+
+    def want(layer, theta):
+        out, _ = oracle.update_i8(SEED, STEP, layer, mb, pairs, theta.shape[0], theta.shape[1], 8, F, thr, theta)
+        return out
+
+    assert (got["emb"] == want(LAYER, P["emb"])).all()
+    for i in range(L):
+        base = LAYER + 1 + 6 * i
+        for m in range(4):
+            assert (got["gru_w"][i, m] == want(base + m, P["gru_w"][i, m])).all(), (i, m)
+        assert (got["mlp1"][i] == want(base + 4, P["mlp1"][i])).all()
+        assert (got["mlp2"][i] == want(base + 5, P["mlp2"][i])).all()
+    assert (got["head"] == want(LAYER + 1 + 6 * L, P["head"])).all()
+    for k in ("ln1", "ln2", "ln_out", "gru_b"):
+        assert (got[k] == P[k]).all()
+    moved = (got["head"] != P["head"]).mean()
+    assert 0.1 < moved < 0.6          # about the fraction alpha = 0.3 of the entries moves by one bin
+
+
+def test_forward_and_update_use_the_same_noise(ctx):
+    """One member pair decides the update (F = e_p): the table row its first token selects moves toward that
+    member's own perturbation of the row, the one the forward pass added."""
+    D, L, N = 64, 0, 8
+    P = inputs.egg_model(D, L, 5)
+    P["emb"][...] = 0
+    P["head"] = np.zeros_like(P["head"])
+    p = 2
+    tok = np.full((1, N), 65, np.uint8)
+    # forward with corr_shift 0 and a zero table: y = A_p[t] * (+-B_p); recover it through the embedding entry point
+    y = dev(np.zeros((N, D), np.int8))
+    ctx.eggroll_embed_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(0, N, 1, D, D, 1, antithetic=1), 8, 0, dev(P["emb"]), dev(tok[0]), y)
+    y = y.cpu().numpy().astype(np.int64)
+    assert (y[2 * p] == -y[2 * p + 1]).all() and np.abs(y[2 * p]).max() > 0
+    F = np.zeros(N // 2, np.int8)
+    F[p] = 1
+    model = {k: dev(v) for k, v in P.items()}
+    ctx.eggroll_egg_update_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(0, N // 2, 1, D, D, 1), L, 8, dev(F), 1, model)
+    emb = model["emb"].cpu().numpy().astype(np.int64)
+    assert (emb[65] == np.sign(y[2 * p])).all()
