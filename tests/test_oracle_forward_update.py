@@ -180,6 +180,25 @@ def test_vecE_identity_covariance_and_outer_norm():
     assert np.isclose(np.linalg.norm(a @ b.T), np.linalg.norm(a) * np.linalg.norm(b), rtol=1e-13)
 
 
+@pytest.mark.parametrize("r", [1, 2, 4, 8])
+def test_entries_of_E_approach_the_gaussian_at_rate_one_over_r(r):
+    # Sec. "Rank Analysis": the odd cumulants of E^r = A B^T / sqrt(r) vanish by symmetry and the fourth one
+    # decays like 1/r.  Closed form for Gaussian factors: E_ij is a normalised sum of r products of independent
+    # N(0,1) pairs, each with fourth moment 9, so var = 1, skewness 0, excess kurtosis = 6 / r.
+    members, d = 600, 24
+    e = []
+    for m in range(members):
+        A = oracle.noise_matrix(5, 0, 2, 0, m, d, r, oracle.NOISE_F32)
+        B = oracle.noise_matrix(5, 0, 2, 1, m, d, r, oracle.NOISE_F32)
+        e.append((A @ B.T / np.sqrt(r)).ravel())
+    e = np.concatenate(e)
+    n_eff = members * d          # entries of one member share factors: count rows, not entries, for the error bars
+    assert abs(e.mean()) < 4 / np.sqrt(n_eff) and abs(e.var() - 1) < 6 / np.sqrt(n_eff)
+    assert abs((e ** 3).mean()) < 30 / np.sqrt(n_eff)
+    excess = (e ** 4).mean() / e.var() ** 2 - 3
+    assert abs(excess - 6.0 / r) < 0.35 * 6.0 / r + 0.1, (r, excess)
+
+
 def test_monte_carlo_update_recovers_linear_fitness_gradient():
     # For f(W) = <Gamma, W - M>/sigma... i.e. f_i = <Gamma, E_i>, (1/N) sum_i E_i f_i -> Gamma because
     # vec(E) has identity covariance (Eq. matrix_mc with the Gaussian score).  Statistical, loose.
