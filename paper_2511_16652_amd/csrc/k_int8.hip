@@ -121,11 +121,35 @@ struct I8Args {
     int8_t* g_out2;
 };
 
-template <bool DOT24>
+// (t >> sh) written straight into byte E of a packed word (SDWA destination select): the shift and the packing
+// of four int8 results cost one instruction per result.  Byte 0 zero-fills the rest of the word.
+template <int E>
+__device__ __forceinline__ void shift_into_byte(uint32_t& word, int sh, int t)
+{
+    if constexpr (E == 0)
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(word) : "v"(sh), "v"(t));
+    else if constexpr (E == 1)
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
+    else if constexpr (E == 2)
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
+    else
+        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
+}
+
+// MODE < 0: gate mode and next-dot accumulation are read from the arguments at run time (general core).
+// MODE >= 0: both are compile-time constants (gate = MODE & 3, next-dot = MODE >> 2), which strips the other
+// variants' code and their uniform branches from a kernel whose time goes into issuing the epilogue.  These
+// kernels also use the folded form of the arithmetic (the launcher checks that it cannot overflow):
+//     (acc + (p >> cs)) >> os  =  ((acc << cs) + p) >> (cs + os)           nested floors of integers
+//     clamp(t >> sh, -127, 127) = clamp(t, -127 << sh, (128 << sh) - 1) >> sh    the shift is monotonic
+// i.e. multiply, shift-add, clamp, and one shift that lands in its byte of the output word.
+template <bool DOT24, int MODE = -1>
 struct I8Epi {
     typedef int value_t;
     typedef I8Args Args;
     static constexpr int MAX_PF_PASSES = 2;  // wave tiles up to 64 wide prefetch
+    __device__ __forceinline__ int gate() const { return MODE >= 0 ? (MODE & 3) : a.gate; }
+    __device__ __forceinline__ bool has_next() const { return MODE >= 0 ? (MODE >> 2) != 0 : a.dots_next != nullptr; }
     Args a;
     char* stage;
     int lane;
@@ -160,7 +184,7 @@ struct I8Epi {
         const int m = min(mw0 + mc, a.d - 16);
         const int64_t off = (int64_t)(a.anti ? n >> 1 : n) * a.d + m;
         av = *(const u32x4*)(a.A + off);
-        if (a.dots_next) bv = *(const u32x4*)(a.B + off);
+        if (has_next()) bv = *(const u32x4*)(a.B + off);
         else bv = u32x4{0u, 0u, 0u, 0u};
         dv = a.dots[n];
     }
@@ -195,11 +219,11 @@ struct I8Epi {
         const char* src = stage + row * P + mc * 4;
         const int64_t idx = (int64_t)min(n, n_rows - 1) * a.d + min(m, a.d - 16);
         u32x4 gv_o = {0u, 0u, 0u, 0u}, gv_s = gv_o, gv_f = gv_o, gv_b = gv_o, out2 = gv_o;
-        if (a.gate) {  // issued first: their latency hides under the accumulator arithmetic below
+        if (gate()) {  // issued first: their latency hides under the accumulator arithmetic below
             gv_o = *(const u32x4*)(a.g_other + idx);
             gv_s = *(const u32x4*)(a.g_state + idx);
             gv_b = *(const u32x4*)(a.g_bias + min(m, a.d - 16));
-            if (a.gate == 2) gv_f = *(const u32x4*)(a.g_f + idx);
+            if (gate() == 2) gv_f = *(const u32x4*)(a.g_f + idx);
         }
         u32x4 out;
         int part = 0;
@@ -207,21 +231,41 @@ struct I8Epi {
         for (int w = 0; w < 4; ++w) {
             const i32x4 acc4 = *(const i32x4*)(src + w * 16);
             int y[4];
+            uint32_t packed = 0;
+            if constexpr (MODE >= 0) {
+                const int sh = a.corr_shift + a.out_shift;
+                const int lo = -(127 << sh), hi = (128 << sh) - 1;
+                int t[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int ae = (int)(int8_t)(av[w] >> (8 * e));
-                // |u . B| < 2^23 was checked on the host when DOT24: the full-rate 24-bit multiply is exact
-                const int prod = DOT24 ? __mul24(dv, ae) : dv * ae;
-                const int corr = prod >> a.corr_shift;  // arithmetic shift: floor
-                y[e] = min(127, max(-127, (acc4[e] + corr) >> a.out_shift));
+                for (int e = 0; e < 4; ++e) {
+                    const int ae = (int)(int8_t)(av[w] >> (8 * e));
+                    const int prod = DOT24 ? __mul24(dv, ae) : dv * ae;
+                    t[e] = min(hi, max(lo, (int)((uint32_t)acc4[e] << a.corr_shift) + prod));
+                    y[e] = t[e] >> sh;   // dead code when the bytes are written directly below
+                }
+                if (gate() == 0) {
+                    shift_into_byte<0>(packed, sh, t[0]);
+                    shift_into_byte<1>(packed, sh, t[1]);
+                    shift_into_byte<2>(packed, sh, t[2]);
+                    shift_into_byte<3>(packed, sh, t[3]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ae = (int)(int8_t)(av[w] >> (8 * e));
+                    // |u . B| < 2^23 was checked on the host when DOT24: the full-rate 24-bit multiply is exact
+                    const int prod = DOT24 ? __mul24(dv, ae) : dv * ae;
+                    const int corr = prod >> a.corr_shift;  // arithmetic shift: floor
+                    y[e] = min(127, max(-127, (acc4[e] + corr) >> a.out_shift));
+                }
             }
-            if (a.gate) {
+            if (gate()) {
                 int y2[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int sj = (int)(int8_t)(gv_s[w] >> (8 * e));
                     const int sum = min(127, max(-127, (int)(int8_t)(gv_o[w] >> (8 * e)) + y[e] + (int)(int8_t)(gv_b[w] >> (8 * e))));
-                    if (a.gate == 1) {
+                    if (gate() == 1) {
                         y[e] = sum;                                                   // f
                         y2[e] = min(127, max(-127, ((sum + 127) * sj) >> 8));         // f^
                     } else {
@@ -235,14 +279,15 @@ struct I8Epi {
                           __builtin_amdgcn_perm((uint32_t)y2[3], (uint32_t)y2[2], 0x04000c0cu);
             }
             // low bytes of y[0..3] -> one word (byte selectors 0-3: second operand, 4-7: first, 0x0c: zero)
-            const uint32_t o = __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
-                               __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu);
+            const uint32_t o = (MODE >= 0 && gate() == 0) ? packed
+                                                          : (__builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
+                                                             __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu));
             out[w] = o;
-            part = __builtin_amdgcn_sdot4((int)(a.gate == 1 ? out2[w] : o), (int)bv[w], part, false);
+            part = __builtin_amdgcn_sdot4((int)(gate() == 1 ? out2[w] : o), (int)bv[w], part, false);
         }
         if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
-        if (ok && a.gate == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
-        if (a.dots_next) {
+        if (ok && gate() == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
+        if (has_next()) {
             if (!ok) part = 0;
             if (a.anti && (n & 1)) part = -part;  // h' . (-B_p)
 #pragma unroll
@@ -433,8 +478,20 @@ static egg_status dispatch_i8(eggroll_ctx* c, const int8_t* W, int d_out, int d_
 {
     // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
     const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
-    if (d_in == 256 && rows >= 2048)
-        return dot24 ? launch_i8_stream<I8Epi<true>>(c, W, d_out, Q, ea) : launch_i8_stream<I8Epi<false>>(c, W, d_out, Q, ea);
+    // the streaming kernel folds the two shifts into one: needs |acc| 2^cs + |dot A| inside int32 and clamp bounds that fit
+    const int sh = ea.corr_shift + ea.out_shift;
+    const bool fold_ok = sh <= 23 && (((int64_t)d_in * 127 * 127) << ea.corr_shift) + (int64_t)d_in * 127 * int_bound * int_bound < (int64_t(1) << 31);
+    if (d_in == 256 && rows >= 2048 && fold_ok)
+    {
+        const int mode = ea.gate | (ea.dots_next ? 4 : 0);
+        switch (mode) {
+#define EGG_STREAM_CASE(M) \
+            case M: return dot24 ? launch_i8_stream<I8Epi<true, M>>(c, W, d_out, Q, ea) : launch_i8_stream<I8Epi<false, M>>(c, W, d_out, Q, ea);
+            EGG_STREAM_CASE(0) EGG_STREAM_CASE(1) EGG_STREAM_CASE(2) EGG_STREAM_CASE(4) EGG_STREAM_CASE(5) EGG_STREAM_CASE(6)
+#undef EGG_STREAM_CASE
+            default: return fail(c, EGG_EINVAL, "gate mode %d", ea.gate);
+        }
+    }
     const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
     Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
     if (big_tiles >= 192)

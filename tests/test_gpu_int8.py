@@ -38,7 +38,7 @@ def ref(wl, member_begin=0):
 @pytest.mark.parametrize("d,N,steps,bound,cs,os_", [
     (64, 33, 1, 8, 4, 8), (144, 300, 3, 8, 4, 6), (256, 130, 5, 8, 0, 8), (1024, 70, 4, 8, 4, 8),
     (48, 9, 2, 0, 4, 5), (128, 257, 2, 127, 9, 9), (272, 40, 1, 16, 2, 0),
-    (256, 2310, 3, 8, 4, 6), (256, 2048, 2, 127, 9, 9)])   # the row-streaming kernel, with the next step's dot products
+    (256, 2310, 3, 8, 4, 6), (256, 2048, 2, 127, 9, 9), (256, 2100, 2, 16, 6, 10), (256, 2050, 2, 8, 0, 9), (256, 2050, 1, 8, 8, 0)])   # the row-streaming kernel, with the next step's dot products
 def test_int8_bit_exact(ctx, d, N, steps, bound, cs, os_):
     wl = inputs.make_int8("t", d, N, steps, 31, bound, cs, os_)
     wl.noise_seed, wl.step, wl.layer = 3, 1, 4
