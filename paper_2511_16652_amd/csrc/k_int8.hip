@@ -121,6 +121,20 @@ struct I8Args {
     int8_t* g_out2;
 };
 
+// Stores and no-return atomics issued from inline asm, for the row-streaming kernel.  The compiler's waitcnt
+// pass treats vmcnt as in-order only while nothing but loads is pending; one store it knows of turns every
+// later use of a loaded register into s_waitcnt vmcnt(0), which would drain the loads of later blocks at
+// each epilogue.  Operations it does not know of can only make its counted waits stricter (they occupy
+// counter slots), never weaker.  Nothing in the kernel reads these locations back.
+__device__ __forceinline__ void store16_untracked(void* p, const u32x4& v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void atomic_add_untracked(int* p, int v)
+{
+    asm volatile("global_atomic_add %0, %1, off" ::"v"(p), "v"(v) : "memory");
+}
+
 // (t >> sh) written straight into byte E of a packed word (SDWA destination select): the shift and the packing
 // of four int8 results cost one instruction per result.  Byte 0 zero-fills the rest of the word.
 template <int E>
@@ -143,7 +157,10 @@ __device__ __forceinline__ void shift_into_byte(uint32_t& word, int sh, int t)
 //     (acc + (p >> cs)) >> os  =  ((acc << cs) + p) >> (cs + os)           nested floors of integers
 //     clamp(t >> sh, -127, 127) = clamp(t, -127 << sh, (128 << sh) - 1) >> sh    the shift is monotonic
 // i.e. multiply, shift-add, clamp, and one shift that lands in its byte of the output word.
-template <bool DOT24, int MODE = -1>
+// SWZ: the staging rows are exactly one wave-tile row of int32 wide (no padding) and the 16-byte slot of a row is
+// XOR-swizzled with the row number instead: the transposing accesses stay conflict-free and the slice shrinks to
+// 32 * 4 * WTM bytes (what lets the row-streaming kernel keep a three-deep ring at two workgroups per CU).
+template <bool DOT24, int MODE = -1, bool SWZ = false>
 struct I8Epi {
     typedef int value_t;
     typedef I8Args Args;
@@ -158,7 +175,7 @@ struct I8Epi {
     int cur_j;
     int row_pitch;  // pitch(wave tile width), fixed by prefetch() at kernel start
 
-    static constexpr __host__ __device__ int pitch(int wtm) { return wtm * 4 + 16; }
+    static constexpr __host__ __device__ int pitch(int wtm) { return SWZ ? wtm * 4 : wtm * 4 + 16; }
     static constexpr __host__ __device__ int lds_per_wave(int wtm) { return 32 * pitch(wtm); }
     __device__ __forceinline__ I8Epi(const Args& a_, char* slice, int lane_) : a(a_), stage(slice), lane(lane_), cur_j(-1) {}
     template <int NT, int BM, int BN>
@@ -202,9 +219,23 @@ struct I8Epi {
         }
     }
     __device__ __forceinline__ void column(int, bool) { ++cur_j; }
+    // Makes the prefetched registers "used" here, so that the one wait for them sits at this point, where only
+    // loads are in flight and the compiler waits by count; a first use behind the epilogue's stores would wait
+    // for every outstanding memory operation, the loads of later blocks included.
+    __device__ __forceinline__ void touch_prefetched()
+    {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int it = 0; it < MAX_PF_PASSES; ++it) {
+                asm volatile("" ::"v"(pa[j][it]), "v"(pdot[j][it]));
+                if (has_next()) asm volatile("" ::"v"(pb[j][it]));
+            }
+    }
     __device__ __forceinline__ void store4(int, int, const int (&v)[4], bool, int ml)
     {
-        *(i32x4*)(stage + (lane & 31) * row_pitch + ml * 4) = i32x4{v[0], v[1], v[2], v[3]};
+        const int r = lane & 31;
+        *(i32x4*)(stage + r * row_pitch + (SWZ ? (ml * 4) ^ ((r & 15) << 4) : ml * 4)) = i32x4{v[0], v[1], v[2], v[3]};
     }
 
     // one lane's 16 outputs of row nb0 + row: correction, shift, saturate, store, next-dot partial
@@ -229,7 +260,8 @@ struct I8Epi {
         int part = 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const i32x4 acc4 = *(const i32x4*)(src + w * 16);
+            const i32x4 acc4 = SWZ ? *(const i32x4*)(stage + row * P + ((mc * 4 + w * 16) ^ ((row & 15) << 4)))
+                                   : *(const i32x4*)(src + w * 16);
             int y[4];
             uint32_t packed = 0;
             if constexpr (MODE >= 0) {
@@ -285,14 +317,22 @@ struct I8Epi {
             out[w] = o;
             part = __builtin_amdgcn_sdot4((int)(gate() == 1 ? out2[w] : o), (int)bv[w], part, false);
         }
-        if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
-        if (ok && gate() == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
+        if constexpr (MODE >= 0) {
+            if (ok) store16_untracked(a.H_out + (int64_t)n * a.d + m, out);
+            if (ok && gate() == 1) store16_untracked(a.g_out2 + (int64_t)n * a.d + m, out2);
+        } else {
+            if (ok) *(u32x4*)(a.H_out + (int64_t)n * a.d + m) = out;
+            if (ok && gate() == 1) *(u32x4*)(a.g_out2 + (int64_t)n * a.d + m) = out2;
+        }
         if (has_next()) {
             if (!ok) part = 0;
             if (a.anti && (n & 1)) part = -part;  // h' . (-B_p)
 #pragma unroll
             for (int off = 1; off < CPR; off <<= 1) part += __shfl_xor(part, off, 64);
-            if (mc == 0 && n < n_rows) atomicAdd(a.dots_next + n, part);
+            if (mc == 0 && n < n_rows) {
+                if constexpr (MODE >= 0) atomic_add_untracked(a.dots_next + n, part);
+                else atomicAdd(a.dots_next + n, part);
+            }
         }
     }
 
@@ -338,21 +378,39 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     return check_hip(c, hipGetLastError(), "forward_gemm_i8");
 }
 
+// Workgroup barrier without the memory fences of __syncthreads(): those wait for every outstanding global load
+// and store of the wave -- the loads of later blocks and the epilogue's stores, which the row-streaming kernel
+// keeps in flight across its barriers.  What the barrier has to order there is LDS traffic only: the ring is
+// written by direct-to-LDS loads whose arrival the kernel confirms itself (s_waitcnt vmcnt) before the barrier,
+// and read by ds_read instructions whose results the MFMAs have consumed before the barrier that frees a buffer.
+// The empty asm statements keep the compiler from moving memory accesses across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // Row-streaming form of the matmul for d_in = 256 (the integer model's width): K is so short that a tile
 // of the general core is all prologue and epilogue, so here a workgroup is persistent instead.  Its four
 // waves keep the MFMA fragments of a 256-row slice of theta in registers for the whole kernel (64 rows x
-// 256 bytes per wave = 64 VGPRs), and blocks of 64 activation rows stream through a two-deep LDS ring
-// filled by direct-to-LDS loads: while block b is multiplied and finished, block b+1 is in LDS or landing,
-// and the load of block b+2 is issued as soon as the multiply of b has released its buffer.  The
-// factor bytes and dot products of block b+1 are fetched before block b's epilogue runs.  Two workgroups
-// per CU let one multiply while the other does its epilogue arithmetic.  Column slices of a wider theta
-// (the 4D x D matrix of the MLP) that read the same rows sit on the same XCD, next to each other in
-// launch order, so that the second to fourth read of a row block hits that XCD's L2.
+// 256 bytes per wave = 64 VGPRs), and blocks of 64 activation rows stream through a three-deep LDS ring
+// filled by direct-to-LDS loads.  The waves of this kernel spend about half their life in s_waitcnt (measured),
+// so the order of an iteration is built around keeping loads in flight:
+//     multiply block b  ->  barrier (its buffer is free)  ->  epilogue of b  ->  fetch the factor bytes and
+//     dot products of b+1 into the registers the epilogue just finished with  ->  issue the loads of b+3 into
+//     the freed buffer  ->  wait until only that prefetch and those loads are outstanding  ->  barrier.
+// Loads complete in issue order among themselves, so the last wait proves that blocks b+1 and b+2 have landed
+// and that the epilogue's stores are done (after which a use of the prefetched registers waits by count and
+// leaves block b+3's loads in flight through the next multiply and epilogue).  Every load named in that count
+// is issued unconditionally.  Column slices of a wider theta (the 4D x D matrix of the MLP) that read the same
+// rows sit on the same XCD, next to each other in launch order, so that the second to fourth read of a row
+// block hits that XCD's L2.
 template <class Epi>
 __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restrict__ W, int d_out, Operand Q, int tiles_m,
                                                            int nstreams, int nblocks, typename Epi::Args ea)
 {
-    constexpr int BN = 64, NT = 256, WTM = 64, MB = 2, NB = 2, PITCH = 128;
+    constexpr int BN = 64, NT = 256, WTM = 64, MB = 2, NB = 2, PITCH = 128, RING = 3;
     constexpr int HALF = BN * PITCH;  // 64 rows x one 128-byte half of K
     constexpr int BUF = 2 * HALF;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -363,7 +421,7 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
     const int tm = q % tiles_m;
     const int stream = xcd * (nstreams >> 3) + q / tiles_m;
     const int m0 = tm * 256, mw0 = m0 + wave * WTM;
-    char* const slice = lds + 2 * BUF + wave * Epi::lds_per_wave(WTM);
+    char* const slice = lds + RING * BUF + wave * Epi::lds_per_wave(WTM);
 
     // theta fragments: lane reads row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5) of each K half
     u32x4 wf[2][4][MB];
@@ -381,7 +439,7 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
     for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * PITCH + (((2 * ks + (lane >> 5)) ^ fsw) << 4);
 
     DmaLoader<BN, NT, false> lq;
-    auto issue = [&](int nb, int buf) {
+    auto issue = [&](int nb, int buf) {   // four loads per lane, unconditional
         const int n0 = nb * BN;
         lq.init(Q, n0, tid);
         const char* g = Q.base + (int64_t)n0 * Q.row_stride;
@@ -393,12 +451,14 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
     if (nb >= nblocks) return;
     issue(nb, 0);
     if (nb + nstreams < nblocks) issue(nb + nstreams, 1);
+    if (nb + 2 * nstreams < nblocks) issue(nb + 2 * nstreams, 2);
     Epi epi(ea, slice, lane);
     epi.template prefetch<MB, NB>(mw0, nb * BN, lane, Q.rows);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();
-    for (int it = 0; nb < nblocks; nb += nstreams, ++it) {
-        const char* buf = lds + (it & 1) * BUF;   // block nb is in LDS (every wave confirmed its share before the last barrier)
+    lds_barrier();
+    int cur = 0;
+    for (; nb < nblocks; nb += nstreams) {
+        const char* buf = lds + cur * BUF;   // block nb is in LDS: every wave confirmed its share before the last barrier
         i32x16 acc[MB][NB];
 #pragma unroll
         for (int i = 0; i < MB; ++i)
@@ -418,19 +478,8 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
 #pragma unroll
                     for (int j = 0; j < NB; ++j) MmaI8::mma(wf[h][ks][i], fb[j], acc[i][j]);
             }
-        __syncthreads();  // every wave has read block nb: its buffer is free
-        const int nb2 = nb + 2 * nstreams, nb1 = nb + nstreams;
-        // Loads complete in issue order among themselves, so once at most the four loads just issued are
-        // outstanding, this wave's share of block nb+1 (issued an iteration ago) has landed; the stores of the
-        // previous epilogue had the multiply above to drain and are not waited for behind the epilogue.
-        if (nb2 < nblocks) {
-            issue(nb2, it & 1);
-            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
-        } else {
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        }
-        Epi next(ea, slice, lane);
-        if (nb1 < nblocks) next.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);
+        lds_barrier();  // every wave has read block nb: its buffer is free
+        epi.touch_prefetched();
         const int n0 = nb * BN;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
@@ -449,8 +498,19 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
                 }
             epi.template flush<WTM>(mw0, n0 + j * 32, Q.rows);
         }
-        epi = next;
-        __syncthreads();  // all waves have confirmed their share of block nb+1
+        const int nb1 = nb + nstreams, nb3 = nb + 3 * nstreams;
+        epi = Epi(ea, slice, lane);   // its registers are dead: the next block's factor bytes load straight into them
+        if (nb3 < nblocks) {
+            epi.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);   // 2 or 3 loads for each of its 4 passes
+            issue(nb3, cur);
+            if (epi.has_next()) __builtin_amdgcn_s_waitcnt(0x0F74 | (1 << 14));  // vmcnt(20) = 4 + 12 + 4
+            else __builtin_amdgcn_s_waitcnt(0x0F70 | (1 << 14));                 // vmcnt(16) = 4 + 8 + 4
+        } else {
+            if (nb1 < nblocks) epi.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // the last blocks: everything
+        }
+        cur = cur == RING - 1 ? 0 : cur + 1;
+        lds_barrier();  // all waves have confirmed their share of block nb+1
     }
 }
 
@@ -461,7 +521,7 @@ static egg_status launch_i8_stream(eggroll_ctx* c, const int8_t* W, int d_out, c
     const int nblocks = (Q.rows + 63) / 64;
     int nstreams = std::max(8, (512 / tiles_m) & ~7);
     nstreams = std::min(nstreams, (nblocks + 7) & ~7);
-    const size_t lds = 2 * 2 * 64 * 128 + 4 * Epi::lds_per_wave(64);
+    const size_t lds = 3 * 2 * 64 * 128 + 4 * Epi::lds_per_wave(64);   // ring of three blocks + the waves' staging slices
     if (!operand_offsets_fit(Q, 64)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     auto kern = stream_i8_kernel<Epi>;
     egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "stream smem attr");
@@ -486,7 +546,7 @@ static egg_status dispatch_i8(eggroll_ctx* c, const int8_t* W, int d_out, int d_
         const int mode = ea.gate | (ea.dots_next ? 4 : 0);
         switch (mode) {
 #define EGG_STREAM_CASE(M) \
-            case M: return dot24 ? launch_i8_stream<I8Epi<true, M>>(c, W, d_out, Q, ea) : launch_i8_stream<I8Epi<false, M>>(c, W, d_out, Q, ea);
+            case M: return dot24 ? launch_i8_stream<I8Epi<true, M, true>>(c, W, d_out, Q, ea) : launch_i8_stream<I8Epi<false, M, true>>(c, W, d_out, Q, ea);
             EGG_STREAM_CASE(0) EGG_STREAM_CASE(1) EGG_STREAM_CASE(2) EGG_STREAM_CASE(4) EGG_STREAM_CASE(5) EGG_STREAM_CASE(6)
 #undef EGG_STREAM_CASE
             default: return fail(c, EGG_EINVAL, "gate mode %d", ea.gate);
