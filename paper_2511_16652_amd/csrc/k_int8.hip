@@ -554,9 +554,17 @@ static egg_status dispatch_i8(eggroll_ctx* c, const int8_t* W, int d_out, int d_
     }
     const int64_t big_tiles = ((d_out + 255) / 256) * ((rows + 255) / 256);
     Operand P{(const char*)W, (int64_t)d_in, 16, d_out};
-    if (big_tiles >= 192)
-        return dot24 ? launch_i8_gemm<256, 256, 2, 4, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<256, 256, 2, 4, I8Epi<false>>(c, P, Q, d_in / 16, ea);
-    return dot24 ? launch_i8_gemm<128, 128, 2, 2, I8Epi<true>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<128, 128, 2, 2, I8Epi<false>>(c, P, Q, d_in / 16, ea);
+    // ungated matmuls (the recurrence of the single-matrix cell, the MLP's second matrix) get the epilogue with
+    // compile-time mode when the folded arithmetic is safe; gated ones at other widths keep the run-time form
+    const int mode = (ea.gate == 0 && fold_ok) ? (ea.dots_next ? 4 : 0) : -1;
+#define EGG_GEMM_CASE(BM, BN, WM, WN, M) \
+    if (mode == M) return dot24 ? launch_i8_gemm<BM, BN, WM, WN, I8Epi<true, M>>(c, P, Q, d_in / 16, ea) : launch_i8_gemm<BM, BN, WM, WN, I8Epi<false, M>>(c, P, Q, d_in / 16, ea);
+    if (big_tiles >= 192) {
+        EGG_GEMM_CASE(256, 256, 2, 4, 0) EGG_GEMM_CASE(256, 256, 2, 4, 4) EGG_GEMM_CASE(256, 256, 2, 4, -1)
+    }
+    EGG_GEMM_CASE(128, 128, 2, 2, 0) EGG_GEMM_CASE(128, 128, 2, 2, 4) EGG_GEMM_CASE(128, 128, 2, 2, -1)
+#undef EGG_GEMM_CASE
+    return fail(c, EGG_EINVAL, "no kernel for this mode");
 }
 
 // One perturbed integer matmul on factor buffers that already exist:  dst = I8((src W^T + ((src . B) A >> cs)) >> os).
