@@ -111,6 +111,20 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* ctx, egg_key key, const egg_sh
                                      const void* W, const void* X, void* Y, void* A_cache, void* B_cache);
 
 /*
+ * Layout of the factor caches that eggroll_perturbed_forward writes and eggroll_update reads on this context
+ * (default EGG_CACHE_ROWS: exactly what eggroll_noise_gen writes, [member][d][rank]).
+ * EGG_CACHE_PANEL keeps only B, already in the form the update's contraction consumes (Sec. 4.2,
+ * "(diag(f)A)^T B"): B_cache is [ceil(member_count / 8)][d_in][8] fp16 (16 bytes = one input column of 8
+ * consecutive members, zero beyond the last member; bf16 factors are exact in fp16), A_cache must be NULL.
+ * The forward pass then costs one more write of the panel, and the update neither regenerates nor repacks B;
+ * A is regenerated from the key (its panel carries the fitness, which the forward pass cannot know).
+ * Supported for bf16, rank 1, one row per member, not antithetic; other shapes return EGG_EUNSUPPORTED when
+ * a B_cache is passed.  Results of both calls are bit-identical to those of the default layout.
+ */
+typedef enum { EGG_CACHE_ROWS = 0, EGG_CACHE_PANEL = 1 } egg_cache_layout;
+egg_status eggroll_set_cache_layout(eggroll_ctx* ctx, egg_cache_layout layout);
+
+/*
  * (2') Integer form (App. "Matrix Multiplication", "Adding EGGROLL Perturbations"), rank 1, one row per
  * member, W[d_out][d_in] int8 (both multiples of 16), applied `steps` times (steps > 1 feeds h' back in
  * and needs d_out == d_in; one step with a rectangular W is the integer MLP's matmul):

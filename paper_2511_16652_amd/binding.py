@@ -18,7 +18,7 @@ EGG_NORMAL, EGG_UNIFORM_INT, EGG_RAW = 0, 1, 2
 EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
-           "eggroll_default_scale", "eggroll_noise_gen", "eggroll_perturbed_forward",
+           "eggroll_default_scale", "eggroll_set_cache_layout", "eggroll_noise_gen", "eggroll_perturbed_forward",
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
@@ -27,6 +27,8 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
 class EggKey(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("step", ctypes.c_uint32), ("layer", ctypes.c_uint32)]
 
+
+EGG_CACHE_ROWS, EGG_CACHE_PANEL = 0, 1
 
 EGG_MODEL_FIELDS = ("emb", "ln1", "gru_w", "gru_b", "ln2", "mlp1", "mlp2", "ln_out", "head")
 
@@ -72,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_last_error.restype = ctypes.c_char_p
     lib.eggroll_default_scale.argtypes = [i64, ctypes.c_double, i32]
     lib.eggroll_default_scale.restype = ctypes.c_double
+    lib.eggroll_set_cache_layout.argtypes = [vp, i32]
+    lib.eggroll_set_cache_layout.restype = i32
     lib.eggroll_noise_gen.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, vp, vp]
     lib.eggroll_noise_gen.restype = i32
     lib.eggroll_perturbed_forward.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp]
@@ -195,6 +199,9 @@ class Context:
         m = EggModelI8(*[_ptr(model[name]) for name in EGG_MODEL_FIELDS])
         self._check(self._lib.eggroll_egg_update_i8(
             self._h, key, ctypes.byref(shape), int(layers), int_bound, _ptr(fitness), int(threshold), ctypes.byref(m)))
+
+    def eggroll_set_cache_layout(self, layout):
+        self._check(self._lib.eggroll_set_cache_layout(self._h, int(layout)))
 
     def eggroll_update(self, key, shape, noise_dtype, fitness, scale, accumulate, G, W=None, lr=0.0,
                        A_cache=None, B_cache=None):

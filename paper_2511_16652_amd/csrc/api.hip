@@ -157,6 +157,14 @@ double eggroll_default_scale(int64_t population, double sigma, int rank)
     return 1.0 / ((double)population * sigma * sqrt((double)rank));
 }
 
+egg_status eggroll_set_cache_layout(eggroll_ctx* c, egg_cache_layout layout)
+{
+    if (!c) return EGG_EINVAL;
+    if (layout != EGG_CACHE_ROWS && layout != EGG_CACHE_PANEL) return fail(c, EGG_EINVAL, "unknown cache layout %d", (int)layout);
+    c->cache_layout = (int)layout;
+    return EGG_OK;
+}
+
 egg_status eggroll_noise_gen(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype dtype, egg_dist dist,
                              int int_bound, void* A_out, void* B_out)
 {
@@ -204,6 +212,8 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* c, egg_key key, const egg_shap
     if (!(sigma == sigma) || sigma < 0.0f) return fail(c, EGG_EINVAL, "sigma must be >= 0");
     if (sigma == 0.0f && (A_cache || B_cache))
         return fail(c, EGG_EINVAL, "sigma == 0 generates no factors: caches must be NULL");
+    const bool panel = c->cache_layout == EGG_CACHE_PANEL;
+    if (panel && A_cache) return fail(c, EGG_EINVAL, "the panel cache layout keeps B only: A_cache must be NULL");
     const int64_t R = shape->member_count * (int64_t)shape->rows_per_member;
     if (R > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "more than 2^31 rows in one call");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
@@ -213,7 +223,7 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* c, egg_key key, const egg_shap
         s = reserve(c, c->t_buf, (size_t)R * shape->rank * sizeof(float));
         if (s != EGG_OK) return s;
         t = (float*)c->t_buf.p;
-        s = launch_project(c, make_stream_key(key.seed, key.step, key.layer, 1), *shape, io_dtype, X, t, B_cache);
+        s = launch_project(c, make_stream_key(key.seed, key.step, key.layer, 1), *shape, io_dtype, X, t, B_cache, panel);
         if (s != EGG_OK) return s;
     }
     return launch_forward_gemm(c, make_stream_key(key.seed, key.step, key.layer, 0), *shape, io_dtype, y_dtype, sigma,
@@ -400,11 +410,18 @@ egg_status eggroll_update(eggroll_ctx* c, egg_key key, const egg_shape* shape, e
     if (noise_dtype != EGG_BF16 && noise_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "noise_dtype %d", (int)noise_dtype);
     if (W && w_dtype != EGG_BF16 && w_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "w_dtype %d", (int)w_dtype);
     if (shape->d_out % 4) return fail(c, EGG_EUNSUPPORTED, "d_out must be a multiple of 4");
-    if ((A_cache == nullptr) != (B_cache == nullptr)) return fail(c, EGG_EINVAL, "pass both caches or neither");
+    const bool b_panel = c->cache_layout == EGG_CACHE_PANEL && B_cache != nullptr;
+    if (b_panel) {
+        if (A_cache) return fail(c, EGG_EINVAL, "the panel cache layout keeps B only: A_cache must be NULL");
+        if (noise_dtype != EGG_BF16 || shape->rank != 1 || shape->d_out % 2 || shape->d_in % 2)
+            return fail(c, EGG_EUNSUPPORTED, "the panel cache layout needs bf16 factors, rank 1 and even dimensions");
+    } else if ((A_cache == nullptr) != (B_cache == nullptr)) {
+        return fail(c, EGG_EINVAL, "pass both caches or neither");
+    }
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     return launch_update(c, make_stream_key(key.seed, key.step, key.layer, 0),
                          make_stream_key(key.seed, key.step, key.layer, 1), *shape, noise_dtype, fitness, scale,
-                         accumulate, G, W, w_dtype, lr, A_cache, B_cache);
+                         accumulate, G, W, w_dtype, lr, A_cache, B_cache, b_panel);
 }
 
 egg_status eggroll_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound, const int8_t* fitness,

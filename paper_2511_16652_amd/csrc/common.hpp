@@ -17,6 +17,7 @@ struct eggroll_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     std::string err;
+    int cache_layout = 0;  // egg_cache_layout of the forward/update caches
 
     // scratch, grown on demand and kept for the life of the context
     struct Buf {
@@ -66,13 +67,13 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bo
 egg_status launch_noise(eggroll_ctx* c, const StreamKey& k, uint32_t member_begin, int64_t members, int64_t n,
                         egg_dtype dtype, egg_dist dist, int int_bound, void* out);
 egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
-                          float* t, void* B_cache);
+                          float* t, void* B_cache, bool panel);
 egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
                                float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
                                void* A_cache);
 egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                          egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
-                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache);
+                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache, bool b_panel);
 egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out);

@@ -8,6 +8,8 @@
 
 namespace egg {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <bool BF16, int RANK>
 __global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int anti_rows, int d_in,
                                                       const void* __restrict__ X, float* __restrict__ t,
@@ -134,10 +136,81 @@ __global__ __launch_bounds__(256) void project_row_kernel(StreamKey kb, uint32_t
     if (tid == 0) t[ml] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// The same projection for 8 consecutive members per workgroup, with B leaving the kernel as the K-packed fp16
+// panel the update contracts ([member / 8][k][member % 8]): a thread generates the column pair (2b, 2b+1) of the
+// 8 members and stores two 16-byte chunks that are neighbours in the panel, 2 KB contiguous per wave.  Every
+// member's partial sums are formed in the order of project_row_kernel, so t is bit-identical to that kernel's.
+__global__ __launch_bounds__(256) void project_row8_kernel(StreamKey kb, uint32_t member_begin, int64_t members, int d_in,
+                                                           const void* __restrict__ X, float* __restrict__ t,
+                                                           u32x4* __restrict__ panel)
+{
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    __shared__ float red[4][8];
+    const int tid = threadIdx.x;
+    const int64_t g = blockIdx.x;
+    const int pairs = d_in >> 1;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int b = tid; b < pairs; b += 256) {
+        float lo[8], hi[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t i = g * 8 + e;
+            lo[e] = hi[e] = 0.f;
+            if (i < members) {
+                uint32_t w0, w1;
+                noise_words(kb, member_begin + (uint32_t)i, (uint32_t)b, w0, w1);
+                float z0, z1;
+                normal_pair<false>(w0, w1, z0, z1);
+                const uint32_t pk = pack_bf16x2(z0, z1);
+                const uint32_t xv = ((const uint32_t*)X)[i * pairs + b];
+                acc[e] = fmaf(bf16_lo(xv), bf16_lo(pk), acc[e]);
+                acc[e] = fmaf(bf16_hi(xv), bf16_hi(pk), acc[e]);
+                lo[e] = bf16_lo(pk);
+                hi[e] = bf16_hi(pk);
+            }
+        }
+        u32x4 c0, c1;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            h2 p, q;
+            p[0] = (_Float16)lo[2 * w]; p[1] = (_Float16)lo[2 * w + 1];
+            q[0] = (_Float16)hi[2 * w]; q[1] = (_Float16)hi[2 * w + 1];
+            c0[w] = __builtin_bit_cast(uint32_t, p);
+            c1[w] = __builtin_bit_cast(uint32_t, q);
+        }
+        u32x4* o = panel + g * d_in + 2 * b;
+        o[0] = c0;
+        o[1] = c1;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) acc[e] += __shfl_xor(acc[e], off, 64);
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[tid >> 6][e] = acc[e];
+    }
+    __syncthreads();
+    if (tid < 8 && g * 8 + tid < members) t[g * 8 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+}
+
 template <bool BF16>
 static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const egg_shape& shape, const void* X, float* t,
-                                   void* B_cache)
+                                   void* B_cache, bool panel)
 {
+    if (panel && B_cache) {
+        if (!BF16 || shape.rank != 1 || shape.rows_per_member != 1 || shape.antithetic)
+            return fail(c, EGG_EUNSUPPORTED, "the panel cache layout needs bf16, rank 1, one row per member, no antithetic pairs");
+        const int64_t groups = (shape.member_count + 7) / 8;
+        if (groups > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many members in one call");
+        KernelScope ks(c, "project");
+        hipLaunchKernelGGL(project_row8_kernel, dim3((unsigned)groups), dim3(256), 0, c->stream, kb, (uint32_t)shape.member_begin,
+                           shape.member_count, shape.d_in, X, t, (u32x4*)B_cache);
+        return check_hip(c, hipGetLastError(), "project launch");
+    }
     egg_shape s = shape;  // the noise view: pairs as members of 2S rows when antithetic
     const int anti_rows = shape.antithetic ? shape.rows_per_member : 0;
     if (shape.antithetic) {
@@ -176,10 +249,10 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
 }
 
 egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
-                          float* t, void* B_cache)
+                          float* t, void* B_cache, bool panel)
 {
-    return io == EGG_BF16 ? launch_project_t<true>(c, kb, s, X, t, B_cache)
-                          : launch_project_t<false>(c, kb, s, X, t, B_cache);
+    return io == EGG_BF16 ? launch_project_t<true>(c, kb, s, X, t, B_cache, panel)
+                          : launch_project_t<false>(c, kb, s, X, t, B_cache, panel);
 }
 
 }  // namespace egg

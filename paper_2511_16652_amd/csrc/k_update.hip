@@ -253,7 +253,7 @@ static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operan
 
 egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                          egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
-                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache)
+                         egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache, bool b_panel)
 {
     const bool bf = noise_dtype == EGG_BF16;
     const int esz = bf ? 2 : 4, epc = bf ? 8 : 4;
@@ -284,7 +284,8 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
         hipLaunchKernelGGL(fitness_norm_kernel, dim3(1), dim3(1024), 0, c->stream, fitness, s.member_count, fnorm);
     }
     if ((st = reserve(c, c->pack_a, (size_t)kgroups * s.d_out * 16)) != EGG_OK) return st;
-    if ((st = reserve(c, c->pack_b, (size_t)kgroups * s.d_in * 16)) != EGG_OK) return st;
+    // b_panel: the caller's B_cache already is the packed panel (written by the forward pass); only A is generated
+    if (!b_panel && (st = reserve(c, c->pack_b, (size_t)kgroups * s.d_in * 16)) != EGG_OK) return st;
     {
         const int64_t ta = kgroups * s.d_out, tb = kgroups * s.d_in;
         if ((ta + 255) / 256 > 0x7FFFFFFF || (tb + 255) / 256 > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "pack grid too large");
@@ -309,7 +310,7 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
         };
         if (gen_packed) {
             gen_pack(ka, fitness, s.d_out, c->pack_a.p);
-            gen_pack(kb, nullptr, s.d_in, c->pack_b.p);
+            if (!b_panel) gen_pack(kb, nullptr, s.d_in, c->pack_b.p);
         } else {
             pack(A_src, fitness, s.d_out, c->pack_a.p);
             pack(B_src, nullptr, s.d_in, c->pack_b.p);
@@ -318,7 +319,7 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
     }
 
     Operand P{(const char*)c->pack_a.p, 16, (int64_t)s.d_out * 16, s.d_out};
-    Operand Q{(const char*)c->pack_b.p, 16, (int64_t)s.d_in * 16, s.d_in};
+    Operand Q{(const char*)(b_panel ? B_cache : c->pack_b.p), 16, (int64_t)s.d_in * 16, s.d_in};
     UpdEpi::Args ea{G, W, fnorm, s.d_out, s.d_in, scale, lr, accumulate, w_dtype == EGG_BF16 ? 1 : 0};
     if (bf) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * (int64_t)((s.d_in + 255) / 256);

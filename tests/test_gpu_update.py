@@ -133,3 +133,44 @@ def test_accumulate_and_weight_update(ctx):
             assert np.abs(got - want).max() <= np.abs(want).max() * 2.0**-8
         else:
             np.testing.assert_allclose(got, want, rtol=1e-6, atol=1e-6)
+
+
+@pytest.mark.parametrize("d_out,d_in,N,mb", [(256, 256, 64, 0), (388, 264, 301, 5), (4096, 512, 1000, 8)])
+def test_panel_cache_layout_is_bit_identical(d_out, d_in, N, mb):
+    """EGG_CACHE_PANEL: the forward pass keeps B as the packed panel the update contracts.  The outputs of the
+    forward pass and of the update must equal, bit for bit, those of the default flow (no caches, everything
+    regenerated), which the other tests hold against the oracle; the panel itself is checked against the
+    oracle's bf16 factors (exact in fp16), zero beyond the last member."""
+    import torch
+    rng = np.random.default_rng(d_out + N)
+    W = to_device(inputs.round_to_bf16((rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)), "bf16")
+    X = to_device(inputs.round_to_bf16(rng.standard_normal((N, d_in)).astype(np.float32)), "bf16")
+    f = torch.from_numpy(inputs.centered(rng.standard_normal(N)).astype(np.float32)).cuda()
+    key, shape = eb.make_key(9, 2, 3), eb.make_shape(mb, N, 1, d_out, d_in, 1)
+    sigma, scale = 0.05, eb.eggroll_default_scale(N, 0.05, 1)
+    outs = []
+    for layout in (eb.EGG_CACHE_ROWS, eb.EGG_CACHE_PANEL):
+        c = eb.Context(0)
+        c.eggroll_set_cache_layout(layout)
+        Y = torch.empty((N, d_out), dtype=torch.bfloat16, device="cuda")
+        G = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+        panel = None
+        if layout == eb.EGG_CACHE_PANEL:
+            panel = torch.full(((N + 7) // 8, d_in, 8), -1.0, dtype=torch.float16, device="cuda")
+            with pytest.raises(eb.EggrollError):      # the panel layout keeps B only
+                c.eggroll_perturbed_forward(key, shape, sigma, eb.EGG_ACT_NONE, W, X, Y, torch.empty((N, d_out, 1), dtype=torch.bfloat16, device="cuda"), panel)
+        c.eggroll_perturbed_forward(key, shape, sigma, eb.EGG_ACT_NONE, W, X, Y, None, panel)
+        c.eggroll_update(key, shape, eb.EGG_BF16, f, scale, 0, G, None, 0.0, None, panel)
+        torch.cuda.synchronize()
+        outs.append((Y.view(torch.int16).cpu().numpy(), G.cpu().numpy(), None if panel is None else panel.float().cpu().numpy()))
+        c.close()
+    assert (outs[0][0] == outs[1][0]).all()
+    assert (outs[0][1] == outs[1][1]).all() and np.abs(outs[0][1]).max() > 0
+    panel = outs[1][2]
+    for i in sorted(set([0, 1, 7, 8, N - 1]) | set(rng.choice(N, 8, replace=False).tolist())):
+        want = oracle.noise_matrix(9, 2, 3, 1, mb + i, d_in, 1, oracle.NOISE_BF16)[:, 0]
+        got = panel[i // 8, :, i % 8]
+        # the kernel's fp32 Box-Muller may land on the neighbouring bf16 value for a few entries (see helpers)
+        assert (got == want).mean() > 0.995 and np.abs(got - want).max() <= 2.0 ** -6 * (1 + np.abs(want).max())
+    if N % 8:
+        assert (panel[-1, :, N % 8:] == 0).all()
