@@ -128,26 +128,13 @@ struct I8Args {
 // counter slots), never weaker.  Nothing in the kernel reads these locations back.
 __device__ __forceinline__ void store16_untracked(void* p, const u32x4& v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(p), "v"(v) : "memory");
+    // the two wait states cover the hazard between a store of more than 64 bits and a VALU write of its data
+    // registers, which the compiler's hazard recognizer handles for its own stores but cannot see inside asm
+    asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void atomic_add_untracked(int* p, int v)
 {
     asm volatile("global_atomic_add %0, %1, off" ::"v"(p), "v"(v) : "memory");
-}
-
-// (t >> sh) written straight into byte E of a packed word (SDWA destination select): the shift and the packing
-// of four int8 results cost one instruction per result.  Byte 0 zero-fills the rest of the word.
-template <int E>
-__device__ __forceinline__ void shift_into_byte(uint32_t& word, int sh, int t)
-{
-    if constexpr (E == 0)
-        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(word) : "v"(sh), "v"(t));
-    else if constexpr (E == 1)
-        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
-    else if constexpr (E == 2)
-        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
-    else
-        asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(word) : "v"(sh), "v"(t));
 }
 
 // MODE < 0: gate mode and next-dot accumulation are read from the arguments at run time (general core).
@@ -156,7 +143,10 @@ __device__ __forceinline__ void shift_into_byte(uint32_t& word, int sh, int t)
 // kernels also use the folded form of the arithmetic (the launcher checks that it cannot overflow):
 //     (acc + (p >> cs)) >> os  =  ((acc << cs) + p) >> (cs + os)           nested floors of integers
 //     clamp(t >> sh, -127, 127) = clamp(t, -127 << sh, (128 << sh) - 1) >> sh    the shift is monotonic
-// i.e. multiply, shift-add, clamp, and one shift that lands in its byte of the output word.
+// i.e. multiply, shift-add, clamp, shift.  (Shifting each result straight into its byte of the output word
+// with a hand-written SDWA destination select was tried and removed: the hazard recognizer does not look
+// inside inline asm, and gfx950 needs a wait state between a partial-register write and the next read of
+// that register, so back-to-back byte writes into one word occasionally read a stale word.)
 // SWZ: the staging rows are exactly one wave-tile row of int32 wide (no padding) and the 16-byte slot of a row is
 // XOR-swizzled with the row number instead: the transposing accesses stay conflict-free and the slice shrinks to
 // 32 * 4 * WTM bytes (what lets the row-streaming kernel keep a three-deep ring at two workgroups per CU).
@@ -263,7 +253,6 @@ struct I8Epi {
             const i32x4 acc4 = SWZ ? *(const i32x4*)(stage + row * P + ((mc * 4 + w * 16) ^ ((row & 15) << 4)))
                                    : *(const i32x4*)(src + w * 16);
             int y[4];
-            uint32_t packed = 0;
             if constexpr (MODE >= 0) {
                 const int sh = a.corr_shift + a.out_shift;
                 const int lo = -(127 << sh), hi = (128 << sh) - 1;
@@ -273,13 +262,7 @@ struct I8Epi {
                     const int ae = (int)(int8_t)(av[w] >> (8 * e));
                     const int prod = DOT24 ? __mul24(dv, ae) : dv * ae;
                     t[e] = min(hi, max(lo, (int)((uint32_t)acc4[e] << a.corr_shift) + prod));
-                    y[e] = t[e] >> sh;   // dead code when the bytes are written directly below
-                }
-                if (gate() == 0) {
-                    shift_into_byte<0>(packed, sh, t[0]);
-                    shift_into_byte<1>(packed, sh, t[1]);
-                    shift_into_byte<2>(packed, sh, t[2]);
-                    shift_into_byte<3>(packed, sh, t[3]);
+                    y[e] = t[e] >> sh;
                 }
             } else {
 #pragma unroll
@@ -311,9 +294,8 @@ struct I8Epi {
                           __builtin_amdgcn_perm((uint32_t)y2[3], (uint32_t)y2[2], 0x04000c0cu);
             }
             // low bytes of y[0..3] -> one word (byte selectors 0-3: second operand, 4-7: first, 0x0c: zero)
-            const uint32_t o = (MODE >= 0 && gate() == 0) ? packed
-                                                          : (__builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
-                                                             __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu));
+            const uint32_t o = __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x0c0c0400u) |
+                               __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x04000c0cu);
             out[w] = o;
             part = __builtin_amdgcn_sdot4((int)(gate() == 1 ? out2[w] : o), (int)bv[w], part, false);
         }
