@@ -303,9 +303,31 @@ def cpu_baseline_linear(wl):
             break
         m = want
         tf, tu = run(m)
-    return {"value": m * wl.S / (tf + tu), "unit": "tokens/s", "cores": th, "kind": "oracle",
-            "sample": "%d of %d members, forward (%.2f s) + update (%.2f s); cost is linear in members" % (
-                m, wl.N, tf, tu)}
+    res = {"value": m * wl.S / (tf + tu), "unit": "tokens/s", "cores": th, "kind": "oracle",
+           "sample": "%d of %d members, forward (%.2f s) + update (%.2f s); cost is linear in members" % (
+               m, wl.N, tf, tu)}
+    # context beside the oracle's figure: the factored form itself (shared GEMM + rank-r terms, update as one
+    # contraction) in fp32 on the same host cores with a BLAS, to separate what the algorithm buys from what the
+    # GPU buys.  Timing only: random factors of the right shapes, no claim on values.
+    try:
+        import torch
+        R = wl.N * wl.S
+        g = torch.Generator().manual_seed(0)
+        W = torch.from_numpy(np.ascontiguousarray(wl.W, dtype=np.float32))
+        X = torch.from_numpy(np.ascontiguousarray(wl.X, dtype=np.float32))
+        A = torch.randn((wl.N, wl.d_out, wl.rank), generator=g)
+        B = torch.randn((wl.N, wl.d_in, wl.rank), generator=g)
+        f = torch.randn(wl.N, generator=g)
+        t0 = time.perf_counter()
+        Xm = X.view(wl.N, wl.S, wl.d_in)
+        Y = (X @ W.t()).view(wl.N, wl.S, wl.d_out) + wl.sigma * torch.bmm(torch.bmm(Xm, B), A.transpose(1, 2))
+        G = (A * f[:, None, None]).permute(1, 0, 2).reshape(wl.d_out, -1) @ B.permute(1, 0, 2).reshape(wl.d_in, -1).t()
+        dt = time.perf_counter() - t0
+        res["factored_form_fp32_blas"] = {"value": R / dt, "unit": "tokens/s", "threads": torch.get_num_threads(),
+                                          "seconds": dt, "checksum": float(Y.sum() + G.sum())}
+    except Exception as e:  # context only: never fail the benchmark line for it
+        res["factored_form_fp32_blas"] = {"error": str(e)}
+    return res
 
 
 def int8_workload(args):
