@@ -145,12 +145,13 @@ def test_forward_rejects_bad_arguments(ctx):
         ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N - 1, 1, D, D, 1, antithetic=1), L, 8, 4, T, P, tok, S, torch.empty_like(S), lg)
 
 
-def test_forward_real_shape_sampled(ctx):
-    """The benchmark's launch configuration (D = 256, 6 layers, 2^18 members in antithetic pairs) over 2 tokens:
-    sampled pairs against the oracle (a member's trajectory depends on no other member), plus the range
-    invariant of I8 over the whole output."""
+@pytest.mark.parametrize("N,T", [(1 << 18, 2), (1 << 20, 1)])
+def test_forward_real_shape_sampled(ctx, N, T):
+    """The benchmark's launch configuration (D = 256, 6 layers, 2^18 members in antithetic pairs) over 2 tokens,
+    and the largest population the paper evaluates on one GPU (2^20) over one token: sampled pairs against the
+    oracle (a member's trajectory depends on no other member), plus the range invariant of I8 over the whole output."""
     import torch
-    D, L, N, T = 256, 6, 1 << 18, 2
+    D, L = 256, 6
     P = inputs.egg_model(D, L, 1006)
     tok = inputs.egg_tokens(T, N, 1007)
     model = {k: dev(v) for k, v in P.items()}
@@ -169,7 +170,7 @@ def test_forward_real_shape_sampled(ctx):
                                              S[:, m:m + 2].cpu().numpy(), antithetic=True)
         assert (logits[:, m:m + 2].cpu().numpy() == want).all(), m
         assert (S_out[:, m:m + 2].cpu().numpy() == S_want).all(), m
-    assert logits.float().std() > 3
+    assert logits[:, :4096].float().std() > 3
 
 
 @pytest.mark.parametrize("D,L,pairs,mb", [(64, 2, 300, 0), (256, 1, 1000, 6), (16, 0, 64, 2)])
