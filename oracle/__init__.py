@@ -87,6 +87,8 @@ def _load():
         lib.oracle_embed_i8.restype = None
         lib.oracle_egg_forward_i8.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, i32] + [vp] * 13
         lib.oracle_egg_forward_i8.restype = i32
+        lib.oracle_loglik_i8.argtypes = [i64, vp, vp, i32, vp]
+        lib.oracle_loglik_i8.restype = None
         lib.oracle_threads.argtypes = []
         lib.oracle_threads.restype = i32
         _lib = lib
@@ -298,6 +300,18 @@ def egg_forward_i8(seed, step, layer, member_begin, member_count, D, L, bound, c
     if rc != 0:
         raise MemoryError("oracle_egg_forward_i8")
     return logits, S_out
+
+
+def loglik_i8(logits, targets, out=None) -> np.ndarray:
+    """Log-likelihood of the target tokens in 1/16 bit: logits int8 [rows, 256], targets uint8 [rows] -> int32
+    [rows]; added to `out` when given."""
+    logits, targets = _c(logits, np.int8), _c(targets, np.uint8)
+    rows = logits.shape[0]
+    assert logits.shape == (rows, 256) and targets.shape == (rows,)
+    acc = out is not None
+    res = _c(out, np.int32).copy() if acc else np.empty(rows, np.int32)
+    _load().oracle_loglik_i8(rows, _ptr(logits), _ptr(targets), int(acc), _ptr(res))
+    return res
 
 
 def int_threshold(alpha: float, n_terms: int, noise_std: float) -> int:

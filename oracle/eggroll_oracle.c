@@ -659,6 +659,29 @@ int oracle_egg_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t 
     return 0;
 }
 
+/* ------------------------------------------------------------------------------------------ */
+/* fitness of the integer language model (App. "Fitness Calculation in Integer Types")         */
+/* ------------------------------------------------------------------------------------------ */
+/*
+ *   y' = I32(y) + 128;   o = y'[t'] - LOG2[ sum_j EXP2[y'_j] ]
+ *   EXP2[i] = 16 * 2^(i/16),   LOG2[s] = 16 * log2(s / 16)
+ * the log-likelihood of token t' in units of 1/16 bit (logits count sixteenths of a bit).  Reading: both
+ * tables hold their formula rounded to the nearest integer (the paper calls them integer lookup tables and
+ * does not say how the entries are rounded).  logits: int8 [rows][256], targets: uint8 [rows]; out: int32
+ * [rows], added to what is there when accumulate != 0 (a member's fitness is the sum over its tokens).
+ */
+void oracle_loglik_i8(int64_t rows, const int8_t* logits, const uint8_t* targets, int accumulate, int32_t* out)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        const int8_t* y = logits + (size_t)r * 256;
+        int64_t sum = 0;
+        for (int j = 0; j < 256; ++j) sum += (int64_t)nearbyint(16.0 * exp2(((double)y[j] + 128.0) / 16.0));
+        const int32_t lg = (int32_t)nearbyint(16.0 * log2((double)sum / 16.0));
+        const int32_t o = ((int32_t)y[targets[r]] + 128) - lg;
+        out[r] = accumulate ? out[r] + o : o;
+    }
+}
+
 int oracle_threads(void)
 {
 #ifdef _OPENMP

@@ -211,3 +211,38 @@ def test_without_noise_members_with_equal_inputs_agree_and_noise_separates_them(
     assert (quiet == quiet[:, :1]).all()
     noisy, _ = oracle.egg_forward_i8(SEED, STEP, LAYER, 0, N, D, L, 8, 1, P, tok, S)
     assert any((noisy[:, m] != noisy[:, 0]).any() for m in range(1, N))
+
+
+# ------------------------------------------------------------------------------------------------
+# fitness: integer log-likelihood
+# ------------------------------------------------------------------------------------------------
+def test_loglik_of_equal_logits_is_minus_eight_bits():
+    # all 256 logits equal: every token has probability 1/256 = 8 bits = 128 sixteenths, whatever the level
+    for level in (-127, -40, 0, 77, 127):
+        y = np.full((3, 256), level, np.int8)
+        o = oracle.loglik_i8(y, np.array([0, 100, 255], np.uint8))
+        assert (np.abs(o + 128) <= 1).all(), (level, o)
+
+
+def test_loglik_tracks_the_real_log_softmax_and_normalises():
+    rng = np.random.default_rng(0)
+    y = rng.integers(-127, 128, (200, 256)).astype(np.int8)
+    y[:50] = rng.integers(-20, 21, (50, 256))                     # flat rows as well as peaked ones
+    t = rng.integers(0, 256, 200).astype(np.uint8)
+    o = oracle.loglik_i8(y, t)
+    z = y.astype(np.float64) / 16.0                                # logits in bits
+    ref = 16.0 * (z[np.arange(200), t] - np.log2(np.exp2(z).sum(1)))
+    assert np.abs(o - ref).max() <= 1.5 and (o <= 1).all()        # two table roundings
+    # over all 256 targets of a row the probabilities 2^(o/16) sum to about 1
+    row = y[7]
+    allo = oracle.loglik_i8(np.repeat(row[None], 256, 0), np.arange(256, dtype=np.uint8))
+    assert abs(np.exp2(allo / 16.0).sum() - 1.0) < 0.05
+
+
+def test_loglik_moves_with_the_target_logit_and_accumulates():
+    y = np.zeros((2, 256), np.int8)
+    y[1, 9] = 64                                                   # 4 bits above the rest
+    o = oracle.loglik_i8(y, np.array([9, 9], np.uint8))
+    assert o[1] > o[0] + 40
+    again = oracle.loglik_i8(y, np.array([9, 9], np.uint8), out=o)
+    assert (again == 2 * o).all()
