@@ -210,6 +210,18 @@ egg_status eggroll_egg_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape
                                   const int8_t* S_in, int8_t* S_out, int8_t* logits);
 
 /*
+ * Fitness of the integer language model (App. "Fitness Calculation in Integer Types"): for each row the
+ * log-likelihood of its target token in units of 1/16 bit,
+ *   y' = I32(y) + 128;   o = y'[t'] - LOG2[ sum_j EXP2[y'_j] ],   EXP2[i] = 16 * 2^(i/16),  LOG2[s] = 16 * log2(s/16),
+ * both tables rounded to the nearest integer (LOG2 is evaluated exactly for every sum, not stored: 2^28 entries).
+ * logits: int8 [rows][256] (what eggroll_egg_forward_i8 writes for one time step, or several steps as one
+ * block of rows), targets: uint8 [rows], out: int32 [rows]; accumulate != 0 adds to out (a member's fitness is
+ * the sum over its tokens).  Pointers 16-byte aligned (targets: any).  Not perturbed.  Bit-exact.
+ */
+egg_status eggroll_loglik_i8(eggroll_ctx* ctx, int64_t rows, const int8_t* logits, const uint8_t* targets,
+                             int accumulate, int32_t* out);
+
+/*
  * Integer update of every perturbed parameter of the model (App. "Parameter Update"), the counterpart of
  * eggroll_egg_forward_i8 with the same key: for the embedding table, the four GRU matrices and the two MLP
  * matrices of each layer, and the head, with that parameter's noise layer,

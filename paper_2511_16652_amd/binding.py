@@ -20,7 +20,7 @@ EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
            "eggroll_default_scale", "eggroll_set_cache_layout", "eggroll_noise_gen", "eggroll_perturbed_forward",
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
-           "eggroll_egg_forward_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
+           "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
 
 
@@ -92,6 +92,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_embed_i8.restype = i32
     lib.eggroll_egg_forward_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, P(EggModelI8), vp, vp, vp, vp]
     lib.eggroll_egg_forward_i8.restype = i32
+    lib.eggroll_loglik_i8.argtypes = [vp, i64, vp, vp, i32, vp]
+    lib.eggroll_loglik_i8.restype = i32
     lib.eggroll_egg_update_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, vp, ctypes.c_int32, P(EggModelI8)]
     lib.eggroll_egg_update_i8.restype = i32
     lib.eggroll_update_i8.argtypes = [vp, EggKey, P(EggShape), i32, vp, ctypes.c_int32, vp, vp]
@@ -193,6 +195,9 @@ class Context:
         self._check(self._lib.eggroll_egg_forward_i8(
             self._h, key, ctypes.byref(shape), int(layers), int_bound, corr_shift, int(steps), ctypes.byref(m),
             _ptr(tokens), _ptr(S_in), _ptr(S_out), _ptr(logits)))
+
+    def eggroll_loglik_i8(self, rows, logits, targets, accumulate, out):
+        self._check(self._lib.eggroll_loglik_i8(self._h, int(rows), _ptr(logits), _ptr(targets), int(accumulate), _ptr(out)))
 
     def eggroll_egg_update_i8(self, key, shape, layers, int_bound, fitness, threshold, model):
         """Updates model["emb"], ["gru_w"], ["mlp1"], ["mlp2"], ["head"] in place."""

@@ -126,7 +126,7 @@ egg_status eggroll_destroy(eggroll_ctx* c)
     if (!c) return EGG_EINVAL;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page};
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut};
     for (auto* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& r : c->recs) {
@@ -354,6 +354,17 @@ egg_status eggroll_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* 
         return fail(c, EGG_EUNSUPPORTED, "D too large for int32 accumulation");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     return launch_egg_forward_i8(c, key, *shape, layers, int_bound, corr_shift, steps, *model, tokens, S_in, S_out, logits);
+}
+
+egg_status eggroll_loglik_i8(eggroll_ctx* c, int64_t rows, const int8_t* logits, const uint8_t* targets, int accumulate,
+                             int32_t* out)
+{
+    if (!c) return EGG_EINVAL;
+    if (rows < 0 || rows > (int64_t(1) << 31)) return fail(c, EGG_EINVAL, "rows outside [0, 2^31]");
+    if (!logits || !targets || !out) return fail(c, EGG_EINVAL, "NULL pointer argument");
+    if (!aligned16(logits) || !aligned16(out)) return fail(c, EGG_EINVAL, "logits and out must be 16-byte aligned");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return launch_loglik_i8(c, rows, logits, targets, accumulate, out);
 }
 
 egg_status eggroll_egg_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int layers, int int_bound,

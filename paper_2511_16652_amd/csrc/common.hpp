@@ -33,6 +33,7 @@ struct eggroll_ctx {
     Buf i8_h;         // int8 path: ping-pong state
     Buf gru;          // integer GRU cell: factors of its four matrices, gate and matmul intermediates
     Buf zero_page;    // 256 zero bytes (K-tail loads of the GEMM core)
+    Buf lut;          // integer log-likelihood: EXP2 table and the thresholds that invert LOG2
 
     // profiling
     bool prof = false;
@@ -121,6 +122,7 @@ egg_status launch_embed_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int 
 egg_status launch_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int int_bound, int corr_shift, int T,
                                  const egg_model_i8& P, const uint8_t* tokens, const int8_t* S_in, int8_t* S_out,
                                  int8_t* logits);
+egg_status launch_loglik_i8(eggroll_ctx* c, int64_t rows, const int8_t* logits, const uint8_t* targets, int accumulate, int32_t* out);
 egg_status launch_update_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                             int int_bound, const int8_t* F, int32_t threshold, int8_t* theta, int32_t* E_out);
 

@@ -11,6 +11,7 @@
 //     exactly (the multiplier's excess (mav - 1) * |x| stays below 2^21); one integer division per lane
 //     for the multiplier, a multiply-high per element -- no table.
 #include "common.hpp"
+#include <math.h>
 
 namespace egg {
 
@@ -129,6 +130,70 @@ __global__ __launch_bounds__(256) void embed_i8_kernel(const int8_t* __restrict_
         ov[w] = o;
     }
     *(u32x4*)(y + ((size_t)row << d_log2) + (size_t)part * 16) = ov;
+}
+
+// Log-likelihood of the target token in 1/16 bit (App. "Fitness Calculation in Integer Types").  EXP2 is a
+// 256-entry table; LOG2 is not stored (the paper's table would have 2^28 entries) but inverted exactly:
+// round(16 log2 s) is the largest k whose threshold ceil(2^((k - 1/2) / 16)) is at most s, found by bisection
+// over 512 thresholds in LDS.  16 lanes share a row of 256 logits.
+__global__ __launch_bounds__(256) void loglik_i8_kernel(const int8_t* __restrict__ logits, const uint8_t* __restrict__ targets,
+                                                        const int* __restrict__ lut, int64_t rows, int accumulate,
+                                                        int* __restrict__ out)
+{
+    __shared__ int s_exp[256];
+    __shared__ int s_thr[512];
+    const int tid = threadIdx.x;
+    s_exp[tid] = lut[tid];
+    s_thr[tid] = lut[256 + tid];
+    s_thr[256 + tid] = lut[512 + tid];
+    __syncthreads();
+    const int64_t gid = (int64_t)blockIdx.x * 256 + tid;
+    const int64_t row = gid >> 4;
+    const int part = (int)(gid & 15);
+    int sum = 0;
+    if (row < rows) {
+        const u32x4 yv = *(const u32x4*)(logits + row * 256 + part * 16);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t yw = yv[w];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) sum += s_exp[sbyte(yw, b) + 128];
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) sum += __shfl_xor(sum, o, 64);
+    if (row >= rows || part != 0) return;
+    int lo = 0, hi = 511;   // invariant: s_thr[lo] <= sum; the answer is the largest such index
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_thr[mid] <= sum) lo = mid;
+        else hi = mid - 1;
+    }
+    const int o = ((int)logits[row * 256 + targets[row]] + 128) - (lo - 64);
+    out[row] = accumulate ? out[row] + o : o;
+}
+
+egg_status launch_loglik_i8(eggroll_ctx* c, int64_t rows, const int8_t* logits, const uint8_t* targets, int accumulate, int32_t* out)
+{
+    if (!c->lut.p) {
+        // tables in double on the host, once per context: EXP2[i] = round(16 * 2^(i/16)); threshold k is the
+        // smallest integer s with 16 log2 s >= k - 1/2 (never an exact tie: 2^((2k-1)/32) is irrational)
+        std::vector<int> h(256 + 512);
+        for (int i = 0; i < 256; ++i) h[i] = (int)nearbyint(16.0 * exp2(i / 16.0));
+        for (int k = 0; k < 512; ++k) {
+            const double v = ceil(exp2((k - 0.5) / 16.0));
+            h[256 + k] = v < 2147483647.0 ? (int)v : 2147483647;
+        }
+        egg_status st = reserve(c, c->lut, h.size() * sizeof(int));
+        if (st != EGG_OK) return st;
+        if ((st = check_hip(c, hipMemcpy(c->lut.p, h.data(), h.size() * sizeof(int), hipMemcpyHostToDevice), "log-likelihood tables")) != EGG_OK) return st;
+    }
+    if (rows == 0) return EGG_OK;
+    KernelScope ks(c, "loglik_i8");
+    const int64_t threads = rows * 16;
+    hipLaunchKernelGGL(loglik_i8_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, logits, targets,
+                       (const int*)c->lut.p, rows, accumulate, out);
+    return check_hip(c, hipGetLastError(), "loglik_i8 launch");
 }
 
 static int ilog2(int v)

@@ -223,3 +223,73 @@ def test_forward_and_update_use_the_same_noise(ctx):
     ctx.eggroll_egg_update_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(0, N // 2, 1, D, D, 1), L, 8, dev(F), 1, model)
     emb = model["emb"].cpu().numpy().astype(np.int64)
     assert (emb[65] == np.sign(y[2 * p])).all()
+
+
+@pytest.mark.parametrize("rows", [1, 17, 4099])
+def test_loglik_bit_exact(ctx, rows):
+    import torch
+    rng = np.random.default_rng(rows)
+    y = rng.integers(-127, 128, (rows, 256)).astype(np.int8)
+    k = rows // 3
+    y[:k] = rng.integers(-10, 11, (k, 256))                     # flat rows
+    y[k:2 * k] = -127
+    y[k:2 * k, 5] = 127                                         # one-hot rows: the smallest and the largest sums
+    t = rng.integers(0, 256, rows).astype(np.uint8)
+    out = torch.zeros(rows, dtype=torch.int32, device="cuda")
+    ctx.eggroll_loglik_i8(rows, dev(y), dev(t), 0, out)
+    want = oracle.loglik_i8(y, t)
+    assert (out.cpu().numpy() == want).all()
+    ctx.eggroll_loglik_i8(rows, dev(y), dev(t), 1, out)         # accumulate
+    assert (out.cpu().numpy() == 2 * want).all()
+
+
+def test_loglik_every_level_and_every_threshold(ctx):
+    # rows of equal logits at every level, and rows whose sum of exponentials sweeps the range in small steps:
+    # every entry of the EXP2 table and, densely, the rounding boundaries of the inverted LOG2
+    import torch
+    rows = []
+    for level in range(-127, 128):
+        rows.append(np.full(256, level))
+    rng = np.random.default_rng(1)
+    for hot in range(1, 256, 3):
+        for level in range(-127, 128, 7):
+            r = np.full(256, -127)
+            r[:hot] = level
+            rows.append(r)
+    y = np.array(rows, np.int8)
+    t = rng.integers(0, 256, len(rows)).astype(np.uint8)
+    out = torch.zeros(len(rows), dtype=torch.int32, device="cuda")
+    ctx.eggroll_loglik_i8(len(rows), dev(y), dev(t), 0, out)
+    assert (out.cpu().numpy() == oracle.loglik_i8(y, t)).all()
+
+
+def test_integer_es_learns_a_cycle(ctx):
+    """End to end on the GPU, integers only: forward pass of a small model for a population in antithetic pairs,
+    log-likelihood fitness, sign(s+ - s-) shaping, integer update of all parameters.  The data is the cycle
+    a b c d a b ... at a random phase per pair, so the next token follows from the current one: from about 8.5 bits
+    per token (logits of a random model) the population's mean must fall below 2 bits in 30 ES steps.  Checks that
+    the forward pass, the fitness and the update agree on which member carries which sign of which noise."""
+    import torch
+    D, L, N, T, bound, cs = 64, 1, 8192, 16, 8, 4
+    model = {k: dev(v) for k, v in inputs.egg_model(D, L, 3).items()}
+    rng = np.random.default_rng(0)
+    sym = np.frombuffer(b"abcd", np.uint8)
+    thr = eb.eggroll_int_threshold(0.3, N // 2, (bound * (bound + 1) / 3.0) ** 0.5)
+    S0 = torch.zeros((L, N, D), dtype=torch.int8, device="cuda")
+    S1 = torch.empty_like(S0)
+    logits = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+    per = torch.empty(N * T, dtype=torch.int32, device="cuda")
+    bits = []
+    for step in range(30):
+        phase = rng.integers(0, 4, N // 2).repeat(2)                      # both members of a pair see the same data
+        seq = sym[(phase[None, :] + np.arange(T + 1)[:, None]) % 4]      # [T + 1, N]
+        key = eb.make_key(1, step, 0)
+        ctx.eggroll_egg_forward_i8(key, eb.make_shape(0, N, 1, D, D, 1, antithetic=1), L, bound, cs, T, model,
+                                   dev(seq[:T]), S0, S1, logits)
+        ctx.eggroll_loglik_i8(N * T, logits.view(N * T, 256), dev(seq[1:]).view(N * T), 0, per)
+        f = per.view(T, N).sum(0)
+        F = torch.sign(f[0::2] - f[1::2]).to(torch.int8).contiguous()
+        ctx.eggroll_egg_update_i8(key, eb.make_shape(0, N // 2, 1, D, D, 1), L, bound, F, thr, model)
+        bits.append(-float(f.float().mean()) / T / 16.0)
+    torch.cuda.synchronize()
+    assert bits[0] > 7.0 and bits[-1] < 2.0, bits[::5]
