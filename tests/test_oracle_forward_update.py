@@ -271,3 +271,26 @@ def test_int8_shift_floors_and_clamp_edges():
                               (-3, 1, 1, -2), (3, 1, 1, 1), (-127, 127, 7, -127), (-100, 100, 7, -79)]:
         got = oracle.forward_i8(0, 0, 0, 0, 1, 1, 0, 4, os_, 1, np.array([[w]], np.int8), np.array([[h]], np.int8))
         assert int(got[0, 0]) == expect, (h, w, os_, int(got[0, 0]), expect)
+
+
+def test_oracle_es_steps_descend_a_quadratic():
+    # Alg. 1 with the oracle's own forward and update: fitness = -sum ||y - W* x||^2 on a batch shared by all
+    # members, z-scored; W += lr * G must reduce the loss.  A wrong sign, a transposed G or factors that differ
+    # between forward and update would make it rise or stall.
+    d, N, S, sigma, r = 8, 512, 8, 0.01, 2
+    lr = 0.3 * sigma
+    rng = np.random.default_rng(0)
+    w_star = rng.standard_normal((d, d)) / np.sqrt(d)
+    W = np.zeros((d, d), np.float32)
+    losses = []
+    for step in range(25):
+        xb = rng.standard_normal((S, d)).astype(np.float32)
+        X = np.tile(xb, (N, 1))
+        target = xb @ w_star.T
+        Y = oracle.forward(7, step, 0, 0, N, S, d, d, r, oracle.NOISE_F32, sigma, 0, W, X)
+        f = -((Y - np.tile(target, (N, 1))) ** 2).sum(1).reshape(N, S).sum(1)
+        z = (f - f.mean()) / (f.std() + 1e-8)
+        G = oracle.update(7, step, 0, 0, N, d, d, r, oracle.NOISE_F32, z, 1.0 / (N * sigma * np.sqrt(r)))
+        W = (W + lr * G).astype(np.float32)
+        losses.append(float(((xb @ W.T - target) ** 2).sum(1).mean()))
+    assert losses[0] > 4.0 and losses[-1] < 0.5 * losses[0], losses[::4]
