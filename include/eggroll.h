@@ -16,6 +16,11 @@
  *     context was created for, 16-byte aligned.  The library allocates only its own scratch
  *     (inside the context), never frees or keeps caller memory, never synchronises the stream:
  *     all work is enqueued on the stream given at creation and is ordered on it.
+ *     Two exceptions to "never synchronises": a call that needs more scratch than the context holds
+ *     (the first call at a new, larger shape) waits for the stream before it replaces the buffer,
+ *     and the first eggroll_loglik_i8 call of a context uploads its tables with a blocking copy.
+ *   - A context is not thread-safe: its calls share the scratch, so calls on one context must not
+ *     overlap in time on the host, and work of two contexts that share a stream is ordered by it.
  *   - Matrices are dense row-major.  M = W[d_out][d_in].  Activations X[R][d_in], Y[R][d_out] with
  *     R = member_count * rows_per_member, member-major: row q belongs to member
  *     member_begin + q / rows_per_member.  Factors are laid out [member][d][rank] (rank fastest).
