@@ -18,7 +18,11 @@ LIB = os.path.join(HERE, "libeggroll.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 UNITS = ["api", "k_noise", "k_project", "k_forward", "k_update", "k_int8", "k_update_i8", "k_gru_i8", "k_egg_model"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Wno-pass-failed", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Wno-pass-failed", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the epilogues are long bodies inside fully unrolled loops over a lane's accumulator blocks: past the
+         # default limit (16 K instructions) a "#pragma unroll" is dropped, the accumulator array is then
+         # indexed dynamically and lives in scratch memory
+         "-mllvm", "-pragma-unroll-threshold=200000"]
 
 
 def _compile(unit: str) -> str:
