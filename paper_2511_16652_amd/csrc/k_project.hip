@@ -137,26 +137,29 @@ __global__ __launch_bounds__(256) void project_row_kernel(StreamKey kb, uint32_t
 }
 
 // The same projection for 8 consecutive members per workgroup, with B leaving the kernel as the K-packed fp16
-// panel the update contracts ([member / 8][k][member % 8]): a thread generates the column pair (2b, 2b+1) of the
-// 8 members and stores two 16-byte chunks that are neighbours in the panel, 2 KB contiguous per wave.  Every
-// member's partial sums are formed in the order of project_row_kernel, so t is bit-identical to that kernel's.
-__global__ __launch_bounds__(256) void project_row8_kernel(StreamKey kb, uint32_t member_begin, int64_t members, int d_in,
+// panel the update contracts ([member / 8][k][member % 8]).  512 threads: thread (b, half) generates the column
+// pair (2b, 2b+1) of members 4 half .. 4 half + 3 and stores its 8 bytes of the two 16-byte chunks, which are
+// neighbours in the panel.  The first 256 threads (half 0) and the last 256 (half 1) each hold the 256 b-lanes
+// in the order of project_row_kernel, and every member's partial sums go through the same shuffle tree and the
+// same final additions, so t is bit-identical to that kernel's.
+__global__ __launch_bounds__(512) void project_row8_kernel(StreamKey kb, uint32_t member_begin, int64_t members, int d_in,
                                                            const void* __restrict__ X, float* __restrict__ t,
                                                            u32x4* __restrict__ panel)
 {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     __shared__ float red[4][8];
     const int tid = threadIdx.x;
+    const int half = tid >> 8, bl = tid & 255;
     const int64_t g = blockIdx.x;
     const int pairs = d_in >> 1;
-    float acc[8];
+    float acc[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int b = tid; b < pairs; b += 256) {
-        float lo[8], hi[8];
+    for (int e = 0; e < 4; ++e) acc[e] = 0.f;
+    for (int b = bl; b < pairs; b += 256) {
+        float lo[4], hi[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t i = g * 8 + e;
+        for (int e = 0; e < 4; ++e) {
+            const int64_t i = g * 8 + half * 4 + e;
             lo[e] = hi[e] = 0.f;
             if (i < members) {
                 uint32_t w0, w1;
@@ -171,27 +174,28 @@ __global__ __launch_bounds__(256) void project_row8_kernel(StreamKey kb, uint32_
                 hi[e] = bf16_hi(pk);
             }
         }
-        u32x4 c0, c1;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        uint2 c0, c1;
+        {
             h2 p, q;
-            p[0] = (_Float16)lo[2 * w]; p[1] = (_Float16)lo[2 * w + 1];
-            q[0] = (_Float16)hi[2 * w]; q[1] = (_Float16)hi[2 * w + 1];
-            c0[w] = __builtin_bit_cast(uint32_t, p);
-            c1[w] = __builtin_bit_cast(uint32_t, q);
+            p[0] = (_Float16)lo[0]; p[1] = (_Float16)lo[1];
+            q[0] = (_Float16)lo[2]; q[1] = (_Float16)lo[3];
+            c0.x = __builtin_bit_cast(uint32_t, p); c0.y = __builtin_bit_cast(uint32_t, q);
+            p[0] = (_Float16)hi[0]; p[1] = (_Float16)hi[1];
+            q[0] = (_Float16)hi[2]; q[1] = (_Float16)hi[3];
+            c1.x = __builtin_bit_cast(uint32_t, p); c1.y = __builtin_bit_cast(uint32_t, q);
         }
-        u32x4* o = panel + g * d_in + 2 * b;
+        uint2* o = (uint2*)(panel + g * d_in + 2 * b) + half;   // bytes 8 half .. 8 half + 7 of chunk 2b
         o[0] = c0;
-        o[1] = c1;
+        o[2] = c1;                                              // the same bytes of chunk 2b + 1
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 4; ++e) {
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) acc[e] += __shfl_xor(acc[e], off, 64);
     }
     if ((tid & 63) == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[tid >> 6][e] = acc[e];
+        for (int e = 0; e < 4; ++e) red[bl >> 6][half * 4 + e] = acc[e];
     }
     __syncthreads();
     if (tid < 8 && g * 8 + tid < members) t[g * 8 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
@@ -207,7 +211,7 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
         const int64_t groups = (shape.member_count + 7) / 8;
         if (groups > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many members in one call");
         KernelScope ks(c, "project");
-        hipLaunchKernelGGL(project_row8_kernel, dim3((unsigned)groups), dim3(256), 0, c->stream, kb, (uint32_t)shape.member_begin,
+        hipLaunchKernelGGL(project_row8_kernel, dim3((unsigned)groups), dim3(512), 0, c->stream, kb, (uint32_t)shape.member_begin,
                            shape.member_count, shape.d_in, X, t, (u32x4*)B_cache);
         return check_hip(c, hipGetLastError(), "project launch");
     }
