@@ -207,8 +207,8 @@ typedef struct {
  * shape: d_out = d_in = D, rank 1, rows_per_member 1; antithetic as in (2').  layers >= 0.
  * tokens: uint8 [steps][member_count]; S_in, S_out: int8 [layers][member_count][D], must not overlap
  * (both may be NULL when layers == 0); logits: int8 [steps][member_count][256].  Scratch held by the
- * context: about (18 layers + 2) D + 512 bytes per noise id for the factors, 11 D + 16 bytes per member for
- * one step's activations and, when steps > 1, one more copy of the state.  Bit-exact.
+ * context: about (18 layers + 2) D + 512 bytes per noise id for the factors, 11 D + 4 (4 + 2 layers) bytes per
+ * member for one step's activations and dot products and, when steps > 1, one more copy of the state.  Bit-exact.
  */
 egg_status eggroll_egg_forward_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int int_bound,
                                   int corr_shift, int steps, const egg_model_i8* model, const uint8_t* tokens,
