@@ -140,3 +140,45 @@ def egg_tokens(T: int, N: int, data_seed: int) -> np.ndarray:
     alphabet = np.arange(32, 127)
     weights = 1.0 / (1.0 + np.arange(alphabet.size))      # Zipf-like
     return rng.choice(rng.permutation(alphabet), size=(T, N), p=weights / weights.sum()).astype(np.uint8)
+
+
+def mlp_stack(d: int, d_ff: int, L: int, data_seed: int) -> dict:
+    """Weights of the GELU MLP stack: W1 [L, d_ff, d] ~ N(0, 1/d), W2 [L, d, d_ff] ~ N(0, 1/d_ff), bf16 values."""
+    rng = np.random.default_rng(data_seed)
+    W1 = np.stack([round_to_bf16(rng.standard_normal((d_ff, d), dtype=np.float32) / np.float32(np.sqrt(d))) for _ in range(L)])
+    W2 = np.stack([round_to_bf16(rng.standard_normal((d, d_ff), dtype=np.float32) / np.float32(np.sqrt(d_ff))) for _ in range(L)])
+    return {"W1": W1, "W2": W2}
+
+
+def member_rows(data_seed: int, member: int, S: int, d: int) -> np.ndarray:
+    """Input rows x ~ N(0, 1) of one member, bf16 values, seeded per member so that any subset of a large
+    population can be drawn without drawing the rest."""
+    rng = np.random.default_rng([data_seed, int(member)])
+    return round_to_bf16(rng.standard_normal((S, d), dtype=np.float32))
+
+
+DECODER_PARAM_SHAPES = lambda V, d, d_ff, L: {  # noqa: E731  (layouts of the decoder's parameter arrays)
+    "emb": (V, d), "norm1": (L, d), "wq": (L, d, d), "wk": (L, d, d), "wv": (L, d, d), "wo": (L, d, d),
+    "norm2": (L, d), "w_up": (L, d_ff, d), "w_down": (L, d, d_ff), "norm_f": (d,), "head": (V, d)}
+
+
+def decoder_params(V: int, d: int, d_ff: int, L: int, data_seed: int, norm_jitter: float = 0.0) -> dict:
+    """Random-init decoder: linear matrices N(0, 1/fan_in), embedding N(0, 1), normalisation gains 1
+    (+ norm_jitter * N(0, 1), for tests that must see the gains), all rounded to bf16."""
+    rng = np.random.default_rng(data_seed)
+    out = {}
+    for name, shape in DECODER_PARAM_SHAPES(V, d, d_ff, L).items():
+        if name.startswith("norm"):
+            a = 1.0 + norm_jitter * rng.standard_normal(shape, dtype=np.float32)
+        elif name == "emb":
+            a = rng.standard_normal(shape, dtype=np.float32)
+        else:
+            a = rng.standard_normal(shape, dtype=np.float32)
+            a *= np.float32(1.0 / np.sqrt(shape[-1]))
+        out[name] = round_to_bf16(a)
+    return out
+
+
+def decoder_tokens(N: int, S: int, V: int, data_seed: int) -> np.ndarray:
+    """Uniform random token ids [N, S] in [0, V)."""
+    return np.random.default_rng(data_seed).integers(0, V, size=(N, S), dtype=np.int64).astype(np.int32)
