@@ -16,9 +16,14 @@
  *     context was created for, 16-byte aligned.  The library allocates only its own scratch
  *     (inside the context), never frees or keeps caller memory, never synchronises the stream:
  *     all work is enqueued on the stream given at creation and is ordered on it.
- *     Two exceptions to "never synchronises": a call that needs more scratch than the context holds
- *     (the first call at a new, larger shape) waits for the stream before it replaces the buffer,
- *     and the first eggroll_loglik_i8 call of a context uploads its tables with a blocking copy.
+ *     One exception to "never synchronises": the first eggroll_loglik_i8 call of a context uploads its
+ *     tables with a blocking copy.
+ *   - Scratch only grows.  A call that needs more scratch than the context holds (the first call at a new,
+ *     larger shape) allocates a larger buffer and parks the old one until eggroll_trim or eggroll_destroy, so
+ *     work already enqueued, and HIP graphs captured from earlier calls, keep valid addresses.  A graph
+ *     replays the scratch addresses of the calls it captured: capture after an eager call of the same shapes,
+ *     and do not call eggroll_trim while such a graph is still in use.  eggroll_scratch_generation changes
+ *     whenever a buffer was replaced.
  *   - A context is not thread-safe: its calls share the scratch, so calls on one context must not
  *     overlap in time on the host, and work of two contexts that share a stream is ordered by it.
  *   - Matrices are dense row-major.  M = W[d_out][d_in].  Activations X[R][d_in], Y[R][d_out] with
@@ -84,6 +89,11 @@ const char* eggroll_strerror(egg_status s);
 /* text of the last failure on this context (host string owned by the context) */
 const char* eggroll_last_error(const eggroll_ctx* ctx);
 
+/* Number of scratch replacements so far (see "Scratch only grows" above). */
+uint64_t eggroll_scratch_generation(const eggroll_ctx* ctx);
+/* Waits for the stream and frees the scratch buffers that larger ones have replaced. */
+egg_status eggroll_trim(eggroll_ctx* ctx);
+
 /* 1/(N * sigma * sqrt(r)): the constant of the Monte-Carlo estimator (Eq. matrix_mc) times the
    1/sqrt(r) of E_i, so that  scale * sum_i f_i A_i B_i^T  =  (1/(sigma N)) sum_i f_i E_i.
    (Alg. 1 absorbs 1/sigma into the learning rate; pass your own `scale` for that form.) */
@@ -114,6 +124,15 @@ egg_status eggroll_noise_gen(eggroll_ctx* ctx, egg_key key, const egg_shape* sha
 egg_status eggroll_perturbed_forward(eggroll_ctx* ctx, egg_key key, const egg_shape* shape,
                                      egg_dtype io_dtype, egg_dtype y_dtype, float sigma, egg_act act,
                                      const void* W, const void* X, void* Y, void* A_cache, void* B_cache);
+
+/*
+ * (2a) The same layer inside a residual stream:  Y = R_in + act( X W_i^T )  with W_i as in (2), summed in
+ * fp32 before the one rounding to y_dtype.  R_in: [R][d_out] of y_dtype; it may be Y itself (every element
+ * is read once and then written once by the same wavefront).  All other arguments as in (2).
+ */
+egg_status eggroll_perturbed_forward_add(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                         egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                         const void* R_in, void* Y, void* A_cache, void* B_cache);
 
 /*
  * Layout of the factor caches that eggroll_perturbed_forward writes and eggroll_update reads on this context
@@ -275,6 +294,77 @@ egg_status eggroll_update_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* sha
    alpha >= 1 gives 0; alpha <= 0 gives INT64_MAX.  Uniform integers on {-b..b} have
    noise_std = sqrt(b(b+1)/3).  Host-only, no context needed. */
 int64_t eggroll_int_threshold(double alpha, int64_t n_terms, double noise_std);
+
+/*
+ * (4) Multi-layer float workloads built on (2) and (3).  The paper perturbs every parameter matrix of a
+ * model independently (Alg. 1; Sec. 4.1) and evaluates all members in one batched pass (Sec. 4.2); the two
+ * model families below are the synthetic stand-ins this library is measured on.  Everything is bf16,
+ * row-major, member-major rows; a population is walked in chunks of `chunk_members` members (0 = a default
+ * of about 2^18 rows per chunk), which changes neither noise nor results.  Activations of one chunk live in
+ * the context's scratch.
+ *
+ * Unperturbed glue (identical in the perturbed and the sigma = 0 pass); d a multiple of 8:
+ *   embed_rows       X[q] = emb[tokens[q]]                         emb [vocab][d], tokens int32 [rows] in [0, vocab)
+ *   rmsnorm          Y[q][k] = X[q][k] gain[k] / sqrt(mean_k X[q][k]^2 + eps);  Y may be X
+ *   causal_attention per member and head, over the member's own rows_per_member <= 256 tokens:
+ *                    O[s] = sum_{s' <= s} softmax_s'( Q[s].K[s'] / sqrt(head_dim) ) V[s'],  no positional encoding;
+ *                    Q, K, V, O [members * rows_per_member][heads * head_dim], head h in columns h*head_dim..;
+ *                    head_dim in {32, 64, 128}; O must not overlap Q, K or V
+ *   token_loglik     out[q] = logits[q][tokens[q+1]] - log sum_j exp(logits[q][j]) for every token that has a
+ *                    successor in its member, 0 for a member's last token; logits [rows][vocab], vocab a multiple of 8
+ */
+egg_status eggroll_embed_rows_bf16(eggroll_ctx* ctx, int64_t rows, int d, int vocab, const void* emb, const int32_t* tokens, void* X);
+egg_status eggroll_rmsnorm_bf16(eggroll_ctx* ctx, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y);
+egg_status eggroll_causal_attention_bf16(eggroll_ctx* ctx, int64_t members, int rows_per_member, int heads, int head_dim,
+                                         const void* Q, const void* K, const void* V, void* O);
+egg_status eggroll_token_loglik_bf16(eggroll_ctx* ctx, int64_t members, int rows_per_member, int vocab, const void* logits,
+                                     const int32_t* tokens, float* out);
+
+/*
+ * GELU MLP stack:  per layer l  h <- W2_l' gelu( W1_l' h ),  W' the member's perturbed copy, gelu in the exact
+ * erf form, activations rounded to bf16 between the linear layers, no bias, normalisation or residual.
+ * shape: d_out = d_in = d (a multiple of 8), rows_per_member = S, rank, member range; antithetic 0.
+ * W1: [layers][d_ff][d], W2: [layers][d][d_ff];  X, Y: [member_count * S][d] (Y may not be X).
+ * Noise layer ids: key.layer + 2 l (W1_l), key.layer + 2 l + 1 (W2_l).
+ * The update applies (3) to every matrix with its noise layer:  W <- bf16( W + lr * scale * sum_i f_i A_i B_i^T );
+ * there shape names the whole population (rows_per_member ignored).
+ */
+egg_status eggroll_mlp_stack_forward(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int d_ff, float sigma,
+                                     const void* W1, const void* W2, const void* X, void* Y, int64_t chunk_members);
+egg_status eggroll_mlp_stack_update(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int layers, int d_ff,
+                                    const float* fitness, float scale, float lr, void* W1, void* W2);
+
+/*
+ * Pre-norm decoder:  x = emb[token];  per layer l:
+ *   h = rmsnorm(x; norm1_l);  q, k, v = Wq' h, Wk' h, Wv' h;  o = causal_attention(q, k, v);  x = x + Wo' o;
+ *   h = rmsnorm(x; norm2_l);  x = x + Wdown' gelu( Wup' h );
+ * logits = Whead' rmsnorm(x; norm_f).  The embedding table and the normalisation gains are not perturbed; the
+ * 6 layers + 1 matrices are, under the noise layer ids key.layer + 6 l + {0..5: q, k, v, o, up, down} and
+ * key.layer + 6 layers (head).  Every stored tensor is bf16; the residual sums are formed in fp32 (2a).
+ * shape: rows_per_member = S <= 256 tokens per member, rank, member range (d_out, d_in ignored); antithetic 0.
+ * tokens: int32 [member_count][S] in [0, vocab).  logits: bf16 [member_count * S][vocab] or NULL (then only a
+ * chunk's logits exist at a time, in scratch); loglik: fp32 [member_count * S] as token_loglik defines, or NULL.
+ * d_model = heads * head_dim with head_dim in {32, 64, 128}; d_model, d_ff, vocab multiples of 8.
+ */
+typedef struct { int32_t layers, d_model, heads, d_ff, vocab; float rms_eps; } egg_decoder_cfg;
+typedef struct {
+    void* emb;     /* [vocab][d]      */
+    void* norm1;   /* [layers][d]     */
+    void* wq;      /* [layers][d][d]  */
+    void* wk;      /* [layers][d][d]  */
+    void* wv;      /* [layers][d][d]  */
+    void* wo;      /* [layers][d][d]  */
+    void* norm2;   /* [layers][d]     */
+    void* w_up;    /* [layers][d_ff][d] */
+    void* w_down;  /* [layers][d][d_ff] */
+    void* norm_f;  /* [d]             */
+    void* head;    /* [vocab][d]      */
+} egg_decoder_weights;
+egg_status eggroll_decoder_forward(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, const egg_decoder_cfg* cfg,
+                                   const egg_decoder_weights* weights, float sigma, const int32_t* tokens, void* logits,
+                                   float* loglik, int64_t chunk_members);
+egg_status eggroll_decoder_update(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, const egg_decoder_cfg* cfg,
+                                  const float* fitness, float scale, float lr, const egg_decoder_weights* weights);
 
 /*
  * Per-kernel timing for benchmarks.  With profiling on, every kernel the library launches is

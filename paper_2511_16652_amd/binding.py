@@ -21,7 +21,10 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
            "eggroll_default_scale", "eggroll_set_cache_layout", "eggroll_noise_gen", "eggroll_perturbed_forward",
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
-           "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read"]
+           "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read",
+           "eggroll_scratch_generation", "eggroll_trim", "eggroll_perturbed_forward_add",
+           "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_token_loglik_bf16",
+           "eggroll_mlp_stack_forward", "eggroll_mlp_stack_update", "eggroll_decoder_forward", "eggroll_decoder_update"]
 
 
 class EggKey(ctypes.Structure):
@@ -35,6 +38,18 @@ EGG_MODEL_FIELDS = ("emb", "ln1", "gru_w", "gru_b", "ln2", "mlp1", "mlp2", "ln_o
 
 class EggModelI8(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in EGG_MODEL_FIELDS]
+
+
+class EggDecoderCfg(ctypes.Structure):
+    _fields_ = [("layers", ctypes.c_int32), ("d_model", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("d_ff", ctypes.c_int32), ("vocab", ctypes.c_int32), ("rms_eps", ctypes.c_float)]
+
+
+EGG_DECODER_FIELDS = ("emb", "norm1", "wq", "wk", "wv", "wo", "norm2", "w_up", "w_down", "norm_f", "head")
+
+
+class EggDecoderWeights(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in EGG_DECODER_FIELDS]
 
 
 class EggShape(ctypes.Structure):
@@ -100,6 +115,28 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_update_i8.restype = i32
     lib.eggroll_int_threshold.argtypes = [ctypes.c_double, i64, ctypes.c_double]
     lib.eggroll_int_threshold.restype = i64
+    lib.eggroll_scratch_generation.argtypes = [vp]
+    lib.eggroll_scratch_generation.restype = ctypes.c_uint64
+    lib.eggroll_trim.argtypes = [vp]
+    lib.eggroll_trim.restype = i32
+    lib.eggroll_perturbed_forward_add.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp, vp]
+    lib.eggroll_perturbed_forward_add.restype = i32
+    lib.eggroll_embed_rows_bf16.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+    lib.eggroll_embed_rows_bf16.restype = i32
+    lib.eggroll_rmsnorm_bf16.argtypes = [vp, i64, i32, f32, vp, vp, vp]
+    lib.eggroll_rmsnorm_bf16.restype = i32
+    lib.eggroll_causal_attention_bf16.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.eggroll_causal_attention_bf16.restype = i32
+    lib.eggroll_token_loglik_bf16.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+    lib.eggroll_token_loglik_bf16.restype = i32
+    lib.eggroll_mlp_stack_forward.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, vp, vp, vp, vp, i64]
+    lib.eggroll_mlp_stack_forward.restype = i32
+    lib.eggroll_mlp_stack_update.argtypes = [vp, EggKey, P(EggShape), i32, i32, vp, f32, f32, vp, vp]
+    lib.eggroll_mlp_stack_update.restype = i32
+    lib.eggroll_decoder_forward.argtypes = [vp, EggKey, P(EggShape), P(EggDecoderCfg), P(EggDecoderWeights), f32, vp, vp, vp, i64]
+    lib.eggroll_decoder_forward.restype = i32
+    lib.eggroll_decoder_update.argtypes = [vp, EggKey, P(EggShape), P(EggDecoderCfg), vp, f32, f32, P(EggDecoderWeights)]
+    lib.eggroll_decoder_update.restype = i32
     lib.eggroll_profile_enable.argtypes = [vp, i32]
     lib.eggroll_profile_enable.restype = i32
     lib.eggroll_profile_read.argtypes = [vp, P(ctypes.c_char_p), P(i64), P(ctypes.c_double), i32]
@@ -112,6 +149,10 @@ def _dtype_code(t) -> int:
     import torch
     return {torch.float32: EGG_F32, torch.bfloat16: EGG_BF16, torch.int8: EGG_I8,
             torch.uint32: EGG_U32, torch.int32: EGG_U32}[t.dtype]
+
+
+def make_decoder_cfg(layers, d_model, heads, d_ff, vocab, rms_eps=1e-5) -> EggDecoderCfg:
+    return EggDecoderCfg(int(layers), int(d_model), int(heads), int(d_ff), int(vocab), float(rms_eps))
 
 
 def _ptr(t):
@@ -171,6 +212,53 @@ class Context:
         self._check(self._lib.eggroll_perturbed_forward(
             self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
             _ptr(W), _ptr(X), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
+
+    def eggroll_perturbed_forward_add(self, key, shape, sigma, act, W, X, R_in, Y, A_cache=None, B_cache=None):
+        self._check(self._lib.eggroll_perturbed_forward_add(
+            self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
+            _ptr(W), _ptr(X), _ptr(R_in), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
+
+    def eggroll_embed_rows_bf16(self, rows, d, vocab, emb, tokens, X):
+        self._check(self._lib.eggroll_embed_rows_bf16(self._h, int(rows), int(d), int(vocab), _ptr(emb), _ptr(tokens), _ptr(X)))
+
+    def eggroll_rmsnorm_bf16(self, rows, d, eps, gain, X, Y):
+        self._check(self._lib.eggroll_rmsnorm_bf16(self._h, int(rows), int(d), float(eps), _ptr(gain), _ptr(X), _ptr(Y)))
+
+    def eggroll_causal_attention_bf16(self, members, rows_per_member, heads, head_dim, Q, K, V, O):
+        self._check(self._lib.eggroll_causal_attention_bf16(
+            self._h, int(members), int(rows_per_member), int(heads), int(head_dim), _ptr(Q), _ptr(K), _ptr(V), _ptr(O)))
+
+    def eggroll_token_loglik_bf16(self, members, rows_per_member, vocab, logits, tokens, out):
+        self._check(self._lib.eggroll_token_loglik_bf16(
+            self._h, int(members), int(rows_per_member), int(vocab), _ptr(logits), _ptr(tokens), _ptr(out)))
+
+    def eggroll_mlp_stack_forward(self, key, shape, layers, d_ff, sigma, W1, W2, X, Y, chunk_members=0):
+        self._check(self._lib.eggroll_mlp_stack_forward(
+            self._h, key, ctypes.byref(shape), int(layers), int(d_ff), float(sigma), _ptr(W1), _ptr(W2), _ptr(X), _ptr(Y),
+            int(chunk_members)))
+
+    def eggroll_mlp_stack_update(self, key, shape, layers, d_ff, fitness, scale, lr, W1, W2):
+        self._check(self._lib.eggroll_mlp_stack_update(
+            self._h, key, ctypes.byref(shape), int(layers), int(d_ff), _ptr(fitness), float(scale), float(lr), _ptr(W1), _ptr(W2)))
+
+    def eggroll_decoder_forward(self, key, shape, cfg, weights, sigma, tokens, logits=None, loglik=None, chunk_members=0):
+        """cfg: EggDecoderCfg; weights: mapping from the names in EGG_DECODER_FIELDS to bf16 device tensors."""
+        w = EggDecoderWeights(*[_ptr(weights[name]) for name in EGG_DECODER_FIELDS])
+        self._check(self._lib.eggroll_decoder_forward(
+            self._h, key, ctypes.byref(shape), ctypes.byref(cfg), ctypes.byref(w), float(sigma), _ptr(tokens), _ptr(logits),
+            _ptr(loglik), int(chunk_members)))
+
+    def eggroll_decoder_update(self, key, shape, cfg, fitness, scale, lr, weights):
+        """Updates the 6 layers + 1 perturbed matrices of `weights` in place."""
+        w = EggDecoderWeights(*[_ptr(weights[name]) for name in EGG_DECODER_FIELDS])
+        self._check(self._lib.eggroll_decoder_update(
+            self._h, key, ctypes.byref(shape), ctypes.byref(cfg), _ptr(fitness), float(scale), float(lr), ctypes.byref(w)))
+
+    def eggroll_scratch_generation(self):
+        return int(self._lib.eggroll_scratch_generation(self._h))
+
+    def eggroll_trim(self):
+        self._check(self._lib.eggroll_trim(self._h))
 
     def eggroll_perturbed_forward_i8(self, key, shape, int_bound, corr_shift, out_shift, steps, W, H_in, H_out):
         self._check(self._lib.eggroll_perturbed_forward_i8(

@@ -27,24 +27,32 @@ egg_status check_hip(eggroll_ctx* c, hipError_t e, const char* what)
     return fail(c, EGG_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// Scratch only grows.  A buffer that is too small is replaced by a larger one and parked on the retired list
+// instead of being freed: kernels already enqueued, and HIP graphs captured earlier, keep valid addresses.
+// Growth is geometric so that a slowly growing sequence of shapes retires O(log) buffers.
 egg_status reserve(eggroll_ctx* c, eggroll_ctx::Buf& b, size_t bytes)
 {
     if (b.bytes >= bytes) return EGG_OK;
+    size_t want = (bytes + 255) & ~size_t(255);
+    void* p = nullptr;
+    hipError_t e = hipErrorOutOfMemory;
     if (b.p) {
-        // work that still reads the old buffer is ordered on our stream
-        if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, EGG_EHIP, "sync before scratch growth");
-        (void)hipFree(b.p);
-        b.p = nullptr;
-        b.bytes = 0;
+        const size_t geo = (b.bytes + b.bytes / 2 + 255) & ~size_t(255);
+        if (geo > want) {
+            e = hipMalloc(&p, geo);
+            if (e == hipSuccess) want = geo;
+            else (void)hipGetLastError();
+        }
     }
-    const size_t want = (bytes + 255) & ~size_t(255);
-    hipError_t e = hipMalloc(&b.p, want);
+    if (e != hipSuccess) e = hipMalloc(&p, want);
     if (e != hipSuccess) {
-        b.p = nullptr;
         (void)hipGetLastError();
         return fail(c, EGG_ENOMEM, "scratch of %zu bytes: %s", want, hipGetErrorString(e));
     }
+    if (b.p) c->retired.push_back(b);
+    b.p = p;
     b.bytes = want;
+    ++c->scratch_generation;
     return EGG_OK;
 }
 
@@ -91,6 +99,71 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bo
     return EGG_OK;
 }
 
+// projection pre-pass + shared GEMM with the correction epilogue for one validated linear layer
+egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
+                          egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
+                          float* t_fixed)
+{
+    const bool panel = c->cache_layout == EGG_CACHE_PANEL;
+    const int64_t R = shape.member_count * (int64_t)shape.rows_per_member;
+    float* t = nullptr;
+    if (sigma != 0.0f) {
+        egg_status s = EGG_OK;
+        if (t_fixed) {
+            t = t_fixed;  // the caller's (static) projection buffer: nothing is allocated on this path
+        } else {
+            s = reserve(c, c->t_buf, (size_t)R * shape.rank * sizeof(float));
+            if (s != EGG_OK) return s;
+            t = (float*)c->t_buf.p;
+        }
+        s = launch_project(c, make_stream_key(key.seed, key.step, key.layer, 1), shape, io_dtype, X, t, B_cache, panel);
+        if (s != EGG_OK) return s;
+    }
+    return launch_forward_gemm(c, make_stream_key(key.seed, key.step, key.layer, 0), shape, io_dtype, y_dtype, sigma, act, W, X, Y,
+                               t, A_cache, resid);
+}
+
+// validation shared by the forward entry points; t_fixed != NULL: the projections go to that buffer of t_capacity
+// values and nothing may be allocated on the way
+egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype, egg_dtype y_dtype,
+                                float sigma, egg_act act, const void* W, const void* X, const void* R_in, bool need_r, void* Y,
+                                void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity)
+{
+    if (!c) return EGG_EINVAL;
+    egg_status s = validate_shape(c, shape, true, true);
+    if (s != EGG_OK) return s;
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!W || !X || !Y || (need_r && !R_in)) return fail(c, EGG_EINVAL, "W, X, Y (and R_in) must be non-NULL");
+    if (!aligned16(W) || !aligned16(X) || !aligned16(Y) || !aligned16(A_cache) || !aligned16(B_cache) || !aligned16(R_in))
+        return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
+    if (io_dtype != EGG_BF16 && io_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "io_dtype %d", (int)io_dtype);
+    if (y_dtype != EGG_BF16 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "y_dtype %d", (int)y_dtype);
+    if (io_dtype == EGG_F32 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "fp32 inputs need fp32 output");
+    if (act != EGG_ACT_NONE && act != EGG_ACT_GELU) return fail(c, EGG_EINVAL, "unknown activation");
+    const int kq = io_dtype == EGG_BF16 ? 8 : 4;
+    if (shape->d_in % kq) return fail(c, EGG_EUNSUPPORTED, "d_in must be a multiple of %d", kq);
+    if (shape->d_out % 4) return fail(c, EGG_EUNSUPPORTED, "d_out must be a multiple of 4");
+    if (!(sigma == sigma) || sigma < 0.0f) return fail(c, EGG_EINVAL, "sigma must be >= 0");
+    if (sigma == 0.0f && (A_cache || B_cache))
+        return fail(c, EGG_EINVAL, "sigma == 0 generates no factors: caches must be NULL");
+    const bool panel = c->cache_layout == EGG_CACHE_PANEL;
+    if (panel && A_cache) return fail(c, EGG_EINVAL, "the panel cache layout keeps B only: A_cache must be NULL");
+    const int64_t R = shape->member_count * (int64_t)shape->rows_per_member;
+    if (R > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "more than 2^31 rows in one call");
+    if (t_fixed) {
+        if (c->prof) return fail(c, EGG_EINVAL, "per-kernel timing creates events: switch it off for the no-allocation entry point");
+        if ((uint64_t)R * (uint64_t)shape->rank > t_capacity)
+            return fail(c, EGG_EUNSUPPORTED, "rows * rank = %lld exceeds the static scratch of %zu values", (long long)R * shape->rank,
+                        t_capacity);
+        // the one other scratch user of this path: factors materialised for S > 1 or rank > 1 go to the caller's cache
+        const bool regen = sigma == 0.0f || (shape->rank == 1 && shape->rows_per_member == 1 && !(shape->antithetic && A_cache));
+        if (!regen && !A_cache)
+            return fail(c, EGG_EINVAL, "more than one row per member or rank > 1 materialises A_i: pass A_cache (this entry point does not allocate)");
+    }
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return forward_linear(c, key, *shape, io_dtype, y_dtype, sigma, act, W, X, Y, A_cache, B_cache, R_in, t_fixed);
+}
+
 }  // namespace egg
 
 using namespace egg;
@@ -126,9 +199,10 @@ egg_status eggroll_destroy(eggroll_ctx* c)
     if (!c) return EGG_EINVAL;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut};
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut, &c->model, &c->model_g};
     for (auto* b : bufs)
         if (b->p) (void)hipFree(b->p);
+    for (auto& b : c->retired) (void)hipFree(b.p);
     for (auto& r : c->recs) {
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
@@ -151,6 +225,18 @@ const char* eggroll_strerror(egg_status s)
 }
 
 const char* eggroll_last_error(const eggroll_ctx* c) { return c ? c->err.c_str() : "no context"; }
+
+uint64_t eggroll_scratch_generation(const eggroll_ctx* c) { return c ? c->scratch_generation : 0; }
+
+egg_status eggroll_trim(eggroll_ctx* c)
+{
+    if (!c) return EGG_EINVAL;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, EGG_EHIP, "sync before trimming scratch");
+    for (auto& b : c->retired) (void)hipFree(b.p);
+    c->retired.clear();
+    return EGG_OK;
+}
 
 double eggroll_default_scale(int64_t population, double sigma, int rank)
 {
@@ -195,39 +281,14 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* c, egg_key key, const egg_shap
                                      egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
                                      void* Y, void* A_cache, void* B_cache)
 {
-    if (!c) return EGG_EINVAL;
-    egg_status s = validate_shape(c, shape, true, true);
-    if (s != EGG_OK) return s;
-    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
-    if (!W || !X || !Y) return fail(c, EGG_EINVAL, "W, X, Y must be non-NULL");
-    if (!aligned16(W) || !aligned16(X) || !aligned16(Y) || !aligned16(A_cache) || !aligned16(B_cache))
-        return fail(c, EGG_EINVAL, "pointers must be 16-byte aligned");
-    if (io_dtype != EGG_BF16 && io_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "io_dtype %d", (int)io_dtype);
-    if (y_dtype != EGG_BF16 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "y_dtype %d", (int)y_dtype);
-    if (io_dtype == EGG_F32 && y_dtype != EGG_F32) return fail(c, EGG_EUNSUPPORTED, "fp32 inputs need fp32 output");
-    if (act != EGG_ACT_NONE && act != EGG_ACT_GELU) return fail(c, EGG_EINVAL, "unknown activation");
-    const int kq = io_dtype == EGG_BF16 ? 8 : 4;
-    if (shape->d_in % kq) return fail(c, EGG_EUNSUPPORTED, "d_in must be a multiple of %d", kq);
-    if (shape->d_out % 4) return fail(c, EGG_EUNSUPPORTED, "d_out must be a multiple of 4");
-    if (!(sigma == sigma) || sigma < 0.0f) return fail(c, EGG_EINVAL, "sigma must be >= 0");
-    if (sigma == 0.0f && (A_cache || B_cache))
-        return fail(c, EGG_EINVAL, "sigma == 0 generates no factors: caches must be NULL");
-    const bool panel = c->cache_layout == EGG_CACHE_PANEL;
-    if (panel && A_cache) return fail(c, EGG_EINVAL, "the panel cache layout keeps B only: A_cache must be NULL");
-    const int64_t R = shape->member_count * (int64_t)shape->rows_per_member;
-    if (R > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "more than 2^31 rows in one call");
-    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    return checked_forward(c, key, shape, io_dtype, y_dtype, sigma, act, W, X, nullptr, false, Y, A_cache, B_cache, nullptr, 0);
+}
 
-    float* t = nullptr;
-    if (sigma != 0.0f) {
-        s = reserve(c, c->t_buf, (size_t)R * shape->rank * sizeof(float));
-        if (s != EGG_OK) return s;
-        t = (float*)c->t_buf.p;
-        s = launch_project(c, make_stream_key(key.seed, key.step, key.layer, 1), *shape, io_dtype, X, t, B_cache, panel);
-        if (s != EGG_OK) return s;
-    }
-    return launch_forward_gemm(c, make_stream_key(key.seed, key.step, key.layer, 0), *shape, io_dtype, y_dtype, sigma,
-                               act, W, X, Y, t, A_cache);
+egg_status eggroll_perturbed_forward_add(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                         egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                         const void* R_in, void* Y, void* A_cache, void* B_cache)
+{
+    return checked_forward(c, key, shape, io_dtype, y_dtype, sigma, act, W, X, R_in, true, Y, A_cache, B_cache, nullptr, 0);
 }
 
 egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound,

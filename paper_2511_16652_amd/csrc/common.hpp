@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <algorithm>
 #include <map>
 #include <string>
 #include <vector>
@@ -34,6 +35,12 @@ struct eggroll_ctx {
     Buf gru;          // integer GRU cell: factors of its four matrices, gate and matmul intermediates
     Buf zero_page;    // 256 zero bytes (K-tail loads of the GEMM core)
     Buf lut;          // integer log-likelihood: EXP2 table and the thresholds that invert LOG2
+    Buf model;        // multi-layer drivers: activations of one chunk of members
+    Buf model_g;      // multi-layer updates: fp32 G of the matrix being updated
+    // buffers that a later, larger call outgrew: kept until eggroll_trim / eggroll_destroy, because work already
+    // enqueued -- or a HIP graph captured earlier -- may still hold their addresses
+    std::vector<Buf> retired;
+    uint64_t scratch_generation = 0;  // bumped whenever a scratch buffer is replaced
 
     // profiling
     bool prof = false;
@@ -71,10 +78,32 @@ egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& 
                           float* t, void* B_cache, bool panel);
 egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
                                float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
-                               void* A_cache);
+                               void* A_cache, const void* resid = nullptr);
 egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                          egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
                          egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache, bool b_panel);
+egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
+                          egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
+                          float* t_fixed = nullptr);
+egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype, egg_dtype y_dtype,
+                           float sigma, egg_act act, const void* W, const void* X, const void* R_in, bool need_r, void* Y,
+                           void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity);
+// unperturbed glue of the decoder workload
+egg_status launch_embed_rows(eggroll_ctx* c, int64_t rows, int d, int vocab, const void* emb, const int32_t* tokens, void* X);
+egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y);
+egg_status launch_attention(eggroll_ctx* c, int64_t members, int S, int heads, int head_dim, const void* Q, const void* K,
+                            const void* V, void* O);
+egg_status launch_token_loglik(eggroll_ctx* c, int64_t members, int S, int vocab, const void* logits, const int32_t* tokens, float* out);
+// multi-layer drivers
+egg_status launch_mlp_stack_forward(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int d_ff, float sigma,
+                                    const void* W1, const void* W2, const void* X, void* Y, int64_t chunk_members);
+egg_status launch_mlp_stack_update(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int d_ff, const float* fitness,
+                                   float scale, float lr, void* W1, void* W2);
+egg_status launch_decoder_forward(eggroll_ctx* c, egg_key key, const egg_shape& s, const egg_decoder_cfg& cfg,
+                                  const egg_decoder_weights& w, float sigma, const int32_t* tokens, void* logits, float* loglik,
+                                  int64_t chunk_members);
+egg_status launch_decoder_update(eggroll_ctx* c, egg_key key, const egg_shape& s, const egg_decoder_cfg& cfg, const float* fitness,
+                                 float scale, float lr, const egg_decoder_weights& w);
 egg_status launch_forward_i8(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                              int int_bound, int corr_shift, int out_shift, int steps, const int8_t* W,
                              const int8_t* H_in, int8_t* H_out);

@@ -1,0 +1,320 @@
+// Unperturbed glue of the decoder workload: token embedding gather, RMS normalisation, causal softmax
+// attention over a member's own tokens, and the per-token log-likelihood of the next token.  The paper
+// perturbs the matrix parameters of a model (Sec. 4.1; Alg. 1); everything here is identical in the
+// perturbed and the unperturbed pass and exists so that the perturbed linear layers can be driven as a
+// whole model.  All tensors are bf16 row-major [rows][d], rows member-major.
+#include "common.hpp"
+#include "gemm_core.hpp"
+
+namespace egg {
+
+// ---- embedding gather: X[row] = emb[token[row]] ----------------------------------------------------
+__global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restrict__ tokens, const uint4* __restrict__ emb,
+                                                         uint4* __restrict__ X, int64_t rows, int chunks, int vocab)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int tok = min(max(tokens[row], 0), vocab - 1);  // ids are validated by the caller; never read outside the table
+    const uint4* src = emb + (int64_t)tok * chunks;
+    uint4* dst = X + row * chunks;
+    for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+}
+
+// ---- RMS normalisation: Y[row][k] = X[row][k] * gain[k] / sqrt(mean_k X[row][k]^2 + eps) -------------
+// One wave per row; the second pass over the row re-reads it from cache.  HBM-bound: 2 d bytes in, 2 d out.
+__device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8])
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = bf16_lo(w[e]);
+        x[2 * e + 1] = bf16_hi(w[e]);
+    }
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ X, const uint4* __restrict__ gain,
+                                                      uint4* __restrict__ Y, int64_t rows, int chunks, float inv_d, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const uint4* xr = X + row * chunks;
+    float ss = 0.f;
+    for (int c = lane; c < chunks; c += 64) {
+        float x[8];
+        unpack8(xr[c], x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    const float r = 1.0f / sqrtf(ss * inv_d + eps);
+    uint4* yr = Y + row * chunks;
+    for (int c = lane; c < chunks; c += 64) {
+        float x[8], g[8];
+        unpack8(xr[c], x);
+        unpack8(gain[c], g);
+        uint4 o;
+        o.x = pack_bf16x2(x[0] * r * g[0], x[1] * r * g[1]);
+        o.y = pack_bf16x2(x[2] * r * g[2], x[3] * r * g[3]);
+        o.z = pack_bf16x2(x[4] * r * g[4], x[5] * r * g[5]);
+        o.w = pack_bf16x2(x[6] * r * g[6], x[7] * r * g[7]);
+        yr[c] = o;
+    }
+}
+
+// ---- causal softmax attention ------------------------------------------------------------------------
+// One workgroup (8 waves) per (member, head): K [S][HD] and V transposed [HD][S] of the head sit in LDS, wave w
+// owns 32 query rows and walks the key blocks 0 .. its own (the causal triangle).  The two waves of a SIMD get
+// query blocks b and 7 - b, so every SIMD does the same number of key blocks.
+//   scores^T = K Q^T      as MFMA C[m = key][n = query]: a lane holds 16 scores of ONE query, so the row
+//                         maximum and sum are in-lane reductions plus one exchange between the lane halves;
+//   O^T     += V^T P^T    as MFMA C[m = hd][n = query]: the P operand is the lane's own 16 probabilities
+//                         (bf16), the V^T operand reads the keys in the same order from LDS.
+// Online softmax in base 2 (running maximum and sum per query, fp32).  S <= 256.
+template <int HD>
+struct AttnCfg {
+    static constexpr int SMAX = 256;
+    static constexpr int KP = HD * 2 + 16;    // K row pitch in bytes (68 dwords at HD = 128: 16 lanes cover all banks)
+    static constexpr int VP = SMAX * 2 + 8;   // V^T row pitch in bytes (130 dwords: 32 lanes x 8 bytes cover all banks)
+    static constexpr int LDS = SMAX * KP + HD * VP;
+};
+
+template <int HD>
+__global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                                                        const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int S,
+                                                        int heads, int64_t ld, float scale_log2)
+{
+    typedef AttnCfg<HD> C;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* sK = smem;
+    char* sV = smem + C::SMAX * C::KP;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t member = blockIdx.x / heads;
+    const int head = (int)(blockIdx.x - member * heads);
+    const int64_t base = member * S * ld + (int64_t)head * HD;
+    const uint16_t *Qg = Q + base, *Kg = K + base, *Vg = V + base;
+    const int SP = (S + 31) & ~31;
+    constexpr int CPR = HD / 8;  // 16-byte chunks per row
+
+    for (int idx = tid; idx < SP * CPR; idx += 512) {
+        const int row = idx / CPR, ch = idx - row * CPR;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < S) v = *(const uint4*)(Kg + (int64_t)row * ld + ch * 8);
+        *(uint4*)(sK + row * C::KP + ch * 16) = v;
+    }
+    // V: a wave's 64 lanes take 64 consecutive keys of one 8-column chunk, so each 2-byte transposed store
+    // instruction writes 128 contiguous bytes of one V^T row
+    for (int it = wave; it < (SP / 64 + (SP % 64 ? 1 : 0)) * CPR; it += 8) {
+        const int kg = it / CPR, ch = it - kg * CPR;
+        const int key = kg * 64 + lane;
+        if (key < SP) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (key < S) v = *(const uint4*)(Vg + (int64_t)key * ld + ch * 8);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                *(uint16_t*)(sV + (ch * 8 + 2 * e) * C::VP + key * 2) = (uint16_t)(w[e] & 0xFFFFu);
+                *(uint16_t*)(sV + (ch * 8 + 2 * e + 1) * C::VP + key * 2) = (uint16_t)(w[e] >> 16);
+            }
+        }
+    }
+    __syncthreads();
+
+    const int nqb = SP / 32;
+    const int qb = wave < 4 ? wave : 11 - wave;
+    if (qb >= nqb) return;  // no barrier follows
+    const int n = lane & 31, h = lane >> 5;
+    const int qrow = qb * 32 + n;
+    u32x4 qf[HD / 16];
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) {
+        qf[ks] = u32x4{0u, 0u, 0u, 0u};
+        if (qrow < S) qf[ks] = *(const u32x4*)(Qg + (int64_t)qrow * ld + (2 * ks + h) * 8);
+    }
+    f32x16 oacc[HD / 32];
+#pragma unroll
+    for (int mb = 0; mb < HD / 32; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[mb][e] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
+
+    for (int kb = 0; kb <= qb; ++kb) {
+        f32x16 s;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[e] = 0.f;
+        const char* kp = sK + (kb * 32 + n) * C::KP + h * 16;
+#pragma unroll
+        for (int ks = 0; ks < HD / 16; ++ks) {
+            const u32x4 a = *(const u32x4*)(kp + ks * 32);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
+        }
+        float p[16];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int key = kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+            p[i] = (kb == qb && key > qrow) ? -INFINITY : s[i] * scale_log2;
+            mx = fmaxf(mx, p[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mnew = fmaxf(mrun, mx);  // finite: key 0 of the member is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+        float lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(p[i] - mnew);
+            lsum += p[i];
+        }
+        lrun = lrun * alpha + lsum;
+        mrun = mnew;
+#pragma unroll
+        for (int mb = 0; mb < HD / 32; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[mb][e] *= alpha;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const u32x4 pb = {pack_bf16x2(p[8 * t], p[8 * t + 1]), pack_bf16x2(p[8 * t + 2], p[8 * t + 3]),
+                              pack_bf16x2(p[8 * t + 4], p[8 * t + 5]), pack_bf16x2(p[8 * t + 6], p[8 * t + 7])};
+#pragma unroll
+            for (int mb = 0; mb < HD / 32; ++mb) {
+                // K-slots j < 4: keys kb*32 + 16t + 4h + j;  j >= 4: the same + 8 -- the order of the lane's p values
+                const char* vp = sV + (mb * 32 + n) * C::VP + (kb * 32 + 16 * t + 4 * h) * 2;
+                const uint2 lo = *(const uint2*)vp, hi = *(const uint2*)(vp + 16);
+                const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
+                oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pb), oacc[mb], 0, 0, 0);
+            }
+        }
+    }
+    const float inv = 1.0f / (lrun + __shfl_xor(lrun, 32, 64));
+    if (qrow < S) {
+        uint16_t* orow = O + base + (int64_t)qrow * ld;
+#pragma unroll
+        for (int mb = 0; mb < HD / 32; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint2 o = make_uint2(pack_bf16x2(oacc[mb][4 * q] * inv, oacc[mb][4 * q + 1] * inv),
+                                           pack_bf16x2(oacc[mb][4 * q + 2] * inv, oacc[mb][4 * q + 3] * inv));
+                *(uint2*)(orow + mb * 32 + 8 * q + 4 * h) = o;
+            }
+    }
+}
+
+// ---- next-token log-likelihood: out[row] = logits[row][token[row+1]] - log sum_j exp(logits[row][j]) -----
+// One workgroup per row; online maximum / sum in base 2 per thread, combined through LDS.  The member's last
+// token has no successor: 0.  HBM-bound: 2 V bytes per row.
+__global__ __launch_bounds__(256) void token_loglik_kernel(const uint4* __restrict__ logits, const int32_t* __restrict__ tokens,
+                                                           float* __restrict__ out, int S, int vocab)
+{
+    __shared__ float red_m[4], red_l[4];
+    const int64_t row = blockIdx.x;
+    const int tid = threadIdx.x;
+    if ((int)(row % S) == S - 1) {
+        if (tid == 0) out[row] = 0.f;
+        return;
+    }
+    const int chunks = vocab >> 3;
+    const uint4* lr = logits + row * chunks;
+    constexpr float LOG2E = 1.4426950408889634f;
+    float m = -INFINITY, l = 0.f;
+    for (int c = tid; c < chunks; c += 256) {
+        float x[8];
+        unpack8(lr[c], x);
+        float mx = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, x[e]);
+        const float mnew = fmaxf(m, mx * LOG2E);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += exp2f(x[e] * LOG2E - mnew);
+        l = l * exp2f(m - mnew) + s;
+        m = mnew;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float om = __shfl_xor(m, off, 64), ol = __shfl_xor(l, off, 64);
+        const float mn = fmaxf(m, om);
+        l = (m == -INFINITY ? 0.f : l * exp2f(m - mn)) + (om == -INFINITY ? 0.f : ol * exp2f(om - mn));
+        m = mn;
+    }
+    if ((tid & 63) == 0) {
+        red_m[tid >> 6] = m;
+        red_l[tid >> 6] = l;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float mm = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+        float ll = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (red_m[w] != -INFINITY) ll += red_l[w] * exp2f(red_m[w] - mm);
+        const int tgt = min(max(tokens[row + 1], 0), vocab - 1);
+        const float xt = bf16_bits_to_f32(((const uint16_t*)lr)[tgt]);
+        out[row] = xt - (mm + log2f(ll)) * 0.6931471805599453f;
+    }
+}
+
+// ---- launchers -------------------------------------------------------------------------------------------
+egg_status launch_embed_rows(eggroll_ctx* c, int64_t rows, int d, int vocab, const void* emb, const int32_t* tokens, void* X)
+{
+    if (rows == 0) return EGG_OK;
+    KernelScope ks(c, "embed_rows");
+    hipLaunchKernelGGL(embed_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, tokens, (const uint4*)emb,
+                       (uint4*)X, rows, d / 8, vocab);
+    return check_hip(c, hipGetLastError(), "embed_rows launch");
+}
+
+egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y)
+{
+    if (rows == 0) return EGG_OK;
+    KernelScope ks(c, "rmsnorm");
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, (const uint4*)X,
+                       (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps);
+    return check_hip(c, hipGetLastError(), "rmsnorm launch");
+}
+
+template <int HD>
+static egg_status launch_attention_t(eggroll_ctx* c, int64_t members, int S, int heads, const void* Q, const void* K,
+                                     const void* V, void* O)
+{
+    auto kern = attention_kernel<HD>;
+    static bool attr_set = false;  // once per process and instantiation: the attribute belongs to the function
+    if (!attr_set) {
+        egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, AttnCfg<HD>::LDS), "attention smem attr");
+        if (st != EGG_OK) return st;
+        attr_set = true;
+    }
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+    KernelScope ks(c, "attention");
+    hipLaunchKernelGGL(kern, dim3((unsigned)(members * heads)), dim3(512), AttnCfg<HD>::LDS, c->stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)O, S, heads, (int64_t)heads * HD, scale_log2);
+    return check_hip(c, hipGetLastError(), "attention launch");
+}
+
+egg_status launch_attention(eggroll_ctx* c, int64_t members, int S, int heads, int head_dim, const void* Q, const void* K,
+                            const void* V, void* O)
+{
+    if (members == 0) return EGG_OK;
+    if (S < 1 || S > 256) return fail(c, EGG_EUNSUPPORTED, "attention: rows_per_member %d outside [1, 256]", S);
+    if (members * heads > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "attention: too many (member, head) pairs in one call");
+    switch (head_dim) {
+        case 32: return launch_attention_t<32>(c, members, S, heads, Q, K, V, O);
+        case 64: return launch_attention_t<64>(c, members, S, heads, Q, K, V, O);
+        case 128: return launch_attention_t<128>(c, members, S, heads, Q, K, V, O);
+    }
+    return fail(c, EGG_EUNSUPPORTED, "attention: head dimension %d not in {32, 64, 128}", head_dim);
+}
+
+egg_status launch_token_loglik(eggroll_ctx* c, int64_t members, int S, int vocab, const void* logits, const int32_t* tokens, float* out)
+{
+    const int64_t rows = members * S;
+    if (rows == 0) return EGG_OK;
+    if (rows > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "token_loglik: too many rows in one call");
+    KernelScope ks(c, "token_loglik");
+    hipLaunchKernelGGL(token_loglik_kernel, dim3((unsigned)rows), dim3(256), 0, c->stream, (const uint4*)logits, tokens, out, S, vocab);
+    return check_hip(c, hipGetLastError(), "token_loglik launch");
+}
+
+}  // namespace egg

@@ -30,6 +30,7 @@ struct FwdEpi {
         int stage_a;    // !REGEN: the tile's slice of A fits the LDS tail and is staged there
         int mma_corr;   // !REGEN, bf16, S % 32 == 0: the correction is folded in by one extra MFMA per block
         int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
+        const void* resid;  // optional [R][d_out] of the output dtype, added after the activation (residual stream)
     };
     static constexpr int A_STAGE_BYTES = 48 * 1024;
     static constexpr bool REGEN_MODE = REGEN;
@@ -255,6 +256,18 @@ struct FwdEpi {
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] = 0.5f * y[e] * (1.0f + erff(y[e] * 0.70710678118654752f));
         }
+        if (a.resid && live) {
+            // each output element is read here and written (by flush or below) exactly once, so Y may be the
+            // residual buffer itself
+            if (a.y_bf16) {
+                const uint2 rv = *(const uint2*)((const uint16_t*)a.resid + (int64_t)n * a.d_out + m);
+                y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x);
+                y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+            } else {
+                const float4 rv = *(const float4*)((const float*)a.resid + (int64_t)n * a.d_out + m);
+                y[0] += rv.x; y[1] += rv.y; y[2] += rv.z; y[3] += rv.w;
+            }
+        }
         if (a.y_bf16) {
             sty.put(a.wtm_pitch, ml, pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));  // written out by flush
         } else if (live) {
@@ -306,7 +319,8 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
 
 template <bool BF16, int RANK, bool REGEN>
 static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype yd, float sigma,
-                                   egg_act act, const void* W, const void* X, void* Y, const float* t, void* A_buf)
+                                   egg_act act, const void* W, const void* X, void* Y, const float* t, void* A_buf,
+                                   const void* resid)
 {
     typedef FwdEpi<BF16, RANK, REGEN> Epi;
     const int esz = BF16 ? 2 : 4;
@@ -318,7 +332,7 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
     typename Epi::Args ea{ka, (uint32_t)(s.member_begin / anti), s.rows_per_member * anti, s.d_out, sigma / sqrtf((float)s.rank),
-                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0, (REGEN && s.antithetic) ? 1 : 0};
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0, (REGEN && s.antithetic) ? 1 : 0, resid};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
@@ -338,14 +352,14 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
 
 egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
                                float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
-                               void* A_cache)
+                               void* A_cache, const void* resid)
 {
     const bool bf = io == EGG_BF16;
     // rank 1 with one row per member (or the unperturbed pass): regenerate in the epilogue
     // (with antithetic pairs a kept cache has one entry per pair, not per row: that goes the materialised way)
     if (sigma == 0.f || (s.rank == 1 && s.rows_per_member == 1 && !(s.antithetic && A_cache))) {
-        return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache)
-                  : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache);
+        return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid)
+                  : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid);
     }
     // otherwise materialise A once (into the caller's cache if there is one) and read it back
     void* A_buf = A_cache;
@@ -359,7 +373,7 @@ egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_sh
     egg_status st = launch_noise(c, ka, (uint32_t)(s.member_begin / anti), s.member_count / anti, (int64_t)s.d_out * s.rank, io,
                                  EGG_NORMAL, 0, A_buf);
     if (st != EGG_OK) return st;
-#define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf)
+#define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf, resid)
     if (bf) {
         switch (s.rank) {
             case 1: EGG_FWD(true, 1);

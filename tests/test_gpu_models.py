@@ -1,0 +1,331 @@
+"""GPU parity of the multi-layer float workloads (MLP stack, decoder) and of their glue kernels against the
+CPU oracle (oracle/models.py, oracle.forward, oracle.update), all through the C ABI.
+
+Per-layer checks use teacher forcing: the oracle's step is fed the GPU's own input of that step, so each
+kernel is held to the single-kernel tolerance (bf16: 1e-2 of |ref| + rms(ref)); one end-to-end number per
+model is compared at a looser bound that the depth of the model explains."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import assert_close, to_device, to_numpy
+from oracle import models
+from paper_2511_16652_amd import binding as eb
+from paper_2511_16652_amd import inputs
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-5
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    c = eb.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def bf16_dev(a):
+    return to_device(np.asarray(a, dtype=np.float32), "bf16")
+
+
+def rb(a):
+    return models.round_bf16(a)
+
+
+@pytest.mark.parametrize("N,S,d_out,d_in,rank,act", [(40, 1, 96, 64, 1, 0), (6, 32, 160, 128, 4, 1), (9, 5, 72, 40, 2, 0)])
+def test_forward_with_residual(ctx, N, S, d_out, d_in, rank, act):
+    import torch
+    wl = inputs.make_linear("t", "bf16", d_out, d_in, N, S, rank, 0.05, 31, layer=3)
+    R = inputs.round_to_bf16(np.random.default_rng(5).standard_normal((N * S, d_out)).astype(np.float32))
+    W, X, Rd = bf16_dev(wl.W), bf16_dev(wl.X), bf16_dev(R)
+    Y = torch.empty_like(Rd)
+    key, shape = eb.make_key(0, 0, 3), eb.make_shape(7, N, S, d_out, d_in, rank)
+    ctx.eggroll_perturbed_forward_add(key, shape, 0.05, act, W, X, Rd, Y)
+    torch.cuda.synchronize()
+    ref = R.astype(np.float64) + oracle.forward(0, 0, 3, 7, N, S, d_out, d_in, rank, oracle.NOISE_BF16, 0.05, act, wl.W, wl.X)
+    assert_close(to_numpy(Y), ref, 1e-2, "forward + residual")
+    # in place: Y is the residual buffer itself; same bits
+    ctx.eggroll_perturbed_forward_add(key, shape, 0.05, act, W, X, Rd, Rd)
+    torch.cuda.synchronize()
+    assert torch.equal(Rd.view(torch.int16), Y.view(torch.int16))
+    # the plain entry point is the same layer without the residual term
+    Y0 = torch.empty_like(Y)
+    ctx.eggroll_perturbed_forward(key, shape, 0.05, act, W, X, Y0)
+    torch.cuda.synchronize()
+    assert_close(to_numpy(Y0), ref - R, 1e-2, "forward")
+
+
+def test_forward_with_residual_fp32(ctx):
+    import torch
+    N, d = 12, 64
+    wl = inputs.make_linear("t", "f32", d, d, N, 1, 1, 0.01, 32)
+    R = np.random.default_rng(6).standard_normal((N, d)).astype(np.float32)
+    W, X, Rd = to_device(wl.W, "f32"), to_device(wl.X, "f32"), to_device(R, "f32")
+    Y = torch.empty_like(Rd)
+    ctx.eggroll_perturbed_forward_add(eb.make_key(0, 0, 0), eb.make_shape(0, N, 1, d, d, 1), 0.01, 0, W, X, Rd, Y)
+    torch.cuda.synchronize()
+    ref = R.astype(np.float64) + oracle.forward(0, 0, 0, 0, N, 1, d, d, 1, oracle.NOISE_F32, 0.01, 0, wl.W, wl.X)
+    assert_close(Y.cpu().numpy(), ref, 1e-5, "fp32 forward + residual")
+
+
+@pytest.mark.parametrize("rows,d", [(1, 8), (37, 72), (260, 2048), (5, 4096)])
+def test_rmsnorm(ctx, rows, d):
+    import torch
+    rng = np.random.default_rng(rows + d)
+    x = inputs.round_to_bf16((rng.standard_normal((rows, d)) * rng.uniform(0.01, 30, (rows, 1))).astype(np.float32))
+    x[0] = 0.0                                 # a zero row stays zero
+    g = inputs.round_to_bf16((1.0 + 0.3 * rng.standard_normal(d)).astype(np.float32))
+    X, G = bf16_dev(x), bf16_dev(g)
+    Y = torch.empty_like(X)
+    ctx.eggroll_rmsnorm_bf16(rows, d, EPS, G, X, Y)
+    torch.cuda.synchronize()
+    ref = models.rmsnorm(x, g, EPS)
+    got = to_numpy(Y)
+    assert not got[0].any()
+    # bf16 output: half an ulp relative per entry (2^-9) plus fp32 arithmetic
+    assert (np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30).all()
+    ctx.eggroll_rmsnorm_bf16(rows, d, EPS, G, X, X)   # in place
+    torch.cuda.synchronize()
+    assert torch.equal(X.view(torch.int16), Y.view(torch.int16))
+
+
+def test_embed_rows(ctx):
+    import torch
+    V, d, rows = 300, 136, 1000
+    emb = inputs.round_to_bf16(np.random.default_rng(1).standard_normal((V, d)).astype(np.float32))
+    tok = np.random.default_rng(2).integers(0, V, rows).astype(np.int32)
+    tok[:2] = (0, V - 1)
+    X = torch.empty((rows, d), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_embed_rows_bf16(rows, d, V, bf16_dev(emb), torch.from_numpy(tok).cuda(), X)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_numpy(X), emb[tok])
+
+
+@pytest.mark.parametrize("members,S,heads,hd", [(3, 1, 2, 32), (2, 5, 3, 64), (2, 32, 2, 128), (3, 100, 2, 128),
+                                               (2, 256, 2, 128), (1, 255, 1, 64), (2, 64, 4, 32)])
+def test_causal_attention(ctx, members, S, heads, hd):
+    import torch
+    d = heads * hd
+    rng = np.random.default_rng(S * 7 + hd)
+    q, k, v = (inputs.round_to_bf16(rng.standard_normal((members * S, d)).astype(np.float32)) for _ in range(3))
+    q *= 1.5                                   # sharper softmax than unit-variance scores
+    q = inputs.round_to_bf16(q)
+    Q, K, V = bf16_dev(q), bf16_dev(k), bf16_dev(v)
+    O = torch.full((members * S, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_causal_attention_bf16(members, S, heads, hd, Q, K, V, O)
+    torch.cuda.synchronize()
+    got = to_numpy(O)
+    ref = np.concatenate([models.causal_attention(q[m * S:(m + 1) * S], k[m * S:(m + 1) * S], v[m * S:(m + 1) * S], heads)
+                          for m in range(members)])
+    assert_close(got, ref, 1e-2, "attention S=%d hd=%d" % (S, hd))
+    # the first token of every member attends to itself only: exactly its own v
+    assert np.array_equal(got[::S], v[::S])
+    # causality on the device, bit for bit: changing the last token's k, v, q leaves all earlier outputs as they were
+    if S > 1:
+        k2, v2, q2 = k.copy(), v.copy(), q.copy()
+        for a in (k2, v2, q2):
+            a[S - 1::S] = -a[S - 1::S] + 1.0
+        O2 = torch.empty_like(O)
+        ctx.eggroll_causal_attention_bf16(members, S, heads, hd, bf16_dev(q2), bf16_dev(k2), bf16_dev(v2), O2)
+        torch.cuda.synchronize()
+        keep = np.ones(members * S, bool)
+        keep[S - 1::S] = False
+        assert np.array_equal(to_numpy(O2)[keep], got[keep])
+
+
+@pytest.mark.parametrize("members,S,V", [(3, 7, 40), (2, 1, 64), (5, 16, 1000), (2, 3, 32000)])
+def test_token_loglik(ctx, members, S, V):
+    import torch
+    rng = np.random.default_rng(V + S)
+    logits = inputs.round_to_bf16((4.0 * rng.standard_normal((members * S, V))).astype(np.float32))
+    tok = rng.integers(0, V, (members, S)).astype(np.int32)
+    out = torch.full((members * S,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.eggroll_token_loglik_bf16(members, S, V, bf16_dev(logits), torch.from_numpy(tok).cuda(), out)
+    torch.cuda.synchronize()
+    ref = np.concatenate([models.token_loglik(logits[m * S:(m + 1) * S], tok[m]) for m in range(members)])
+    got = out.cpu().numpy()
+    assert (got[S - 1::S] == 0).all()
+    assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max() + 1e-5
+
+
+# ---------------------------------------------------------------------------------------------------------
+def _mlp_inputs(d, ff, L, N, S, seed):
+    P = inputs.mlp_stack(d, ff, L, seed)
+    X = np.concatenate([inputs.member_rows(seed + 1, m, S, d) for m in range(N)])
+    return P, X
+
+
+@pytest.mark.parametrize("d,ff,L,N,S,rank,chunk", [(128, 256, 3, 24, 32, 4, 0), (64, 136, 2, 13, 5, 2, 4), (256, 512, 2, 300, 1, 1, 128)])
+def test_mlp_stack_layers_teacher_forced_and_end_to_end(ctx, d, ff, L, N, S, rank, chunk):
+    import torch
+    sigma, base, mb = 0.02, 40, 3
+    P, X = _mlp_inputs(d, ff, L, N, S, 50 + d)
+    W1, W2, Xd = bf16_dev(P["W1"]), bf16_dev(P["W2"]), bf16_dev(X)
+    # layer by layer through the single-layer entry point, each against the oracle fed the GPU's own input
+    h = Xd
+    for l in range(L):
+        u = torch.empty((N * S, ff), dtype=torch.bfloat16, device="cuda")
+        ctx.eggroll_perturbed_forward(eb.make_key(0, 0, base + 2 * l), eb.make_shape(mb, N, S, ff, d, rank), sigma, eb.EGG_ACT_GELU, W1[l], h, u)
+        ref = oracle.forward(0, 0, base + 2 * l, mb, N, S, ff, d, rank, oracle.NOISE_BF16, sigma, oracle.ACT_GELU, P["W1"][l], to_numpy(h))
+        assert_close(to_numpy(u), ref, 1e-2, "W1 of layer %d" % l)
+        h2 = torch.empty((N * S, d), dtype=torch.bfloat16, device="cuda")
+        ctx.eggroll_perturbed_forward(eb.make_key(0, 0, base + 2 * l + 1), eb.make_shape(mb, N, S, d, ff, rank), sigma, eb.EGG_ACT_NONE, W2[l], u, h2)
+        ref = oracle.forward(0, 0, base + 2 * l + 1, mb, N, S, d, ff, rank, oracle.NOISE_BF16, sigma, 0, P["W2"][l], to_numpy(u))
+        assert_close(to_numpy(h2), ref, 1e-2, "W2 of layer %d" % l)
+        h = h2
+    # the driver is that chain: same bits, whatever the chunking
+    Y = torch.empty_like(Xd)
+    ctx.eggroll_mlp_stack_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), L, ff, sigma, W1, W2, Xd, Y, chunk)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.int16), h.view(torch.int16))
+    # end to end against the oracle's own chain (no teacher forcing)
+    Yo = models.mlp_stack_forward(0, 0, base, range(mb, mb + N), S, rank, sigma, P["W1"], P["W2"], X.reshape(N, S, d))
+    fro = assert_close(to_numpy(Y), Yo.reshape(N * S, d), 2e-2, "MLP stack end to end")
+    assert fro < 1e-2
+    # sigma = 0: the unperturbed stack (every member the same function)
+    Y0 = torch.empty_like(Xd)
+    ctx.eggroll_mlp_stack_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), L, ff, 0.0, W1, W2, Xd, Y0, chunk)
+    torch.cuda.synchronize()
+    Yo0 = models.mlp_stack_forward(0, 0, base, range(N), S, rank, 0.0, P["W1"], P["W2"], X.reshape(N, S, d))
+    assert_close(to_numpy(Y0), Yo0.reshape(N * S, d), 2e-2, "MLP stack sigma = 0")
+
+
+def test_mlp_stack_update(ctx):
+    import torch
+    d, ff, L, N, rank, base, sigma, lr = 64, 128, 2, 96, 4, 11, 0.05, 0.5
+    P = inputs.mlp_stack(d, ff, L, 77)
+    f = inputs.centered(np.random.default_rng(3).standard_normal(N))
+    scale = eb.eggroll_default_scale(N, sigma, rank)
+    W1, W2 = bf16_dev(P["W1"]), bf16_dev(P["W2"])
+    ctx.eggroll_mlp_stack_update(eb.make_key(0, 2, base), eb.make_shape(0, N, 1, d, d, rank), L, ff,
+                                 torch.from_numpy(f.astype(np.float32)).cuda(), scale, lr, W1, W2)
+    torch.cuda.synchronize()
+    for l in range(L):
+        for j, (Wd, W0, do, di) in enumerate(((W1, P["W1"], ff, d), (W2, P["W2"], d, ff))):
+            G = oracle.update(0, 2, base + 2 * l + j, 0, N, do, di, rank, oracle.NOISE_BF16, f.astype(np.float32).astype(np.float64), scale)
+            want = W0[l].astype(np.float64) + lr * G
+            got = to_numpy(Wd[l]).astype(np.float64)
+            assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-2 * lr * np.sqrt(np.mean(G ** 2))).all(), (l, j)
+            assert not np.array_equal(got, W0[l])
+
+
+# ---------------------------------------------------------------------------------------------------------
+def _decoder_inputs(V, d, ff, L, N, S, seed):
+    P = inputs.decoder_params(V, d, ff, L, seed, norm_jitter=0.2)
+    tok = inputs.decoder_tokens(N, S, V, seed + 1)
+    return P, tok
+
+
+@pytest.mark.parametrize("V,d,heads,ff,L,N,S,chunk", [(512, 128, 2, 256, 2, 6, 40, 0), (64, 64, 2, 136, 1, 5, 32, 2)])
+def test_decoder_layers_teacher_forced_and_end_to_end(ctx, V, d, heads, ff, L, N, S, chunk):
+    import torch
+    sigma, base, mb, rank = 0.02, 100, 4, 1
+    hd = d // heads
+    P, tok = _decoder_inputs(V, d, ff, L, N, S, 60 + d)
+    Wd = {k: bf16_dev(v) for k, v in P.items()}
+    tokd = torch.from_numpy(tok).cuda()
+    R = N * S
+    new = lambda n: torch.empty((R, n), dtype=torch.bfloat16, device="cuda")  # noqa: E731
+    shape = lambda do, di: eb.make_shape(mb, N, S, do, di, rank)  # noqa: E731
+
+    def lin(layer, W, Wd_, inp, act=0, resid=None, what=""):
+        do, di = W.shape
+        out = new(do)
+        if resid is None:
+            ctx.eggroll_perturbed_forward(eb.make_key(0, 0, layer), shape(do, di), sigma, act, Wd_, inp, out)
+        else:
+            ctx.eggroll_perturbed_forward_add(eb.make_key(0, 0, layer), shape(do, di), sigma, act, Wd_, inp, resid, out)
+        ref = oracle.forward(0, 0, layer, mb, N, S, do, di, rank, oracle.NOISE_BF16, sigma, act, W, to_numpy(inp))
+        if resid is not None:
+            ref = ref + to_numpy(resid)
+        assert_close(to_numpy(out), ref, 1e-2, what)
+        return out
+
+    def norm(g, gd, inp, what):
+        out = new(d)
+        ctx.eggroll_rmsnorm_bf16(R, d, EPS, gd, inp, out)
+        ref = models.rmsnorm(to_numpy(inp), g, EPS)
+        assert (np.abs(to_numpy(out) - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-30).all(), what
+        return out
+
+    x = new(d)
+    ctx.eggroll_embed_rows_bf16(R, d, V, Wd["emb"], tokd, x)
+    assert np.array_equal(to_numpy(x), P["emb"][tok.reshape(-1)])
+    for l in range(L):
+        lid = base + 6 * l
+        h = norm(P["norm1"][l], Wd["norm1"][l], x, "norm1")
+        q = lin(lid + 0, P["wq"][l], Wd["wq"][l], h, what="q")
+        k = lin(lid + 1, P["wk"][l], Wd["wk"][l], h, what="k")
+        v = lin(lid + 2, P["wv"][l], Wd["wv"][l], h, what="v")
+        o = new(d)
+        ctx.eggroll_causal_attention_bf16(N, S, heads, hd, q, k, v, o)
+        qn, kn, vn = to_numpy(q), to_numpy(k), to_numpy(v)
+        ref = np.concatenate([models.causal_attention(qn[m * S:(m + 1) * S], kn[m * S:(m + 1) * S], vn[m * S:(m + 1) * S], heads) for m in range(N)])
+        assert_close(to_numpy(o), ref, 1e-2, "attention")
+        x = lin(lid + 3, P["wo"][l], Wd["wo"][l], o, resid=x, what="o-proj + residual")
+        h = norm(P["norm2"][l], Wd["norm2"][l], x, "norm2")
+        u = lin(lid + 4, P["w_up"][l], Wd["w_up"][l], h, act=eb.EGG_ACT_GELU, what="up + gelu")
+        x = lin(lid + 5, P["w_down"][l], Wd["w_down"][l], u, resid=x, what="down + residual")
+    h = norm(P["norm_f"], Wd["norm_f"], x, "final norm")
+    lg = lin(base + 6 * L, P["head"], Wd["head"], h, what="head")
+    ll = torch.empty(R, dtype=torch.float32, device="cuda")
+    ctx.eggroll_token_loglik_bf16(N, S, V, lg, tokd, ll)
+    lgn = to_numpy(lg)
+    ref = np.concatenate([models.token_loglik(lgn[m * S:(m + 1) * S], tok[m]) for m in range(N)])
+    assert np.abs(ll.cpu().numpy() - ref).max() <= 1e-4
+
+    # the driver is that chain, bit for bit, whatever the chunking; with and without a logits buffer
+    cfg = eb.make_decoder_cfg(L, d, heads, ff, V, EPS)
+    logits = new(V)
+    ll2 = torch.empty_like(ll)
+    ctx.eggroll_decoder_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, 0 + d, d, rank), cfg, Wd, sigma, tokd, logits, ll2, chunk)
+    torch.cuda.synchronize()
+    assert torch.equal(logits.view(torch.int16), lg.view(torch.int16)) and torch.equal(ll2, ll)
+    ll3 = torch.empty_like(ll)
+    ctx.eggroll_decoder_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), cfg, Wd, sigma, tokd, None, ll3, chunk)
+    torch.cuda.synchronize()
+    assert torch.equal(ll3, ll)
+
+    # end to end against the oracle's own chain
+    lo, llo = models.decoder_forward(0, 0, base, range(mb, mb + N), tok, P, heads, EPS, rank, sigma)
+    fro = assert_close(lgn, lo.reshape(R, V), 3e-2, "decoder logits end to end")
+    assert fro < 1.5e-2
+    assert np.abs(ll.cpu().numpy() - llo.reshape(-1)).max() < 0.05
+    # sigma = 0 run of the same pipeline: members with equal tokens agree bit for bit; against the unperturbed oracle
+    tok0 = np.repeat(tok[:1], N, axis=0)
+    l0 = new(V)
+    ctx.eggroll_decoder_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), cfg, Wd, 0.0, torch.from_numpy(tok0).cuda(), l0, None, chunk)
+    torch.cuda.synchronize()
+    l0n = to_numpy(l0).reshape(N, S, V)
+    assert all(np.array_equal(l0n[0], l0n[m]) for m in range(1, N))
+    lo0, _ = models.decoder_forward(0, 0, base, [0], tok[:1], P, heads, EPS, rank, 0.0)
+    assert_close(l0n[0], lo0[0], 3e-2, "decoder sigma = 0")
+
+
+def test_decoder_update(ctx):
+    import torch
+    V, d, heads, ff, L, N, rank, base, sigma, lr = 128, 64, 2, 136, 2, 80, 1, 9, 0.05, 0.3
+    P = inputs.decoder_params(V, d, ff, L, 88)
+    Wd = {k: bf16_dev(v) for k, v in P.items()}
+    f = inputs.centered(np.random.default_rng(4).standard_normal(N)).astype(np.float32)
+    scale = eb.eggroll_default_scale(N, sigma, rank)
+    cfg = eb.make_decoder_cfg(L, d, heads, ff, V, EPS)
+    ctx.eggroll_decoder_update(eb.make_key(0, 1, base), eb.make_shape(0, N, 1, d, d, rank), cfg, torch.from_numpy(f).cuda(), scale, lr, Wd)
+    torch.cuda.synchronize()
+
+    def check(name, l, layer):
+        W0 = P[name][l] if l is not None else P[name]
+        got = to_numpy(Wd[name][l] if l is not None else Wd[name]).astype(np.float64)
+        G = oracle.update(0, 1, layer, 0, N, W0.shape[0], W0.shape[1], rank, oracle.NOISE_BF16, f.astype(np.float64), scale)
+        want = W0.astype(np.float64) + lr * G
+        assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-2 * lr * np.sqrt(np.mean(G ** 2))).all(), (name, l)
+
+    for l in range(L):
+        for j, name in enumerate(("wq", "wk", "wv", "wo", "w_up", "w_down")):
+            check(name, l, base + 6 * l + j)
+    check("head", None, base + 6 * L)
+    # not perturbed, not updated
+    for name in ("emb", "norm1", "norm2", "norm_f"):
+        assert np.array_equal(to_numpy(Wd[name]), P[name])
