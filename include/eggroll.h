@@ -126,6 +126,20 @@ egg_status eggroll_perturbed_forward(eggroll_ctx* ctx, egg_key key, const egg_sh
                                      const void* W, const void* X, void* Y, void* A_cache, void* B_cache);
 
 /*
+ * (2b) eggroll_perturbed_forward for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as (2); the one
+ * scratch buffer of that path, the projections t[R][rank] (fp32), lives in a static device array of
+ * 2^20 values (4 MiB per GPU, held until the process ends) instead of the context's growable scratch, and the
+ * call performs no hipMalloc / hipFree.  Limits: member_count * rows_per_member * rank <= 2^20, else
+ * EGG_EUNSUPPORTED; with more than one row per member or rank > 1 the factors A_i are materialised, so A_cache
+ * must be given (EGG_EINVAL otherwise); per-kernel timing must be off.  Every call on one GPU, from any
+ * context, shares the array: calls that overlap in time on one GPU race; calls ordered on one stream do not.
+ */
+egg_status eggroll_perturbed_forward_noalloc(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                             egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                             void* Y, void* A_cache, void* B_cache);
+
+/*
  * (2a) The same layer inside a residual stream:  Y = R_in + act( X W_i^T )  with W_i as in (2), summed in
  * fp32 before the one rounding to y_dtype.  R_in: [R][d_out] of y_dtype; it may be Y itself (every element
  * is read once and then written once by the same wavefront).  All other arguments as in (2).

@@ -22,7 +22,7 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read",
-           "eggroll_scratch_generation", "eggroll_trim", "eggroll_perturbed_forward_add",
+           "eggroll_scratch_generation", "eggroll_trim", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
            "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_token_loglik_bf16",
            "eggroll_mlp_stack_forward", "eggroll_mlp_stack_update", "eggroll_decoder_forward", "eggroll_decoder_update"]
 
@@ -95,6 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_noise_gen.restype = i32
     lib.eggroll_perturbed_forward.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp]
     lib.eggroll_perturbed_forward.restype = i32
+    lib.eggroll_perturbed_forward_noalloc.argtypes = lib.eggroll_perturbed_forward.argtypes
+    lib.eggroll_perturbed_forward_noalloc.restype = i32
     lib.eggroll_perturbed_forward_i8.argtypes = [vp, EggKey, P(EggShape), i32, i32, i32, i32, vp, vp, vp]
     lib.eggroll_perturbed_forward_i8.restype = i32
     lib.eggroll_update.argtypes = [vp, EggKey, P(EggShape), i32, vp, f32, i32, vp, vp, i32, f32, vp, vp]
@@ -210,6 +212,11 @@ class Context:
 
     def eggroll_perturbed_forward(self, key, shape, sigma, act, W, X, Y, A_cache=None, B_cache=None):
         self._check(self._lib.eggroll_perturbed_forward(
+            self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
+            _ptr(W), _ptr(X), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
+
+    def eggroll_perturbed_forward_noalloc(self, key, shape, sigma, act, W, X, Y, A_cache=None, B_cache=None):
+        self._check(self._lib.eggroll_perturbed_forward_noalloc(
             self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
             _ptr(W), _ptr(X), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
 

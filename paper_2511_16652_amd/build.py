@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libeggroll.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-UNITS = ["api", "api_models", "k_decoder", "k_models", "k_noise", "k_project", "k_forward", "k_update", "k_int8", "k_update_i8", "k_gru_i8", "k_egg_model"]
+UNITS = ["api", "api_models", "api_noalloc", "k_decoder", "k_models", "k_noise", "k_project", "k_forward", "k_update", "k_int8", "k_update_i8", "k_gru_i8", "k_egg_model"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Wno-pass-failed", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # the epilogues are long bodies inside fully unrolled loops over a lane's accumulator blocks: past the
