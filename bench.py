@@ -8,8 +8,9 @@ in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload W] [--no-cpu-baseline]
 
-Workloads: cfg2 (default), cfg1, cfg3 (int8 recurrence + integer update), gru (integer GRU cell), egg (integer model forward),
-p0, p0_r2, p0_r4, p0_r8, mlp_up, mlp_down, ffn_up, attn_proj.
+Workloads: cfg5 (default: the 1B-scale decoder, forward over all 97 perturbed matrices + their updates), cfg4 (8-layer GELU MLP
+stack), cfg2, cfg1, cfg3 (int8 recurrence + integer update), gru (integer GRU cell), egg (integer model forward),
+p0, p0_r2, p0_r4, p0_r8, p0_r16, mlp_up, mlp_down, ffn_up, attn_proj, lm_head.
 """
 from __future__ import annotations
 
@@ -27,13 +28,20 @@ if ROOT not in sys.path:
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 3 for cfg4/cfg5, 200 otherwise)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: 1 for cfg4/cfg5, 50 otherwise)")
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--members", type=int, default=None, help="cfg4/cfg5: population override (for quick runs; the headline uses the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 64 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    return ap.parse_args()
+    a = ap.parse_args()
+    heavy = a.workload in ("cfg4", "cfg5")
+    if a.steps is None:
+        a.steps = 3 if heavy else 200
+    if a.warmup is None:
+        a.warmup = 1 if heavy else 50
+    return a
 
 
 def profiled_traffic(workload, markers):
@@ -90,6 +98,341 @@ def timed(fn, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+def timed_events(fn, steps, warmup):
+    """Per-iteration HIP events on the current stream (the stream the library was created on): seconds as
+    {"mean", "median", "min"}; the mean is over the same iterations."""
+    import statistics
+
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = [a.elapsed_time(b) * 1e-3 for a, b in ev]
+    return {"mean": sum(ts) / len(ts), "median": statistics.median(ts), "min": min(ts)}
+
+
+def measured_ceilings():
+    """Two ceilings measured on this machine beside the datasheet peaks: the vendor GEMM at 8192^3 bf16 and a 64 MiB
+    device-to-device copy."""
+    import torch
+    a = torch.randn((8192, 8192), device="cuda").to(torch.bfloat16)
+    b = torch.randn((8192, 8192), device="cuda").to(torch.bfloat16)
+    c = torch.empty_like(a)
+    prewarm(lambda: torch.matmul(a, b.t(), out=c), 0.3)
+    t = timed_events(lambda: torch.matmul(a, b.t(), out=c), 20, 3)
+    src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    tc = timed_events(lambda: dst.copy_(src), 50, 5)
+    return {"vendor_gemm_8192_bf16_TFLOPs": 2.0 * 8192 ** 3 / t["median"] / 1e12,
+            "copy_64MiB_GBs": 2.0 * (64 << 20) / tc["median"] / 1e9}
+
+
+def kernel_table(prof):
+    return {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms} for k, (n, ms) in prof.items()}
+
+
+def decoder_workload(args):
+    """Configuration 5: a 1B-scale pre-norm decoder (16 layers, d = 2048, 16 heads, ffn 8192, vocabulary 32000),
+    N = 8192 members x 256 uniform-random tokens, rank 1, sigma = 1e-3.  A step is the perturbed forward of the whole
+    population through all 97 perturbed matrices (ending in the per-token log-likelihood) plus the 97 updates."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+
+    from paper_2511_16652_amd import binding as eb
+    from paper_2511_16652_amd import inputs, roofline
+
+    L, d, heads, ff, V, S, rank, sigma, eps = 16, 2048, 16, 8192, 32000, 256, 1, 1e-3, 1e-5
+    N = args.members or 8192
+    R = N * S
+    P = inputs.decoder_params_device(V, d, ff, L, 1005)
+    tokens = inputs.decoder_tokens_device(N, S, V, 1105)
+    raw = torch.randn(N, generator=torch.Generator(device="cuda").manual_seed(1205), device="cuda")
+    fit = (raw - raw.mean()).float().contiguous()
+    ll = torch.empty(R, dtype=torch.float32, device="cuda")
+    ctx = eb.Context(0)
+    cfg = eb.make_decoder_cfg(L, d, heads, ff, V, eps)
+    key, shape = eb.make_key(0, 0, 0), eb.make_shape(0, N, S, d, d, rank)
+    scale, lr = eb.eggroll_default_scale(N, sigma, rank), 1e-5
+
+    def forward():
+        ctx.eggroll_decoder_forward(key, shape, cfg, P, sigma, tokens, None, ll, 0)
+
+    def unperturbed():
+        ctx.eggroll_decoder_forward(key, shape, cfg, P, 0.0, tokens, None, ll, 0)
+
+    def update():
+        ctx.eggroll_decoder_update(key, shape, cfg, fit, scale, lr, P)
+
+    def step():
+        forward()
+        update()
+
+    hd = d // heads
+    chunk = max(1, (1 << 18) // S)
+
+    def torch_pipeline():
+        """The unperturbed model on the vendor libraries (torch.matmul = hipBLASLt, SDPA, rms_norm), same chunking."""
+        for m0 in range(0, N, chunk):
+            n = min(chunk, N - m0)
+            tok = tokens[m0:m0 + n]
+            x = P["emb"][tok.reshape(-1).long()]
+            for l in range(L):
+                h = F.rms_norm(x, (d,), P["norm1"][l], eps)
+                q, k, v = (torch.matmul(h, P[w][l].t()).view(n, S, heads, hd).transpose(1, 2) for w in ("wq", "wk", "wv"))
+                o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(n * S, d)
+                x = x + torch.matmul(o, P["wo"][l].t())
+                h = F.rms_norm(x, (d,), P["norm2"][l], eps)
+                x = x + torch.matmul(F.gelu(torch.matmul(h, P["w_up"][l].t())), P["w_down"][l].t())
+            lg = torch.matmul(F.rms_norm(x, (d,), P["norm_f"], eps), P["head"].t())
+            lse = torch.logsumexp(lg.float(), dim=-1)
+            tgt = torch.roll(tok, -1, dims=1).reshape(-1, 1).long()
+            ll[m0 * S:(m0 + n) * S] = lg.gather(1, tgt).squeeze(1).float() - lse
+
+    def torch_gemms_only():
+        """Just the 97 plain GEMMs of one population forward on the vendor library (no glue): the shared-GEMM part
+        of the unperturbed pass."""
+        for m0 in range(0, N, chunk):
+            n = min(chunk, N - m0) * S
+            for l in range(L):
+                for w in ("wq", "wk", "wv", "wo"):
+                    torch.matmul(xs[:n], P[w][l].t(), out=ys[:n])
+                torch.matmul(xs[:n], P["w_up"][l].t(), out=us[:n])
+                torch.matmul(us[:n], P["w_down"][l].t(), out=ys[:n])
+            torch.matmul(xs[:n], P["head"].t(), out=lgs[:n])
+
+    if args.calibrate_copy:
+        calibration_copy()
+    forward()
+    torch.cuda.synchronize()
+    t_step = timed_events(step, args.steps, args.warmup)
+    t_fwd = timed_events(forward, max(2, args.steps - 1), 0)
+    t_unp = timed_events(unperturbed, max(2, args.steps - 1), 1)
+    t_upd = timed_events(update, max(2, args.steps - 1), 0)
+
+    # per-kernel durations of one step, HIP events on the library's stream
+    ctx.profile_enable(True)
+    step()
+    kernels = kernel_table(ctx.profile_read())
+    ctx.profile_enable(False)
+    loglik_mean = float(ll.view(N, S)[:, :-1].mean())
+    ctx.eggroll_trim()
+
+    # vendor-library yardsticks (run after the library's legs so that both have the memory they need)
+    t_torch = timed_events(torch_pipeline, 2, 1)
+    rows_c = min(chunk, N) * S
+    xs = torch.randn((rows_c, d), device="cuda").to(torch.bfloat16)
+    ys = torch.empty_like(xs)
+    us = torch.empty((rows_c, ff), dtype=torch.bfloat16, device="cuda")
+    lgs = torch.empty((rows_c, V), dtype=torch.bfloat16, device="cuda")
+    t_gemms = timed_events(torch_gemms_only, 2, 1)
+    del xs, ys, us, lgs
+    ceil = measured_ceilings()
+
+    lin_flops_row = 2.0 * (L * (4 * d * d + 2 * d * ff) + V * d)
+    corr_flops_row = sum(2.0 * rank * (a + b) + b for a, b in [(d, d)] * (4 * L) + [(d, ff)] * L + [(ff, d)] * L + [(d, V)])
+    attn_flops = 4.0 * L * heads * hd * N * S * (S + 1) / 2.0          # QK^T and PV over the causal triangle
+    fwd_flops = R * (lin_flops_row + corr_flops_row) + attn_flops
+    upd_flops = 2.0 * N * rank * (L * (4 * d * d + 2 * d * ff) + V * d)
+    gemm = kernels.get("forward_gemm_bf16", {"total_ms": float("nan"), "launches": 0, "avg_us": float("nan")})
+    gemm_flops = R * (lin_flops_row + corr_flops_row)   # algorithmic flops of all launches of the dominant kernel in one step
+    achieved = gemm_flops / (gemm["total_ms"] * 1e-3) / 1e12
+    peak = roofline.MFMA_PEAK_TFLOPS["bf16"]
+    upd = kernels.get("update_gemm_f16")
+    out = {
+        "metric": "population tokens/sec (perturbed forward + update), 1 GPU",
+        "value": R / t_step["median"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_step["median"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg5_decoder_L16_d2048_h16_ff8192_V32000_N%d_S256_r1" % N, "layers": L, "d_model": d, "heads": heads,
+                   "d_ff": ff, "vocab": V, "population": N, "tokens_per_member": S, "rank": rank, "sigma": sigma,
+                   "perturbed_matrices": 6 * L + 1, "chunk_members": chunk, "weights": "random init, drawn on the device (seeded)"},
+        "timing": {"method": "HIP events around each step on the library's stream", "step_s": t_step, "forward_s": t_fwd,
+                   "unperturbed_forward_s": t_unp, "update_s": t_upd, "torch_unperturbed_pipeline_s": t_torch,
+                   "torch_gemms_only_s": t_gemms},
+        "tokens_per_s": {"forward_plus_update": R / t_step["median"], "forward_only": R / t_fwd["median"],
+                         "unperturbed_own": R / t_unp["median"], "unperturbed_torch_pipeline": R / t_torch["median"]},
+        "pct_of_unperturbed": {"forward_vs_own_sigma0": 100.0 * t_unp["median"] / t_fwd["median"],
+                               "forward_vs_torch_pipeline": 100.0 * t_torch["median"] / t_fwd["median"],
+                               "forward_vs_torch_gemms_only": 100.0 * t_gemms["median"] / t_fwd["median"],
+                               "quoted": 100.0 * min(t_unp["median"], t_torch["median"]) / t_fwd["median"]},
+        "model_flops": {"forward_linear_plus_correction": R * (lin_flops_row + corr_flops_row), "forward_attention": attn_flops,
+                        "update": upd_flops,
+                        "forward_frac_of_bf16_peak": fwd_flops / t_fwd["median"] / 1e12 / peak,
+                        "step_frac_of_bf16_peak": (fwd_flops + upd_flops) / t_step["median"] / 1e12 / peak},
+        "roofline": {"bound": "mfma", "kernel": "forward_gemm_bf16 (all %d launches of one step)" % gemm["launches"],
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": profiled_traffic("cfg5", ("MmaBf16", "FwdEpi"))},
+        "measured_ceilings": ceil,
+        "mean_token_loglik": loglik_mean,
+        "kernels": kernels,
+    }
+    if upd:
+        ut = upd_flops / (upd["total_ms"] * 1e-3) / 1e12
+        out["update_roofline"] = {"bound": "mfma", "kernel": "update_gemm_f16", "achieved": ut, "peak": peak, "unit": "TFLOP/s", "frac": ut / peak}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_decoder(P, tokens, L, d, heads, ff, V, S, N, rank, sigma, eps)
+    ctx.close()
+    return out
+
+
+def cpu_baseline_decoder(P, tokens, L, d, heads, ff, V, S, N, rank, sigma, eps):
+    """The oracle (explicit W_i per member and matrix, fp64) on ONE member through the first layers and the head, and the
+    explicit outer-product update of one attention matrix over a few members; both costs are linear in what was
+    left out (layers, members, matrix entries), so the full step is extrapolated from them."""
+    import numpy as np
+
+    import oracle
+    from oracle import models
+
+    Lc = min(L, 2)
+    Ph = {k: (v[:Lc] if v.dim() == 3 or (v.dim() == 2 and k in ("norm1", "norm2")) else v).float().cpu().numpy() for k, v in P.items()}
+    tok = tokens[:1].cpu().numpy()
+    t0 = time.perf_counter()
+    models.decoder_forward(0, 0, 0, [0], tok, Ph, heads, eps, rank, sigma)
+    t_fwd = time.perf_counter() - t0
+    # head + embedding cost is in the sample once; layers scale linearly: time one more layer-free pass to separate them
+    P0 = dict(Ph, **{k: Ph[k][:0] for k in ("norm1", "norm2", "wq", "wk", "wv", "wo", "w_up", "w_down")})
+    t0 = time.perf_counter()
+    models.decoder_forward(0, 0, 6 * L, [0], tok, P0, heads, eps, rank, sigma)
+    t_head = time.perf_counter() - t0
+    per_member = t_head + (t_fwd - t_head) * L / Lc
+    mu = 64
+    f = np.random.default_rng(0).standard_normal(mu)
+    t0 = time.perf_counter()
+    oracle.update(0, 0, 0, 0, mu, d, d, rank, oracle.NOISE_BF16, f, 1.0)
+    t_upd = time.perf_counter() - t0
+    upd_full = t_upd / (mu * d * d) * N * (L * (4 * d * d + 2 * d * ff) + V * d)
+    total = per_member * N + upd_full
+    return {"value": N * S / total, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "forward: 1 of %d members through %d of %d layers + head (%.1f s; %.1f s of it the head), extrapolated linearly in "
+                      "layers and members to %.3g s; update: one %dx%d matrix over %d members (%.2f s), extrapolated linearly in members "
+                      "and matrix entries to %.3g s" % (N, Lc, L, t_fwd + t_head, t_head, per_member * N, d, d, mu, t_upd, upd_full)}
+
+
+def mlp_stack_workload(args):
+    """Configuration 4: 8-layer GELU MLP stack, d = 2048, ffn = 8192, N = 16384 members x 64 rows, rank 4, sigma = 1e-3;
+    a step is the forward over all 16 perturbed matrices plus their 16 updates (K = N r = 65536)."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+
+    from paper_2511_16652_amd import binding as eb
+    from paper_2511_16652_amd import inputs, roofline
+
+    L, d, ff, S, rank, sigma = 8, 2048, 8192, 64, 4, 1e-3
+    N = args.members or 16384
+    R = N * S
+    g = torch.Generator(device="cuda").manual_seed(1004)
+    W1 = torch.stack([(torch.randn((ff, d), generator=g, device="cuda") / d ** 0.5).to(torch.bfloat16) for _ in range(L)])
+    W2 = torch.stack([(torch.randn((d, ff), generator=g, device="cuda") / ff ** 0.5).to(torch.bfloat16) for _ in range(L)])
+    X = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
+    for lo in range(0, R, 1 << 16):
+        X[lo:lo + (1 << 16)] = torch.randn((min(1 << 16, R - lo), d), generator=g, device="cuda").to(torch.bfloat16)
+    Y = torch.empty_like(X)
+    raw = torch.randn(N, generator=g, device="cuda")
+    fit = (raw - raw.mean()).float().contiguous()
+    ctx = eb.Context(0)
+    key, shape = eb.make_key(0, 0, 0), eb.make_shape(0, N, S, d, d, rank)
+    scale, lr = eb.eggroll_default_scale(N, sigma, rank), 1e-5
+    chunk = max(1, (1 << 18) // S)
+
+    def forward():
+        ctx.eggroll_mlp_stack_forward(key, shape, L, ff, sigma, W1, W2, X, Y, 0)
+
+    def unperturbed():
+        ctx.eggroll_mlp_stack_forward(key, shape, L, ff, 0.0, W1, W2, X, Y, 0)
+
+    def update():
+        ctx.eggroll_mlp_stack_update(key, shape, L, ff, fit, scale, lr, W1, W2)
+
+    def step():
+        forward()
+        update()
+
+    def torch_pipeline():
+        for m0 in range(0, R, chunk * S):
+            h = X[m0:m0 + chunk * S]
+            for l in range(L):
+                h = torch.matmul(F.gelu(torch.matmul(h, W1[l].t())), W2[l].t())
+            Y[m0:m0 + chunk * S] = h
+
+    if args.calibrate_copy:
+        calibration_copy()
+    forward()
+    torch.cuda.synchronize()
+    t_step = timed_events(step, args.steps, args.warmup)
+    t_fwd = timed_events(forward, max(2, args.steps), 0)
+    t_unp = timed_events(unperturbed, max(2, args.steps), 1)
+    t_upd = timed_events(update, max(2, args.steps), 0)
+    ctx.profile_enable(True)
+    step()
+    kernels = kernel_table(ctx.profile_read())
+    ctx.profile_enable(False)
+    ctx.eggroll_trim()
+    t_torch = timed_events(torch_pipeline, 2, 1)
+    ceil = measured_ceilings()
+
+    lin = 2.0 * L * 2 * d * ff
+    corr = L * ((2.0 * rank * (d + ff) + ff) + (2.0 * rank * (ff + d) + d))
+    fwd_flops = R * (lin + corr)
+    upd_flops = 2.0 * N * rank * L * 2 * d * ff
+    peak = roofline.MFMA_PEAK_TFLOPS["bf16"]
+    gemm = kernels["forward_gemm_bf16"]
+    achieved = fwd_flops / (gemm["total_ms"] * 1e-3) / 1e12
+    out = {
+        "metric": "population tokens/sec (perturbed forward + update), 1 GPU",
+        "value": R / t_step["median"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_step["median"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg4_mlp_stack_L8_d2048_ff8192_N%d_S64_r4" % N, "layers": L, "d": d, "d_ff": ff, "population": N,
+                   "rows_per_member": S, "rank": rank, "sigma": sigma, "perturbed_matrices": 2 * L, "chunk_members": chunk},
+        "timing": {"method": "HIP events around each step on the library's stream", "step_s": t_step, "forward_s": t_fwd,
+                   "unperturbed_forward_s": t_unp, "update_s": t_upd, "torch_unperturbed_pipeline_s": t_torch},
+        "tokens_per_s": {"forward_plus_update": R / t_step["median"], "forward_only": R / t_fwd["median"],
+                         "unperturbed_own": R / t_unp["median"], "unperturbed_torch_pipeline": R / t_torch["median"]},
+        "pct_of_unperturbed": {"forward_vs_own_sigma0": 100.0 * t_unp["median"] / t_fwd["median"],
+                               "forward_vs_torch_pipeline": 100.0 * t_torch["median"] / t_fwd["median"],
+                               "quoted": 100.0 * min(t_unp["median"], t_torch["median"]) / t_fwd["median"]},
+        "model_flops": {"forward": fwd_flops, "update": upd_flops,
+                        "forward_frac_of_bf16_peak": fwd_flops / t_fwd["median"] / 1e12 / peak,
+                        "step_frac_of_bf16_peak": (fwd_flops + upd_flops) / t_step["median"] / 1e12 / peak},
+        "roofline": {"bound": "mfma", "kernel": "forward_gemm_bf16 (all %d launches of one step)" % gemm["launches"],
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": profiled_traffic("cfg4", ("MmaBf16", "FwdEpi"))},
+        "measured_ceilings": ceil,
+        "kernels": kernels,
+    }
+    upd = kernels.get("update_gemm_f16")
+    if upd:
+        ut = upd_flops / (upd["total_ms"] * 1e-3) / 1e12
+        out["update_roofline"] = {"bound": "mfma", "kernel": "update_gemm_f16", "achieved": ut, "peak": peak, "unit": "TFLOP/s", "frac": ut / peak}
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import models
+        W1h, W2h = W1[:2].float().cpu().numpy(), W2[:2].float().cpu().numpy()
+        xm = X[:S].float().cpu().numpy()
+        t0 = time.perf_counter()
+        models.mlp_stack_forward(0, 0, 0, [0], S, rank, sigma, W1h, W2h, [xm])
+        t_f = (time.perf_counter() - t0) * L / 2
+        mu = 16
+        f = np.random.default_rng(0).standard_normal(mu)
+        t0 = time.perf_counter()
+        oracle.update(0, 0, 0, 0, mu, d, d, rank, oracle.NOISE_BF16, f, 1.0)
+        t_u = (time.perf_counter() - t0) / (mu * d * d) * N * L * 2 * d * ff
+        out["cpu_baseline"] = {"value": R / (t_f * N + t_u), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": "forward: 1 of %d members through 2 of %d layers, extrapolated linearly to %.3g s; update: one %dx%d "
+                                         "matrix over %d members, extrapolated linearly in members and entries to %.3g s" % (N, L, t_f * N, d, d, mu, t_u)}
+    ctx.close()
+    return out
+
+
 def linear_workload(args):
     """bf16/fp32 linear layer: perturbed forward + update."""
     import numpy as np
@@ -103,11 +446,12 @@ def linear_workload(args):
     elif args.workload.startswith("p0"):   # the paper's own speed benchmark shape: bf16 8192x8192, batch 1024
         rank = int(args.workload[4:]) if args.workload.startswith("p0_r") else 1   # p0_r2, p0_r4, p0_r8: rank sweep
         wl = inputs.make_linear("p0_bf16_8192_N1024_r%d" % rank, "bf16", 8192, 8192, 1024, 1, rank, 1e-3, 1100)
-    elif args.workload in ("mlp_up", "mlp_down", "ffn_up", "attn_proj"):
+    elif args.workload in ("mlp_up", "mlp_down", "ffn_up", "attn_proj", "lm_head"):
         # single layers of the MLP-stack / decoder configurations at full population; inputs are drawn
         # on the device (too large to stage through the host), so these lines have no oracle leg
         shp = {"mlp_up": (8192, 2048, 16384, 64, 4), "mlp_down": (2048, 8192, 16384, 64, 4),
-               "ffn_up": (8192, 2048, 8192, 256, 1), "attn_proj": (2048, 2048, 8192, 256, 1)}[args.workload]
+               "ffn_up": (8192, 2048, 8192, 256, 1), "attn_proj": (2048, 2048, 8192, 256, 1),
+               "lm_head": (32000, 2048, 1024, 256, 1)}[args.workload]
         wl = inputs.LinearWorkload(args.workload, "bf16", shp[0], shp[1], shp[2], shp[3], shp[4], 1e-3, 0)
         g = torch.Generator(device="cuda").manual_seed(1234)
         wl.W = None
@@ -583,7 +927,11 @@ def main():
         sys.stderr.write("bench.py: this build runs on ONE GPU (the hot path of one MI355X); --gpus %d is not "
                          "supported: every figure here is one GPU's throughput.\n" % args.gpus)
         sys.exit(2)
-    if args.workload == "cfg3":
+    if args.workload == "cfg5":
+        res = decoder_workload(args)
+    elif args.workload == "cfg4":
+        res = mlp_stack_workload(args)
+    elif args.workload == "cfg3":
         res = int8_workload(args)
     elif args.workload == "gru":
         res = gru_workload(args)

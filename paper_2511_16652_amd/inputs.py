@@ -182,3 +182,30 @@ def decoder_params(V: int, d: int, d_ff: int, L: int, data_seed: int, norm_jitte
 def decoder_tokens(N: int, S: int, V: int, data_seed: int) -> np.ndarray:
     """Uniform random token ids [N, S] in [0, V)."""
     return np.random.default_rng(data_seed).integers(0, V, size=(N, S), dtype=np.int64).astype(np.int32)
+
+
+def decoder_params_device(V: int, d: int, d_ff: int, L: int, data_seed: int, norm_jitter: float = 0.0) -> dict:
+    """The same recipe as decoder_params, drawn on the GPU by torch's seeded generator (a billion-parameter model is
+    too slow to draw on the host): dict of bf16 device tensors.  The values differ from the host recipe's; a test
+    that needs them on the host copies them back."""
+    import torch
+    g = torch.Generator(device="cuda").manual_seed(data_seed)
+    out = {}
+    for name, shape in DECODER_PARAM_SHAPES(V, d, d_ff, L).items():
+        if name.startswith("norm"):
+            a = 1.0 + norm_jitter * torch.randn(shape, generator=g, device="cuda")
+        else:
+            a = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+            flat = a.view(-1, shape[-1])
+            sc = 1.0 if name == "emb" else 1.0 / float(np.sqrt(shape[-1]))
+            for lo in range(0, flat.shape[0], 1 << 14):      # in slabs: the fp32 draw of a whole tensor need not exist at once
+                n = min(1 << 14, flat.shape[0] - lo)
+                flat[lo:lo + n] = (torch.randn((n, shape[-1]), generator=g, device="cuda") * sc).to(torch.bfloat16)
+        out[name] = a.to(torch.bfloat16).contiguous()
+    return out
+
+
+def decoder_tokens_device(N: int, S: int, V: int, data_seed: int):
+    import torch
+    g = torch.Generator(device="cuda").manual_seed(data_seed)
+    return torch.randint(0, V, (N, S), generator=g, device="cuda", dtype=torch.int32)
