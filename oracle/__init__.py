@@ -59,6 +59,8 @@ def _load():
         lib.oracle_round_bf16.restype = dbl
         lib.oracle_noise_matrix.argtypes = [u64, u32, u32, i32, i64, i64, i32, i32, vp]
         lib.oracle_noise_matrix.restype = None
+        lib.oracle_noise_gather.argtypes = [u64, u32, u32, i32, i64, i64, vp, i64, i32, vp]
+        lib.oracle_noise_gather.restype = None
         lib.oracle_forward.argtypes = [u64, u32, u32, i64, i64, i32, i32, i32, i32, i32, dbl, i32,
                                        vp, vp, vp]
         lib.oracle_forward.restype = i32
@@ -155,6 +157,14 @@ def noise_matrix(seed, step, layer, which, member, d, rank, noise_dtype) -> np.n
     """A_i (which=0) or B_i (which=1) as stored: fp64 array [d, rank] of storage-dtype values."""
     out = np.empty((int(d), int(rank)), np.float64)
     _load().oracle_noise_matrix(seed, step, layer, which, member, d, rank, noise_dtype, _ptr(out))
+    return out
+
+
+def noise_gather(seed, step, layer, which, member_begin, member_count, idx, noise_dtype) -> np.ndarray:
+    """Entries idx (flat indices d*rank + l) of the stored factor vectors of a range of members: fp64 [count, len(idx)]."""
+    idx = _c(idx, np.int64)
+    out = np.empty((int(member_count), idx.size), np.float64)
+    _load().oracle_noise_gather(seed, step, layer, which, member_begin, member_count, _ptr(idx), idx.size, noise_dtype, _ptr(out))
     return out
 
 

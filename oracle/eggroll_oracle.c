@@ -190,6 +190,24 @@ void oracle_noise_matrix(uint64_t seed, uint32_t step, uint32_t layer, int which
     for (uint64_t v = 0; v < n; ++v) out[v] = round_storage(out[v], noise_dtype);
 }
 
+/*
+ * Random access into the factors of many members at once: out[m][q] = storage-rounded entry idx[q] of the
+ * vector of member member_begin + m (which = 0: A, flat index j*rank + l; which = 1: B).  Used by sampled
+ * checks of the update at sizes where no whole factor matrix can be drawn per member.
+ */
+void oracle_noise_gather(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member_begin,
+                         int64_t member_count, const int64_t* idx, int64_t n_idx, int noise_dtype, double* out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < member_count; ++m) {
+        for (int64_t q = 0; q < n_idx; ++q) {
+            double v;
+            oracle_noise_normal(seed, step, layer, which, member_begin + m, (uint64_t)idx[q], 1, &v);
+            out[(size_t)m * (size_t)n_idx + (size_t)q] = round_storage(v, noise_dtype);
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------------------------ */
 /* forward: explicit W_i per member                                                            */
 /* ------------------------------------------------------------------------------------------ */

@@ -294,3 +294,12 @@ def test_oracle_es_steps_descend_a_quadratic():
         W = (W + lr * G).astype(np.float32)
         losses.append(float(((xb @ W.T - target) ** 2).sum(1).mean()))
     assert losses[0] > 4.0 and losses[-1] < 0.5 * losses[0], losses[::4]
+
+
+def test_noise_gather_reads_the_same_entries_as_the_whole_matrix():
+    idx = np.array([0, 1, 7, 38, 39, 5, 5], np.int64)
+    for which, dt in ((0, oracle.NOISE_BF16), (1, oracle.NOISE_F32)):
+        got = oracle.noise_gather(9, 2, 4, which, 100, 6, idx, dt)
+        for m in range(6):
+            full = oracle.noise_matrix(9, 2, 4, which, 100 + m, 10, 4, dt).reshape(-1)
+            assert np.array_equal(got[m], full[idx])
