@@ -102,12 +102,14 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bo
 // projection pre-pass + shared GEMM with the correction epilogue for one validated linear layer
 egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
                           egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
-                          float* t_fixed)
+                          float* t_fixed, const float* t_ready)
 {
     const bool panel = c->cache_layout == EGG_CACHE_PANEL;
     const int64_t R = shape.member_count * (int64_t)shape.rows_per_member;
     float* t = nullptr;
-    if (sigma != 0.0f) {
+    if (sigma != 0.0f && t_ready) {
+        t = const_cast<float*>(t_ready);  // the producer of X already formed the projections
+    } else if (sigma != 0.0f) {
         egg_status s = EGG_OK;
         if (t_fixed) {
             t = t_fixed;  // the caller's (static) projection buffer: nothing is allocated on this path

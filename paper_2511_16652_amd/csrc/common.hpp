@@ -50,6 +50,7 @@ struct eggroll_ctx {
     };
     std::vector<Rec> recs;
     std::vector<hipEvent_t> free_events;
+    std::map<std::string, int> shaped_names;  // interned "kernel[d_out x d_in]" labels (node addresses are stable)
 };
 
 namespace egg {
@@ -66,6 +67,15 @@ struct KernelScope {
     KernelScope(eggroll_ctx* ctx, const char* n);
     ~KernelScope();
 };
+
+// label of a per-shape timing row, e.g. forward_gemm_bf16[8192x2048]; only built when profiling is on
+inline const char* shaped_name(eggroll_ctx* c, const char* base, int d_out, int d_in)
+{
+    if (!c->prof) return base;
+    char buf[96];
+    snprintf(buf, sizeof buf, "%s[%dx%d]", base, d_out, d_in);
+    return c->shaped_names.emplace(buf, 0).first->first.c_str();
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -84,13 +94,15 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
                          egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache, bool b_panel);
 egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
                           egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
-                          float* t_fixed = nullptr);
+                          float* t_fixed = nullptr, const float* t_ready = nullptr);
 egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype, egg_dtype y_dtype,
                            float sigma, egg_act act, const void* W, const void* X, const void* R_in, bool need_r, void* Y,
                            void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity);
 // unperturbed glue of the decoder workload
 egg_status launch_embed_rows(eggroll_ctx* c, int64_t rows, int d, int vocab, const void* emb, const int32_t* tokens, void* X);
 egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y);
+egg_status launch_rmsnorm_proj(eggroll_ctx* c, int64_t rows, int S, int d, float eps, const void* gain, const void* X, void* Y, int nc,
+                               const void* const* B, float* const* t);
 egg_status launch_attention(eggroll_ctx* c, int64_t members, int S, int heads, int head_dim, const void* Q, const void* K,
                             const void* V, void* O);
 egg_status launch_token_loglik(eggroll_ctx* c, int64_t members, int S, int vocab, const void* logits, const int32_t* tokens, float* out);

@@ -33,8 +33,20 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8])
     }
 }
 
+// NC > 0: the pass also forms the rank-1 projections t_c[row] = sum_k Y[row][k] B_c[member(row)][k] of up to three linear
+// layers that consume Y (Sec. 4.2: the "batch of vector-vector dot products"), from the bf16 values it stores, in exactly the
+// order of the stand-alone projection pass (lane = 16-byte chunk modulo 64, ascending; then the xor-shuffle tree): the same
+// bits as that pass, without reading Y again.  B_c: materialised factors [member][d] (bf16).
+struct NormProj {
+    const uint16_t* B[3];
+    float* t[3];
+    int S;  // rows per member
+};
+
+template <int NC>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ X, const uint4* __restrict__ gain,
-                                                      uint4* __restrict__ Y, int64_t rows, int chunks, float inv_d, float eps)
+                                                      uint4* __restrict__ Y, int64_t rows, int chunks, float inv_d, float eps,
+                                                      NormProj np)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -51,6 +63,10 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
     const float r = 1.0f / sqrtf(ss * inv_d + eps);
     uint4* yr = Y + row * chunks;
+    const int64_t member = NC > 0 ? row / np.S : 0;
+    float acc[NC > 0 ? NC : 1];
+#pragma unroll
+    for (int q = 0; q < (NC > 0 ? NC : 1); ++q) acc[q] = 0.f;
     for (int c = lane; c < chunks; c += 64) {
         float x[8], g[8];
         unpack8(xr[c], x);
@@ -61,6 +77,26 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
         o.z = pack_bf16x2(x[4] * r * g[4], x[5] * r * g[5]);
         o.w = pack_bf16x2(x[6] * r * g[6], x[7] * r * g[7]);
         yr[c] = o;
+        if constexpr (NC > 0) {
+            float y[8];
+            unpack8(o, y);
+#pragma unroll
+            for (int q = 0; q < NC; ++q) {
+                float b[8];
+                unpack8(((const uint4*)(np.B[q] + member * (int64_t)chunks * 8))[c], b);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[q] = fmaf(y[e], b[e], acc[q]);
+            }
+        }
+    }
+    if constexpr (NC > 0) {
+#pragma unroll
+        for (int q = 0; q < NC; ++q) {
+            float v = acc[q];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0) np.t[q][row] = v;
+        }
     }
 }
 
@@ -270,9 +306,31 @@ egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const 
 {
     if (rows == 0) return EGG_OK;
     KernelScope ks(c, "rmsnorm");
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, (const uint4*)X,
-                       (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, (const uint4*)X,
+                       (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, NormProj{});
     return check_hip(c, hipGetLastError(), "rmsnorm launch");
+}
+
+// the normalisation with the projections of nc (1 or 3) consuming layers fused in; B[q]: [members][d] bf16, t[q]: [rows]
+egg_status launch_rmsnorm_proj(eggroll_ctx* c, int64_t rows, int S, int d, float eps, const void* gain, const void* X, void* Y, int nc,
+                               const void* const* B, float* const* t)
+{
+    if (rows == 0) return EGG_OK;
+    NormProj np{};
+    for (int q = 0; q < nc; ++q) {
+        np.B[q] = (const uint16_t*)B[q];
+        np.t[q] = t[q];
+    }
+    np.S = S;
+    KernelScope ks(c, "rmsnorm_project");
+    const dim3 g((unsigned)((rows + 3) / 4)), b(256);
+    if (nc == 1)
+        hipLaunchKernelGGL(rmsnorm_kernel<1>, g, b, 0, c->stream, (const uint4*)X, (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, np);
+    else if (nc == 3)
+        hipLaunchKernelGGL(rmsnorm_kernel<3>, g, b, 0, c->stream, (const uint4*)X, (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, np);
+    else
+        return fail(c, EGG_EINVAL, "rmsnorm_proj: %d consumers", nc);
+    return check_hip(c, hipGetLastError(), "rmsnorm_project launch");
 }
 
 template <int HD>

@@ -8,6 +8,36 @@
 
 namespace egg {
 
+// gelu(x) = x Phi(x) for outputs that are rounded to bf16.  Every vector-ALU slot of the epilogue is exposed time
+// (one slot per element costs about 1 % of a K = 2048 tile), and the library erff costs about 27 of them.  Here
+// Phi(x) - 1/2 is an odd degree-17 polynomial on [-4, 4] (least squares on Chebyshev nodes, pinned to 1/2 at the
+// ends so that the clamp continues it with Phi = 0 and Phi = 1): 12 slots.  |error of gelu| <= 2e-5 inside
+// (-3.8, 3.8) and <= 1.3e-4 at |x| = 4 (the neglected tail 4 Phi(-4)); a bf16 ulp of gelu is larger than that
+// wherever |gelu(x)| > 0.03.  fp32 outputs keep erff.
+// Four values at a time, step by step, so that the four Horner chains are independent neighbours in the
+// instruction stream (a dependent fma cannot issue back to back).
+__device__ __forceinline__ void gelu_bf16_grade4(float (&y)[4])
+{
+    float xc[4], x2[4], p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) xc[e] = __builtin_amdgcn_fmed3f(y[e], -4.0f, 4.0f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x2[e] = xc[e] * xc[e];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = fmaf(8.809068429e-11f, x2[e], -7.454938351e-09f);
+#define EGG_GELU_STEP(C) _Pragma("unroll") for (int e = 0; e < 4; ++e) p[e] = fmaf(p[e], x2[e], C);
+    EGG_GELU_STEP(2.826503707e-07f)
+    EGG_GELU_STEP(-6.433988670e-06f)
+    EGG_GELU_STEP(9.985887631e-05f)
+    EGG_GELU_STEP(-1.137293224e-03f)
+    EGG_GELU_STEP(9.882503528e-03f)
+    EGG_GELU_STEP(-6.641100396e-02f)
+    EGG_GELU_STEP(3.989198364e-01f)
+#undef EGG_GELU_STEP
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] *= fmaf(xc[e], p[e], 0.5f);
+}
+
 // Where the lane's factor entries A_i[m..m+3][0..RANK-1] come from:
 //   REGEN  (rank 1, one row per member): regenerated in registers from the counter stream -- each
 //          entry of A is needed by exactly one lane of the grid, so nothing is stored or re-read;
@@ -52,8 +82,8 @@ struct FwdEpi {
     // products stay accurate to about 2^-16.  The epilogue that follows is then the plain store.
     static constexpr int AW = RANK >= 2 ? RANK / 2 : 1;  // 32-bit words of one A_i[m][0..RANK) row in bf16
     static constexpr bool PREFETCH = RANK <= 4;  // rank 8 would not fit the register budget: it loads late
-    uint32_t pf_a[PREFETCH ? 4 : 1][2][AW];   // prefetched A rows of the lane, per (row block, column block)
-    float pf_t[2][RANK];                      // prefetched t of the lane's columns
+    uint32_t pf_a[PREFETCH ? 4 : 1][4][AW];   // prefetched A rows of the lane, per (row block, column block)
+    float pf_t[4][RANK];                      // prefetched t of the lane's columns
 
     template <int NB>
     __device__ __forceinline__ void fetch_t(int nw0, int lane, int n_rows)
@@ -80,7 +110,7 @@ struct FwdEpi {
     __device__ __forceinline__ void prefetch(int mw0, int nw0, int lane, int n_rows)
     {
         if constexpr (!REGEN && BF16 && PREFETCH) {
-            static_assert(MB <= 4 && NB <= 2, "prefetch storage");
+            static_assert(MB <= 4 && NB <= 4, "prefetch storage");
             if (!a.mma_corr) return;
             fetch_t<NB>(nw0, lane, n_rows);
 #pragma unroll
@@ -253,8 +283,12 @@ struct FwdEpi {
             }
         }
         if (a.act == EGG_ACT_GELU) {
+            if (a.y_bf16) {
+                gelu_bf16_grade4(y);
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = 0.5f * y[e] * (1.0f + erff(y[e] * 0.70710678118654752f));
+                for (int e = 0; e < 4; ++e) y[e] = 0.5f * y[e] * (1.0f + erff(y[e] * 0.70710678118654752f));
+            }
         }
         if (a.resid && live) {
             // each output element is read here and written (by flush or below) exactly once, so Y may be the
@@ -311,7 +345,7 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     if (st != EGG_OK) return st;
     const int64_t grid = (int64_t)tiles_m * tiles_n;
     if (grid > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many tiles");
-    KernelScope ks(c, name);
+    KernelScope ks(c, shaped_name(c, name, P.rows, kchunks * 16 / (Epi::IS_BF16 ? 2 : 4)));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks, tiles_m, tiles_n, 0,
                        (const char*)c->zero_page.p, ea);
     return check_hip(c, hipGetLastError(), name);
