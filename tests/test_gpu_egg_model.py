@@ -114,6 +114,22 @@ def test_forward_bit_exact(ctx, D, L, N, T, mb, anti):
         assert (S_want != S).mean() > 0.5
 
 
+def test_forward_65536_members_in_full(ctx):
+    """One token through the whole model (D = 256, 6 layers) for 2^16 members in antithetic pairs, every logit and
+    every state byte against the oracle: the row-streaming matmul kernel in all of its epilogue modes at a size
+    that fills the chip many times over."""
+    D, L, N, T = 256, 6, 1 << 16, 1
+    P = inputs.egg_model(D, L, 4242)
+    rng = np.random.default_rng(4243)
+    P["gru_b"] = rng.integers(-20, 21, P["gru_b"].shape).astype(np.int8)
+    tok = inputs.egg_tokens(T, N, 4244)
+    S = rng.integers(-60, 61, (L, N, D)).astype(np.int8)
+    logits, S_out = run_model(ctx, P, D, L, N, T, 0, 1, tok, S)
+    want, S_want = oracle.egg_forward_i8(SEED, STEP, LAYER, 0, N, D, L, 8, 4, P, tok, S, antithetic=True)
+    assert (S_out == S_want).all()
+    assert (logits == want).all()
+
+
 def test_forward_noise_matters_and_pairs_mirror(ctx):
     # without noise members with the same token history agree; with antithetic noise the two members of
     # a pair differ from each other and from the unperturbed run

@@ -41,6 +41,21 @@ def test_raw_words_bit_exact(ctx, case):
         assert (b[m].reshape(-1) == oracle.raw_words(seed, step, layer, 1, mb + m, 0, d_in * r)).all()
 
 
+def test_raw_words_sixteen_million_bit_exact(ctx):
+    """One call at configuration 2's size: 4096 members x 4096 words of each stream (1.7e7 words per stream),
+    every word against the oracle."""
+    import torch
+    n, d = 4096, 4096
+    A = torch.empty((n, d, 1), dtype=torch.int32, device="cuda")
+    B = torch.empty((n, d, 1), dtype=torch.int32, device="cuda")
+    ctx.eggroll_noise_gen(eb.make_key(0, 0, 0), eb.make_shape(0, n, 1, d, d, 1), eb.EGG_U32, eb.EGG_RAW, 0, A, B)
+    a = A.cpu().numpy().view(np.uint32).reshape(n, d)
+    b = B.cpu().numpy().view(np.uint32).reshape(n, d)
+    for m in range(n):
+        assert (a[m] == oracle.raw_words(0, 0, 0, 0, m, 0, d)).all(), m
+        assert (b[m] == oracle.raw_words(0, 0, 0, 1, m, 0, d)).all(), m
+
+
 @pytest.mark.parametrize("bound", [0, 1, 8, 127])
 @pytest.mark.parametrize("case", CASES[:3])
 def test_int_noise_bit_exact(ctx, case, bound):
