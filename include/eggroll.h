@@ -32,7 +32,7 @@
  *   - Noise depends on the GLOBAL member id (member_begin + local index), so any partition of the
  *     population into calls (or devices) regenerates identical factors.  Ids must stay < 2^32.
  *   - Every call returns egg_status; nothing throws or aborts.  EGG_EINVAL: null pointer,
- *     non-positive or inconsistent size, misaligned pointer, rank not in {1,2,4,8}, member range
+ *     non-positive or inconsistent size, misaligned pointer, rank not in {1,2,4,8,16}, member range
  *     outside [0, 2^32).  EGG_EUNSUPPORTED: a dtype/shape combination no kernel covers (the text
  *     from eggroll_last_error says which).  EGG_EHIP: a HIP runtime call failed.  EGG_ENOMEM:
  *     scratch could not be allocated.
@@ -70,7 +70,7 @@ typedef struct {
     int64_t member_count;     /* members in this call                                    */
     int32_t rows_per_member;  /* S: rows of X per member (tokens evaluated by a member)  */
     int32_t d_out, d_in;      /* M is d_out x d_in                                       */
-    int32_t rank;             /* r in {1,2,4,8}                                          */
+    int32_t rank;             /* r in {1,2,4,8,16}                                       */
     int32_t antithetic;       /* forward passes only: 1 = members 2p, 2p+1 form pair p    */
 } egg_shape;
 

@@ -87,8 +87,8 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bo
     if (!s) return fail(c, EGG_EINVAL, "shape is NULL");
     if (s->member_count <= 0 || s->d_out <= 0 || s->d_in <= 0) return fail(c, EGG_EINVAL, "non-positive size");
     if (need_rows && s->rows_per_member <= 0) return fail(c, EGG_EINVAL, "rows_per_member must be positive");
-    if (s->rank != 1 && s->rank != 2 && s->rank != 4 && s->rank != 8)
-        return fail(c, EGG_EINVAL, "rank %d not in {1,2,4,8}", s->rank);
+    if (s->rank != 1 && s->rank != 2 && s->rank != 4 && s->rank != 8 && s->rank != 16)
+        return fail(c, EGG_EINVAL, "rank %d not in {1,2,4,8,16}", s->rank);
     if (s->member_begin < 0 || s->member_begin + s->member_count > (int64_t(1) << 32))
         return fail(c, EGG_EINVAL, "member ids must lie in [0, 2^32)");
     if (s->antithetic != 0 && s->antithetic != 1) return fail(c, EGG_EINVAL, "antithetic must be 0 or 1");

@@ -102,7 +102,7 @@ struct FwdEpi {
         if constexpr (RANK == 1) dst[0] = src[0];
         else if constexpr (RANK == 2) dst[0] = *(const uint32_t*)src;
         else if constexpr (RANK == 4) { const uint2 v = *(const uint2*)src; dst[0] = v.x; dst[1] = v.y; }
-        else { const u32x4 v = *(const u32x4*)src; dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3]; }
+        else if constexpr (RANK == 8) { const u32x4 v = *(const u32x4*)src; dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3]; }
     }
 
     // issued at kernel start: the operands of extra_mma, so that their latency hides under the main loop
@@ -330,7 +330,8 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     size_t lds = gemm_lds_bytes<BM, BN>();
     size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
     ea.stage_a = 0;
-    ea.mma_corr = (!Epi::REGEN_MODE && Epi::IS_BF16 && ea.c != 0.f && ea.S % 32 == 0) ? 1 : 0;
+    // (rank <= 8: the 16 K-slots of the extra MFMA hold r factor entries beside the hi and lo halves of c t)
+    ea.mma_corr = (!Epi::REGEN_MODE && Epi::IS_BF16 && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % 32 == 0) ? 1 : 0;
     if (!Epi::REGEN_MODE && ea.c != 0.f && !ea.mma_corr) {
         const size_t need = (size_t)(BN / ea.S + 2) * BM * Epi::RANK_ELEMS_BYTES;
         // 16-byte copies: every member slice must start and end on a 16-byte boundary
@@ -413,14 +414,16 @@ egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_sh
             case 1: EGG_FWD(true, 1);
             case 2: EGG_FWD(true, 2);
             case 4: EGG_FWD(true, 4);
-            default: EGG_FWD(true, 8);
+            case 8: EGG_FWD(true, 8);
+            default: EGG_FWD(true, 16);
         }
     } else {
         switch (s.rank) {
             case 1: EGG_FWD(false, 1);
             case 2: EGG_FWD(false, 2);
             case 4: EGG_FWD(false, 4);
-            default: EGG_FWD(false, 8);
+            case 8: EGG_FWD(false, 8);
+            default: EGG_FWD(false, 16);
         }
     }
 #undef EGG_FWD

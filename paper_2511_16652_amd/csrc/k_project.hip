@@ -10,8 +10,11 @@ namespace egg {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// d_in is walked in panels of `panel` columns (a multiple of the 16-byte chunk, all of d_in when B_i fits the LDS budget):
+// per panel B_i[k0 .. k0 + panel) is regenerated into LDS and the member's rows are streamed against it; with more than
+// one panel the partial sums are carried in t itself (a row is always handled by the same wave).
 template <bool BF16, int RANK>
-__global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int anti_rows, int d_in,
+__global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t member_begin, int S, int anti_rows, int d_in, int panel,
                                                       const void* __restrict__ X, float* __restrict__ t,
                                                       void* __restrict__ B_cache)
 {
@@ -19,80 +22,89 @@ __global__ __launch_bounds__(256) void project_kernel(StreamKey kb, uint32_t mem
     const int tid = threadIdx.x;
     const int64_t ml = blockIdx.x;  // local member
     const uint32_t member = member_begin + (uint32_t)ml;
-    const int n = d_in * RANK;  // even: d_in is a multiple of 4
-
-    // ---- phase 1: B_i -> LDS (storage dtype), optional cache -------------------------------------
-    for (int b = tid; b < (n >> 1); b += 256) {
-        uint32_t w0, w1;
-        noise_words(kb, member, (uint32_t)b, w0, w1);
-        float z0, z1;
-        normal_pair<!BF16>(w0, w1, z0, z1);
-        if constexpr (BF16) {
-            const uint32_t pk = pack_bf16x2(z0, z1);
-            ((uint32_t*)smem)[b] = pk;
-            if (B_cache) ((uint32_t*)B_cache)[ml * (n >> 1) + b] = pk;
-        } else {
-            ((float2*)smem)[b] = make_float2(z0, z1);
-            if (B_cache) ((float2*)B_cache)[ml * (n >> 1) + b] = make_float2(z0, z1);
-        }
-    }
-    __syncthreads();
-
-    // ---- phase 2: one wave per row ----------------------------------------------------------------
     constexpr int EPC = BF16 ? 8 : 4;  // elements per 16-byte chunk of X
     const int lane = tid & 63, wave = tid >> 6;
-    const int chunks = d_in / EPC;
-    for (int s = wave; s < S; s += 4) {
-        const int64_t row = ml * S + s;
-        const uint4* xr = (const uint4*)((const char*)X + row * (int64_t)d_in * (BF16 ? 2 : 4));
-        float acc[RANK];
-#pragma unroll
-        for (int l = 0; l < RANK; ++l) acc[l] = 0.f;
-        for (int ch = lane; ch < chunks; ch += 64) {
-            const uint4 xv = xr[ch];
-            float x[EPC];
+
+    for (int k0 = 0; k0 < d_in; k0 += panel) {
+        const int kn = min(panel, d_in - k0);     // columns of this panel
+        const int n = kn * RANK;                  // even: d_in and panel are multiples of 4
+        const int first = k0 * RANK;              // flat index of the panel's first factor entry (even)
+        if (k0) __syncthreads();                  // every wave is done with the previous panel
+        // ---- phase 1: B_i panel -> LDS (storage dtype), optional cache ---------------------------
+        for (int b = tid; b < (n >> 1); b += 256) {
+            const int gb = (first >> 1) + b;      // Threefry block of the member's vector
+            uint32_t w0, w1;
+            noise_words(kb, member, (uint32_t)gb, w0, w1);
+            float z0, z1;
+            normal_pair<!BF16>(w0, w1, z0, z1);
             if constexpr (BF16) {
-                const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    x[2 * e] = __uint_as_float(w[e] << 16);
-                    x[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
-                }
+                const uint32_t pk = pack_bf16x2(z0, z1);
+                ((uint32_t*)smem)[b] = pk;
+                if (B_cache) ((uint32_t*)B_cache)[ml * (int64_t)((d_in * RANK) >> 1) + gb] = pk;
             } else {
-                x[0] = __uint_as_float(xv.x); x[1] = __uint_as_float(xv.y);
-                x[2] = __uint_as_float(xv.z); x[3] = __uint_as_float(xv.w);
+                ((float2*)smem)[b] = make_float2(z0, z1);
+                if (B_cache) ((float2*)B_cache)[ml * (int64_t)((d_in * RANK) >> 1) + gb] = make_float2(z0, z1);
             }
-            // B_i[k][l] for the chunk's k range: EPC*RANK consecutive elements = RANK 16-byte reads
-            const uint4* bp = (const uint4*)smem + (int64_t)ch * RANK;
-            float bv[EPC * RANK];
+        }
+        __syncthreads();
+
+        // ---- phase 2: one wave per row ------------------------------------------------------------
+        const int chunks = kn / EPC;
+        for (int s = wave; s < S; s += 4) {
+            const int64_t row = ml * S + s;
+            const uint4* xr = (const uint4*)((const char*)X + (row * (int64_t)d_in + k0) * (BF16 ? 2 : 4));
+            float acc[RANK];
 #pragma unroll
-            for (int v = 0; v < RANK; ++v) {
-                const uint4 q = bp[v];
-                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+            for (int l = 0; l < RANK; ++l) acc[l] = 0.f;
+            for (int ch = lane; ch < chunks; ch += 64) {
+                const uint4 xv = xr[ch];
+                float x[EPC];
                 if constexpr (BF16) {
+                    const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        bv[v * 8 + 2 * e] = __uint_as_float(w[e] << 16);
-                        bv[v * 8 + 2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+                        x[2 * e] = __uint_as_float(w[e] << 16);
+                        x[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
                     }
                 } else {
+                    x[0] = __uint_as_float(xv.x); x[1] = __uint_as_float(xv.y);
+                    x[2] = __uint_as_float(xv.z); x[3] = __uint_as_float(xv.w);
+                }
+                // B_i[k][l] for the chunk's k range: EPC*RANK consecutive elements = RANK 16-byte reads
+                const uint4* bp = (const uint4*)smem + (int64_t)ch * RANK;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) bv[v * 4 + e] = __uint_as_float(w[e]);
+                for (int v = 0; v < RANK; ++v) {
+                    const uint4 q = bp[v];
+                    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+                    // the 16 bytes hold flat entries v*EPC .. of the chunk: entry f belongs to column f / RANK, rank term f % RANK
+                    if constexpr (BF16) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int f = v * 8 + e;
+                            const float bv = (e & 1) ? __uint_as_float(w[e >> 1] & 0xFFFF0000u) : __uint_as_float(w[e >> 1] << 16);
+                            acc[f % RANK] = fmaf(x[f / RANK], bv, acc[f % RANK]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int f = v * 4 + e;
+                            acc[f % RANK] = fmaf(x[f / RANK], __uint_as_float(w[e]), acc[f % RANK]);
+                        }
+                    }
                 }
             }
 #pragma unroll
-            for (int e = 0; e < EPC; ++e)
+            for (int l = 0; l < RANK; ++l) {
+                float v = acc[l];
 #pragma unroll
-                for (int l = 0; l < RANK; ++l) acc[l] = fmaf(x[e], bv[e * RANK + l], acc[l]);
-        }
-#pragma unroll
-        for (int l = 0; l < RANK; ++l) {
-            float v = acc[l];
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-            // antithetic pairs: the workgroup owns both members of a pair (2 x anti_rows rows); the second
-            // member is evaluated at -sigma, which is folded into its projections
-            if (lane == 0) t[row * RANK + l] = (anti_rows && s >= anti_rows) ? -v : v;
+                for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+                // antithetic pairs: the workgroup owns both members of a pair (2 x anti_rows rows); the second
+                // member is evaluated at -sigma, which is folded into its projections
+                if (lane == 0) {
+                    const float sv = (anti_rows && s >= anti_rows) ? -v : v;
+                    t[row * RANK + l] = k0 ? t[row * RANK + l] + sv : sv;
+                }
+            }
         }
     }
 }
@@ -222,8 +234,11 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
         s.member_count /= 2;
         s.rows_per_member *= 2;
     }
-    const size_t lds = (size_t)s.d_in * s.rank * (BF16 ? 2 : 4);
-    if (lds > 128 * 1024) return fail(c, EGG_EUNSUPPORTED, "d_in * rank = %lld too large for the projection pass", (long long)s.d_in * s.rank);
+    // B_i panels of at most 128 KB in LDS: all of d_in when it fits, else the largest multiple of 64 columns
+    const int esz = BF16 ? 2 : 4;
+    int kpanel = s.d_in;
+    if ((size_t)s.d_in * s.rank * esz > 128 * 1024) kpanel = (int)(128 * 1024 / ((size_t)s.rank * esz)) / 64 * 64;
+    const size_t lds = (size_t)kpanel * s.rank * esz;
     const dim3 g((unsigned)s.member_count), b(256);
     if (s.member_count > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many members in one call");
     const uint32_t mb = (uint32_t)s.member_begin;
@@ -240,13 +255,14 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
             if (st != EGG_OK) return st;                                                                             \
         }                                                                                                            \
         KernelScope ks(c, "project");                                                                                \
-        hipLaunchKernelGGL(kern, g, b, lds, c->stream, kb, mb, s.rows_per_member, anti_rows, s.d_in, X, t, B_cache);            \
+        hipLaunchKernelGGL(kern, g, b, lds, c->stream, kb, mb, s.rows_per_member, anti_rows, s.d_in, kpanel, X, t, B_cache);            \
     }
     switch (s.rank) {
         case 1: EGG_LAUNCH_PROJECT(1) break;
         case 2: EGG_LAUNCH_PROJECT(2) break;
         case 4: EGG_LAUNCH_PROJECT(4) break;
-        default: EGG_LAUNCH_PROJECT(8) break;
+        case 8: EGG_LAUNCH_PROJECT(8) break;
+        default: EGG_LAUNCH_PROJECT(16) break;
     }
 #undef EGG_LAUNCH_PROJECT
     return check_hip(c, hipGetLastError(), "project launch");

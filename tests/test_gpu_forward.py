@@ -73,6 +73,10 @@ SHAPES = [  # dtype, d_out, d_in, N, S, rank, sigma   (ragged: nothing is a mult
     ("bf16", 132, 520, 37, 7, 2, 0.02),
     ("bf16", 260, 136, 5, 64, 4, 0.02),
     ("bf16", 72, 72, 140, 1, 8, 0.02),
+    ("f32", 40, 36, 21, 3, 16, 0.1),
+    ("bf16", 136, 72, 50, 1, 16, 0.02),
+    ("bf16", 96, 160, 4, 64, 16, 0.02),     # rows per member a multiple of 32: no extra-MFMA fold at this rank
+    ("bf16", 64, 8192, 6, 2, 16, 0.02),     # d_in * rank beyond one LDS panel of the projection pass
 ]
 
 

@@ -57,6 +57,8 @@ SHAPES = [  # dtype, d_out, d_in, N, r
     ("bf16", 132, 520, 37, 4),     # K = 148: partial chunk and partial K-tile
     ("bf16", 260, 136, 11, 2),
     ("bf16", 72, 72, 13, 8),
+    ("bf16", 136, 72, 29, 16),
+    ("f32", 40, 36, 21, 16),
 ]
 
 
@@ -174,3 +176,38 @@ def test_panel_cache_layout_is_bit_identical(d_out, d_in, N, mb):
         assert (got == want).mean() > 0.995 and np.abs(got - want).max() <= 2.0 ** -6 * (1 + np.abs(want).max())
     if N % 8:
         assert (panel[-1, :, N % 8:] == 0).all()
+
+
+def test_rank_convergence_on_the_device(ctx):
+    """The O(1/r) statement of Sec. "Rank Analysis" through the device path: fitness cos(<U, W_i>) from the
+    perturbed forward (fp32, one row per member, x = v so that y_i = W_i v), the update from eggroll_update, for
+    r in {1, 2, 4, 8, 16} and 2^20 members.  Each update matches the oracle's on the same fitness values, its
+    component along U matches the closed form (1 + sigma^2/r)^(-r/2-1) within Monte-Carlo error, and the gap to the
+    Gaussian ES limit exp(-sigma^2/2) halves with every doubling of r."""
+    import torch
+    from test_oracle_forward_update import rank_convergence_closed_form, rank_convergence_problem
+    u, v, M = rank_convergence_problem()
+    m, n, N, sigma = 8, 8, 1 << 20, 1.0
+    W = torch.from_numpy(M).cuda()
+    X = torch.from_numpy(np.tile(v[None, :], (N, 1))).cuda()
+    limit, gaps = -np.exp(-0.5), []
+    for r in (1, 2, 4, 8, 16):
+        Y = torch.empty((N, m), dtype=torch.float32, device="cuda")
+        key, shape = eb.make_key(7, 0, 3), eb.make_shape(0, N, 1, m, n, r)
+        ctx.eggroll_perturbed_forward(key, shape, sigma, eb.EGG_ACT_NONE, W, X, Y)
+        f = torch.cos(Y.double() @ torch.from_numpy(u.astype(np.float64)).cuda()).float().contiguous()
+        G = torch.empty((m, n), dtype=torch.float32, device="cuda")
+        scale = eb.eggroll_default_scale(N, sigma, r)
+        ctx.eggroll_update(key, shape, eb.EGG_F32, f, scale, 0, G)
+        torch.cuda.synchronize()
+        g = G.cpu().numpy().astype(np.float64)
+        if r in (1, 16):   # the oracle on the device's own fitness values (2^20 x r outer products: seconds)
+            g_ref = oracle.update(7, 0, 3, 0, N, m, n, r, oracle.NOISE_F32, f.cpu().numpy().astype(np.float64), scale)
+            # a contraction over K = 2^20 r terms of mixed sign: fp32 accumulation over K, not the single-layer 1e-5
+            assert np.abs(g - g_ref).max() <= 1e-4 * np.abs(g_ref).max()
+        got = float(u.astype(np.float64) @ g @ v.astype(np.float64))
+        want = rank_convergence_closed_form(r, sigma)
+        assert abs(got - want) < 5.0 / np.sqrt(N), (r, got, want)
+        gaps.append(abs(got - limit))
+    ratios = [gaps[i] / gaps[i + 1] for i in range(4)]
+    assert all(1.4 < q < 2.4 for q in ratios), ratios

@@ -303,3 +303,43 @@ def test_noise_gather_reads_the_same_entries_as_the_whole_matrix():
         for m in range(6):
             full = oracle.noise_matrix(9, 2, 4, which, 100 + m, 10, 4, dt).reshape(-1)
             assert np.array_equal(got[m], full[idx])
+
+
+def rank_convergence_closed_form(r, sigma=1.0):
+    """<U, g_r> for f(W) = cos(<U, W>), U = u v^T with unit u, v, at <U, M> = pi/2 and scale 1/(sigma N):
+    with X = <U, E^r> = r^{-1/2} sum_l (a_l.u)(b_l.v), E[exp(i s X)] = (1 + s^2/r)^{-r/2} (each (a.u)(b.v) is a product of
+    two independent standard normals, characteristic function (1 + t^2)^{-1/2}), hence
+    (1/sigma) E[cos(pi/2 + sigma X) X] = -(1/sigma) E[sin(sigma X) X] = (1/sigma) d/dsigma (1 + sigma^2/r)^{-r/2}
+    = -(1 + sigma^2/r)^{-r/2-1};  the Gaussian ES limit is -exp(-sigma^2/2)."""
+    return -(1.0 + sigma * sigma / r) ** (-r / 2.0 - 1.0)
+
+
+def rank_convergence_problem(m=8, n=8, seed=5):
+    rng = np.random.default_rng(seed)
+    u = rng.standard_normal(m); u /= np.linalg.norm(u)
+    v = rng.standard_normal(n); v /= np.linalg.norm(v)
+    M = (np.pi / 2.0) * np.outer(u, v)          # <U, M> = pi/2 exactly up to rounding
+    return u.astype(np.float32), v.astype(np.float32), M.astype(np.float32)
+
+
+def test_rank_convergence_of_the_update_is_one_over_r():
+    """Sec. "Rank Analysis" (EGGROLL Rank Convergence): the expected low-rank update approaches the Gaussian ES
+    gradient at rate O(1/r).  For the bounded fitness cos(<U, W>) both are known in closed form; the oracle's
+    forward (fitness through the explicit W_i) and update (explicit outer products) reproduce the finite-r value
+    within Monte-Carlo error, and the gap to the Gaussian limit halves with every doubling of r."""
+    u, v, M = rank_convergence_problem()
+    m, n, N, sigma = 8, 8, 1 << 17, 1.0
+    limit = -np.exp(-0.5)
+    gaps = []
+    for r in (1, 2, 4, 8, 16):
+        X = np.tile(v[None, :], (N, 1))
+        Y = oracle.forward(7, 0, 3, 0, N, 1, m, n, r, oracle.NOISE_F32, sigma, 0, M, X)   # y_i = W_i v
+        f = np.cos(Y @ u.astype(np.float64))                                             # cos(u^T W_i v)
+        G = oracle.update(7, 0, 3, 0, N, m, n, r, oracle.NOISE_F32, f, 1.0 / (N * sigma * np.sqrt(r)))
+        got = float(u.astype(np.float64) @ G @ v.astype(np.float64))
+        want = rank_convergence_closed_form(r, sigma)
+        assert abs(got - want) < 5.0 / np.sqrt(N), (r, got, want)      # Var(f X) <= E X^2 = 1
+        gaps.append(abs(want - limit))
+    ratios = [gaps[i] / gaps[i + 1] for i in range(4)]
+    assert all(1.5 < q < 2.2 for q in ratios), ratios                  # O(1/r): the gap halves as r doubles
+    assert gaps[-1] < 0.03 and gaps[0] > 0.25
