@@ -163,6 +163,13 @@ typedef enum { EGG_CACHE_ROWS = 0, EGG_CACHE_PANEL = 1 } egg_cache_layout;
 egg_status eggroll_set_cache_layout(eggroll_ctx* ctx, egg_cache_layout layout);
 
 /*
+ * Diagnostic switch.  The row-streaming integer matmul (used at d_in = 256) keeps loads in flight across its loop
+ * iterations and waits for them by count; with on != 0 it waits for every outstanding load instead (slower, no
+ * assumption about how many loads are in flight).  Results are identical in both forms; a test holds one against the other.
+ */
+egg_status eggroll_set_conservative_waits(eggroll_ctx* ctx, int on);
+
+/*
  * (2') Integer form (App. "Matrix Multiplication", "Adding EGGROLL Perturbations"), rank 1, one row per
  * member, W[d_out][d_in] int8 (both multiples of 16), applied `steps` times (steps > 1 feeds h' back in
  * and needs d_out == d_in; one step with a rectangular W is the integer MLP's matmul):

@@ -22,7 +22,7 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read",
-           "eggroll_scratch_generation", "eggroll_trim", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
+           "eggroll_scratch_generation", "eggroll_trim", "eggroll_set_conservative_waits", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
            "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_token_loglik_bf16",
            "eggroll_mlp_stack_forward", "eggroll_mlp_stack_update", "eggroll_decoder_forward", "eggroll_decoder_update"]
 
@@ -119,6 +119,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_int_threshold.restype = i64
     lib.eggroll_scratch_generation.argtypes = [vp]
     lib.eggroll_scratch_generation.restype = ctypes.c_uint64
+    lib.eggroll_set_conservative_waits.argtypes = [vp, i32]
+    lib.eggroll_set_conservative_waits.restype = i32
     lib.eggroll_trim.argtypes = [vp]
     lib.eggroll_trim.restype = i32
     lib.eggroll_perturbed_forward_add.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp, vp]
@@ -263,6 +265,9 @@ class Context:
 
     def eggroll_scratch_generation(self):
         return int(self._lib.eggroll_scratch_generation(self._h))
+
+    def eggroll_set_conservative_waits(self, on):
+        self._check(self._lib.eggroll_set_conservative_waits(self._h, int(bool(on))))
 
     def eggroll_trim(self):
         self._check(self._lib.eggroll_trim(self._h))

@@ -4,6 +4,8 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 namespace egg {
@@ -54,6 +56,18 @@ egg_status reserve(eggroll_ctx* c, eggroll_ctx::Buf& b, size_t bytes)
     b.bytes = want;
     ++c->scratch_generation;
     return EGG_OK;
+}
+
+egg_status ensure_dynamic_lds(eggroll_ctx* c, const void* kern, size_t bytes, const char* what)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void*>, size_t> limit;  // (device, function) -> bytes already granted
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& cur = limit[{c->device, kern}];
+    if (bytes <= cur) return EGG_OK;
+    egg_status st = check_hip(c, hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes), what);
+    if (st == EGG_OK) cur = bytes;
+    return st;
 }
 
 KernelScope::KernelScope(eggroll_ctx* ctx, const char* n) : c(ctx), name(n)
@@ -243,6 +257,13 @@ egg_status eggroll_trim(eggroll_ctx* c)
 double eggroll_default_scale(int64_t population, double sigma, int rank)
 {
     return 1.0 / ((double)population * sigma * sqrt((double)rank));
+}
+
+egg_status eggroll_set_conservative_waits(eggroll_ctx* c, int on)
+{
+    if (!c) return EGG_EINVAL;
+    c->conservative_waits = on != 0;
+    return EGG_OK;
 }
 
 egg_status eggroll_set_cache_layout(eggroll_ctx* c, egg_cache_layout layout)

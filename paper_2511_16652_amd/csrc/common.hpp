@@ -19,6 +19,7 @@ struct eggroll_ctx {
     hipStream_t stream = nullptr;
     std::string err;
     int cache_layout = 0;  // egg_cache_layout of the forward/update caches
+    bool conservative_waits = false;  // diagnostic: kernels with counted s_waitcnt wait for everything instead
 
     // scratch, grown on demand and kept for the life of the context
     struct Buf {
@@ -67,6 +68,11 @@ struct KernelScope {
     KernelScope(eggroll_ctx* ctx, const char* n);
     ~KernelScope();
 };
+
+// A kernel that needs more than the default dynamic LDS must have its limit raised; this does it on first use (and again
+// only if a later launch needs more), instead of on every launch.  The limit belongs to the function, not to a context:
+// the bookkeeping is process-wide (per device).
+egg_status ensure_dynamic_lds(eggroll_ctx* c, const void* kern, size_t bytes, const char* what);
 
 // label of a per-shape timing row, e.g. forward_gemm_bf16[8192x2048]; only built when profiling is on
 inline const char* shaped_name(eggroll_ctx* c, const char* base, int d_out, int d_in)

@@ -338,12 +338,8 @@ static egg_status launch_attention_t(eggroll_ctx* c, int64_t members, int S, int
                                      const void* V, void* O)
 {
     auto kern = attention_kernel<HD>;
-    static bool attr_set = false;  // once per process and instantiation: the attribute belongs to the function
-    if (!attr_set) {
-        egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, AttnCfg<HD>::LDS), "attention smem attr");
-        if (st != EGG_OK) return st;
-        attr_set = true;
-    }
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)AttnCfg<HD>::LDS, "attention smem attr");
+    if (st != EGG_OK) return st;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     KernelScope ks(c, "attention");
     hipLaunchKernelGGL(kern, dim3((unsigned)(members * heads)), dim3(512), AttnCfg<HD>::LDS, c->stream, (const uint16_t*)Q,

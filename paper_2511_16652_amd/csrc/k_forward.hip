@@ -342,7 +342,7 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     }
     if (epi_lds > lds) lds = epi_lds;
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "gemm smem attr");
     if (st != EGG_OK) return st;
     const int64_t grid = (int64_t)tiles_m * tiles_n;
     if (grid > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many tiles");

@@ -352,7 +352,7 @@ static egg_status launch_i8_gemm(eggroll_ctx* c, const Operand& P, const Operand
     const size_t lds = std::max(gemm_lds_bytes<BM, BN>(), (size_t)WM * WN * Epi::lds_per_wave(BM / WM));
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, false, Epi, (BM * BN <= 128 * 128 ? 2 : 1)>;
-    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_gemm_i8");
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks,
@@ -382,15 +382,19 @@ __device__ __forceinline__ void lds_barrier()
 //     multiply block b  ->  barrier (its buffer is free)  ->  epilogue of b  ->  fetch the factor bytes and
 //     dot products of b+1 into the registers the epilogue just finished with  ->  issue the loads of b+3 into
 //     the freed buffer  ->  wait until only that prefetch and those loads are outstanding  ->  barrier.
-// Loads complete in issue order among themselves, so the last wait proves that blocks b+1 and b+2 have landed
+// Loads complete in issue order among themselves, so the last wait proves that block b+1 has landed
 // and that the epilogue's stores are done (after which a use of the prefetched registers waits by count and
 // leaves block b+3's loads in flight through the next multiply and epilogue).  Every load named in that count
 // is issued unconditionally.  Column slices of a wider theta (the 4D x D matrix of the MLP) that read the same
 // rows sit on the same XCD, next to each other in launch order, so that the second to fourth read of a row
 // block hits that XCD's L2.
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding (vmcnt is split over
+// bits 3:0 and 15:14; the other counters are left at "do not wait")
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
 template <class Epi>
 __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restrict__ W, int d_out, Operand Q, int tiles_m,
-                                                           int nstreams, int nblocks, typename Epi::Args ea)
+                                                           int nstreams, int nblocks, int conservative, typename Epi::Args ea)
 {
     constexpr int BN = 64, NT = 256, WTM = 64, MB = 2, NB = 2, PITCH = 128, RING = 3;
     constexpr int HALF = BN * PITCH;  // 64 rows x one 128-byte half of K
@@ -485,8 +489,17 @@ __global__ __launch_bounds__(256, 2) void stream_i8_kernel(const int8_t* __restr
         if (nb3 < nblocks) {
             epi.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);   // 2 or 3 loads for each of its 4 passes
             issue(nb3, cur);
-            if (epi.has_next()) __builtin_amdgcn_s_waitcnt(0x0F74 | (1 << 14));  // vmcnt(20) = 4 + 12 + 4
-            else __builtin_amdgcn_s_waitcnt(0x0F70 | (1 << 14));                 // vmcnt(16) = 4 + 8 + 4
+            // Block nb+1 (issued two iterations ago) must have landed; what may stay in flight, in issue order: the
+            // ring loads of block nb+2, the factor prefetch of block nb+1 just issued, the ring loads of block nb+3.
+            // The counts are those of the source (fetch() loads A_i, B_i and the dot product, plus B_next with a
+            // next-dot epilogue; issue() is two DmaLoader passes); the conservative form waits for everything and
+            // exists so that a test can hold the counted form against it bit for bit.
+            constexpr int RING_LOADS = 2 * DmaLoader<BN, NT, false>::L;
+            constexpr int PF_LOADS_PLAIN = MB * NB * 2, PF_LOADS_NEXT = MB * NB * 3;
+            static_assert(2 * RING_LOADS + PF_LOADS_NEXT == 20 && 2 * RING_LOADS + PF_LOADS_PLAIN == 16, "outstanding-load budget of the ring");
+            if (conservative) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            else if (epi.has_next()) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * RING_LOADS + PF_LOADS_NEXT));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * RING_LOADS + PF_LOADS_PLAIN));
         } else {
             if (nb1 < nblocks) epi.template prefetch<MB, NB>(mw0, nb1 * BN, lane, Q.rows);
             __builtin_amdgcn_s_waitcnt(0x0F70);  // the last blocks: everything
@@ -506,10 +519,11 @@ static egg_status launch_i8_stream(eggroll_ctx* c, const int8_t* W, int d_out, c
     const size_t lds = 3 * 2 * 64 * 128 + 4 * Epi::lds_per_wave(64);   // ring of three blocks + the waves' staging slices
     if (!operand_offsets_fit(Q, 64)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     auto kern = stream_i8_kernel<Epi>;
-    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "stream smem attr");
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "stream smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, "forward_stream_i8");
-    hipLaunchKernelGGL(kern, dim3((unsigned)(nstreams * tiles_m)), dim3(256), lds, c->stream, W, d_out, Q, tiles_m, nstreams, nblocks, ea);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(nstreams * tiles_m)), dim3(256), lds, c->stream, W, d_out, Q, tiles_m, nstreams, nblocks,
+                       c->conservative_waits ? 1 : 0, ea);
     return check_hip(c, hipGetLastError(), "forward_stream_i8");
 }
 

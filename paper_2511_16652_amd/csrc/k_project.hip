@@ -251,7 +251,7 @@ static egg_status launch_project_t(eggroll_ctx* c, const StreamKey& kb, const eg
     {                                                                                                                \
         auto kern = project_kernel<BF16, R>;                                                                         \
         if (lds > 48 * 1024) {                                                                                       \
-            egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "project smem attr"); \
+            egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "project smem attr"); \
             if (st != EGG_OK) return st;                                                                             \
         }                                                                                                            \
         KernelScope ks(c, "project");                                                                                \

@@ -176,7 +176,7 @@ static egg_status launch_i8_upd_gemm(eggroll_ctx* c, const Operand& P, const Ope
     const size_t lds = std::max(gemm_lds_bytes<BM, BN>(), (size_t)WM * WN * I8UpdEpi::lds_per_wave(BM / WM));
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
     auto kern = gemm_nt_kernel<MmaI8, BM, BN, WM, WN, true, I8UpdEpi, (BM * BN <= 128 * 128 ? 2 : 1)>;
-    egg_status st = check_hip(c, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), "gemm smem attr");
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "gemm smem attr");
     if (st != EGG_OK) return st;
     ea.tiles = tiles_m * tiles_n;
     KernelScope ks(c, "update_gemm_i8");

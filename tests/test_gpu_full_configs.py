@@ -250,3 +250,24 @@ def test_integer_kernels_are_repeatable(ctx):
             first = (logits, S1)
         else:
             assert torch.equal(logits, first[0]) and torch.equal(S1, first[1]), rep
+
+
+def test_counted_waits_equal_conservative_waits(ctx):
+    """The row-streaming integer matmul waits for its in-flight loads by count.  With the diagnostic switch it waits
+    for every load instead; both forms must give the same bits in all of the kernel's epilogue modes (plain, the two
+    GRU gates, with and without the next-dot accumulation: the integer model's forward uses them all) at 2^16 rows."""
+    import torch
+    D, L, N, T = 256, 2, 1 << 16, 2
+    model = {k: torch.from_numpy(v).cuda() for k, v in inputs.egg_model(D, L, 91).items()}
+    tok = torch.from_numpy(inputs.egg_tokens(T, N, 92)).cuda()
+    S0 = torch.from_numpy(np.random.default_rng(93).integers(-60, 61, (L, N, D)).astype(np.int8)).cuda()
+    res = []
+    for on in (0, 1):
+        ctx.eggroll_set_conservative_waits(on)
+        S1 = torch.empty_like(S0)
+        logits = torch.empty((T, N, 256), dtype=torch.int8, device="cuda")
+        ctx.eggroll_egg_forward_i8(eb.make_key(1, 2, 3), eb.make_shape(0, N, 1, D, D, 1, antithetic=1), L, 8, 4, T, model, tok, S0, S1, logits)
+        torch.cuda.synchronize()
+        res.append((logits, S1))
+    ctx.eggroll_set_conservative_waits(0)
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])

@@ -60,6 +60,54 @@ def test_float_step_in_a_graph():
     ctx.close()
 
 
+def test_graph_survives_scratch_growth():
+    """A graph bakes the scratch addresses of the calls it captured.  A later, larger eager call makes the context
+    allocate bigger buffers; the outgrown ones are parked, not freed, so the graph's replays stay valid and correct.
+    eggroll_scratch_generation reports the replacement."""
+    import torch
+    d_out, d_in, N, sigma = 256, 256, 512, 0.01
+    g = torch.Generator(device="cuda").manual_seed(3)
+    W = (torch.randn((d_out, d_in), generator=g, device="cuda") / d_in ** 0.5).to(torch.bfloat16)
+    X = torch.randn((N, d_in), generator=g, device="cuda").to(torch.bfloat16)
+    f = torch.randn(N, generator=g, device="cuda")
+    Y = torch.empty((N, d_out), dtype=torch.bfloat16, device="cuda")
+    G = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+    ctx = eb.Context(0, stream=s)
+    key, shape = eb.make_key(5, 1, 2), eb.make_shape(0, N, 1, d_out, d_in, 1)
+
+    def step():
+        ctx.eggroll_perturbed_forward(key, shape, sigma, eb.EGG_ACT_NONE, W, X, Y)
+        ctx.eggroll_update(key, shape, eb.EGG_BF16, f, 1.0 / N, 0, G)
+
+    with torch.cuda.stream(s):
+        step()
+    torch.cuda.synchronize()
+    eager = [Y.clone(), G.clone()]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        step()
+    gen0 = ctx.eggroll_scratch_generation()
+    # a much larger eager call on the same context: projections, packed panels and the fitness normaliser all grow
+    Nb, db = 8192, 1024
+    Wb = torch.zeros((db, db), dtype=torch.bfloat16, device="cuda")
+    Xb = torch.zeros((Nb, db), dtype=torch.bfloat16, device="cuda")
+    Yb = torch.empty((Nb, db), dtype=torch.bfloat16, device="cuda")
+    Gb = torch.empty((db, db), dtype=torch.float32, device="cuda")
+    fb = torch.ones(Nb, device="cuda")
+
+    def disturb():
+        with torch.cuda.stream(s):
+            shb = eb.make_shape(0, Nb, 1, db, db, 1)
+            ctx.eggroll_perturbed_forward(eb.make_key(1, 1, 1), shb, 0.1, eb.EGG_ACT_NONE, Wb, Xb, Yb)
+            ctx.eggroll_update(eb.make_key(1, 1, 1), shb, eb.EGG_BF16, fb, 1.0, 0, Gb)
+
+    replay_and_compare(graph, [Y, G], eager, s, disturb)
+    assert ctx.eggroll_scratch_generation() > gen0
+    ctx.eggroll_trim()          # no graph of this context is replayed after this point
+    ctx.close()
+
+
 def test_integer_step_in_a_graph():
     import torch
     wl = inputs.make_int8("g", 256, 2304, 4, 41)

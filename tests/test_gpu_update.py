@@ -211,3 +211,22 @@ def test_rank_convergence_on_the_device(ctx):
         gaps.append(abs(got - limit))
     ratios = [gaps[i] / gaps[i + 1] for i in range(4)]
     assert all(1.4 < q < 2.4 for q in ratios), ratios
+
+
+def test_update_with_a_wide_fitness_range(ctx):
+    """bf16 factors travel through fp16 panels scaled by f_i / 2^ceil(log2 max|f|): members whose fitness is far
+    below the largest one lose relative precision (absolute error <= 2^-25 max|f| per term).  With a 1e6 dynamic
+    range of |f| the result must still sit inside the bf16 tolerance against the fp64 oracle."""
+    d_out, d_in, N, r = 132, 264, 512, 1
+    rng = np.random.default_rng(31)
+    f = rng.standard_normal(N) * 10.0 ** rng.uniform(-6, 0, N)
+    f[0] = 1.0
+    scale = 1.0 / N
+    G = run_update(ctx, (5, 1, 2), 3, N, d_out, d_in, r, "bf16", f, scale)
+    ref = oracle.update(5, 1, 2, 3, N, d_out, d_in, r, oracle.NOISE_BF16, f.astype(np.float32).astype(np.float64), scale)
+    check(G, ref, "bf16", "wide fitness range")
+    # the small-fitness members alone (max |f| = 1e-3 of the others): normalised by their own maximum, full precision again
+    small = np.where(np.abs(f) < 1e-3, f, 0.0)
+    G2 = run_update(ctx, (5, 1, 2), 3, N, d_out, d_in, r, "bf16", small, scale)
+    ref2 = oracle.update(5, 1, 2, 3, N, d_out, d_in, r, oracle.NOISE_BF16, small.astype(np.float32).astype(np.float64), scale)
+    check(G2, ref2, "bf16", "small fitness values alone")
