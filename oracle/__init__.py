@@ -55,6 +55,8 @@ def _load():
         lib.oracle_int_from_byte.restype = i32
         lib.oracle_noise_int.argtypes = [u64, u32, u32, i32, i64, u64, u64, i32, vp]
         lib.oracle_noise_int.restype = None
+        lib.oracle_normal_int_table.argtypes = [vp]
+        lib.oracle_normal_int_table.restype = None
         lib.oracle_round_bf16.argtypes = [dbl]
         lib.oracle_round_bf16.restype = dbl
         lib.oracle_noise_matrix.argtypes = [u64, u32, u32, i32, i64, i64, i32, i32, vp]
@@ -141,6 +143,16 @@ def noise_normal(seed, step, layer, which, member, first, n) -> np.ndarray:
 
 def int_from_byte(byte: int, bound: int) -> int:
     return int(_load().oracle_int_from_byte(byte, bound))
+
+
+BOUND_NORMAL16 = -16   # selects the table noise round(16 z) wherever a bound is taken
+
+
+def normal_int_table() -> np.ndarray:
+    """The 65536-entry int8 table T[k] = round(16 Phi^-1((k + 1/2) / 65536)) of the paper's integer noise."""
+    out = np.empty(65536, np.int8)
+    _load().oracle_normal_int_table(_ptr(out))
+    return out
 
 
 def noise_int(seed, step, layer, which, member, first, n, bound) -> np.ndarray:

@@ -145,9 +145,63 @@ int oracle_int_from_byte(unsigned byte, int bound)
     return ((int)byte < q * m) ? (int)byte / q - bound : 0;
 }
 
+/*
+ * The paper's own integer noise (App. "Adding EGGROLL Perturbations": "a pre-generated table of int8 normals
+ * [round(16 N(0,1))] randomly indexed", so that no floating point runs on the accelerator).  The paper does not
+ * give the table; reading: 2^16 entries, entry k the value at the midpoint of the k-th of 65536 equal-probability
+ * cells of N(0,1), T[k] = round(16 Phi^-1((k + 1/2)/65536)), half away from zero, clipped to 127 (never reached:
+ * the largest magnitude is 69).  Phi^-1 by bisection on Phi(x) = erfc(-x / sqrt 2) / 2.  Indexed by the 16-bit
+ * halves of the stream's words: value n uses half n & 1 (low half first) of word n >> 1.  Selected by bound = -16.
+ */
+#define ORACLE_BOUND_NORMAL16 (-16)
+
+static double normal_cdf(double x) { return 0.5 * erfc(-x * 0.70710678118654752440); }
+
+void oracle_normal_int_table(int8_t* out)
+{
+    for (int k = 0; k < 65536; ++k) {
+        const double p = ((double)k + 0.5) / 65536.0;
+        double lo = -10.0, hi = 10.0;
+        for (int it = 0; it < 200; ++it) { /* Phi is increasing: keep Phi(lo) <= p <= Phi(hi) */
+            const double mid = 0.5 * (lo + hi);
+            if (normal_cdf(mid) < p) lo = mid; else hi = mid;
+        }
+        const double z16 = 16.0 * 0.5 * (lo + hi);
+        double v = z16 >= 0.0 ? floor(z16 + 0.5) : -floor(-z16 + 0.5); /* half away from zero */
+        if (v > 127.0) v = 127.0;
+        if (v < -127.0) v = -127.0;
+        out[k] = (int8_t)v;
+    }
+}
+
+static const int8_t* normal_int_table_once(void)
+{
+    static int8_t table[65536];
+    static int ready = 0;
+#pragma omp critical(oracle_normal_table)
+    {
+        if (!ready) {
+            oracle_normal_int_table(table);
+            ready = 1;
+        }
+    }
+    return table;
+}
+
 void oracle_noise_int(uint64_t seed, uint32_t step, uint32_t layer, int which, int64_t member,
                       uint64_t first, uint64_t n, int bound, int8_t* out)
 {
+    if (bound == ORACLE_BOUND_NORMAL16) {
+        const int8_t* table = normal_int_table_once();
+        for (uint64_t v = 0; v < n; ++v) {
+            const uint64_t idx = first + v;
+            uint32_t blk[2];
+            noise_block(seed, step, layer, which, member, (uint32_t)(idx >> 2), blk);
+            const uint32_t word = blk[(idx >> 1) & 1u];
+            out[v] = table[(word >> (16u * (unsigned)(idx & 1u))) & 0xFFFFu];
+        }
+        return;
+    }
     for (uint64_t v = 0; v < n; ++v) {
         const uint64_t idx = first + v;
         uint32_t blk[2];
