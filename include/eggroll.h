@@ -59,7 +59,14 @@ typedef struct eggroll_ctx eggroll_ctx; /* opaque; owns scratch buffers and the 
 
 typedef enum { EGG_OK = 0, EGG_EINVAL = -1, EGG_EUNSUPPORTED = -2, EGG_EHIP = -3, EGG_ENOMEM = -4 } egg_status;
 typedef enum { EGG_F32 = 0, EGG_BF16 = 1, EGG_I8 = 2, EGG_U32 = 3 } egg_dtype;
-typedef enum { EGG_NORMAL = 0, EGG_UNIFORM_INT = 1, EGG_RAW = 2 } egg_dist;
+typedef enum { EGG_NORMAL = 0, EGG_UNIFORM_INT = 1, EGG_RAW = 2, EGG_NORMAL_INT16 = 3 } egg_dist;
+/* Passed as `int_bound` to any integer entry point: the factors are the paper's own integer noise instead of uniform
+   integers (App. "Adding EGGROLL Perturbations": int8 values round(16 z), z ~ N(0,1), from a pre-generated table indexed
+   at random).  Value n of a factor vector is T[h], h = 16-bit half n & 1 (low half first) of word n >> 1 of the stream,
+   T[k] = round(16 Phi^-1((k + 1/2) / 65536)) for k = 0 .. 65535 (half away from zero; T[65535 - k] = -T[k]; |T| <= 69;
+   standard deviation 16.0 to three digits).  With this noise the paper's correction shift is corr_shift = 4 + sigma_hat.
+   The table is built on the host and uploaded with a blocking copy the first time a context needs it. */
+#define EGG_INT_NOISE_NORMAL16 (-16)
 typedef enum { EGG_ACT_NONE = 0, EGG_ACT_GELU = 1 } egg_act;
 
 /* names one weight matrix at one ES iteration (Alg. 1: the seeds every worker knows) */
@@ -104,6 +111,7 @@ double eggroll_default_scale(int64_t population, double sigma, int rank);
  *   A_out[member_count][d_out][rank], B_out[member_count][d_in][rank]; either may be NULL.
  *   dist = EGG_NORMAL      dtype EGG_F32 or EGG_BF16      Gaussian factors
  *   dist = EGG_UNIFORM_INT dtype EGG_I8                   integers on {-int_bound..int_bound}
+ *   dist = EGG_NORMAL_INT16 dtype EGG_I8                  the table noise of EGG_INT_NOISE_NORMAL16 (int_bound ignored)
  *   dist = EGG_RAW         dtype EGG_U32                  the raw 32-bit words (one per element)
  * rows_per_member is ignored.
  */
@@ -307,6 +315,9 @@ egg_status eggroll_update(eggroll_ctx* ctx, egg_key key, const egg_shape* shape,
  */
 egg_status eggroll_update_i8(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, int int_bound,
                              const int8_t* fitness, int32_t threshold, int8_t* theta, int32_t* E_out);
+
+/* The 65536-entry table behind EGG_INT_NOISE_NORMAL16, computed on the host (out: 65536 bytes).  Host-only. */
+void eggroll_normal_int_table(int8_t* out);
 
 /* Threshold of (3'), computed on the host as the paper prescribes: I32(16 Phi^-1(.)) * 16 sqrt(N) for
    noise of standard deviation 16, read as the two-sided alpha-quantile (a fraction of about alpha of

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(HERE, "libeggroll.so")
 
 EGG_OK, EGG_EINVAL, EGG_EUNSUPPORTED, EGG_EHIP, EGG_ENOMEM = 0, -1, -2, -3, -4
 EGG_F32, EGG_BF16, EGG_I8, EGG_U32 = 0, 1, 2, 3
-EGG_NORMAL, EGG_UNIFORM_INT, EGG_RAW = 0, 1, 2
+EGG_NORMAL, EGG_UNIFORM_INT, EGG_RAW, EGG_NORMAL_INT16 = 0, 1, 2, 3
+EGG_INT_NOISE_NORMAL16 = -16
 EGG_ACT_NONE, EGG_ACT_GELU = 0, 1
 
 EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_last_error",
@@ -22,7 +23,7 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read",
-           "eggroll_scratch_generation", "eggroll_trim", "eggroll_set_conservative_waits", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
+           "eggroll_scratch_generation", "eggroll_trim", "eggroll_set_conservative_waits", "eggroll_normal_int_table", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
            "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_token_loglik_bf16",
            "eggroll_mlp_stack_forward", "eggroll_mlp_stack_update", "eggroll_decoder_forward", "eggroll_decoder_update"]
 
@@ -121,6 +122,8 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_scratch_generation.restype = ctypes.c_uint64
     lib.eggroll_set_conservative_waits.argtypes = [vp, i32]
     lib.eggroll_set_conservative_waits.restype = i32
+    lib.eggroll_normal_int_table.argtypes = [vp]
+    lib.eggroll_normal_int_table.restype = None
     lib.eggroll_trim.argtypes = [vp]
     lib.eggroll_trim.restype = i32
     lib.eggroll_perturbed_forward_add.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp, vp]
@@ -168,6 +171,14 @@ def _ptr(t):
 
 def eggroll_default_scale(population: int, sigma: float, rank: int) -> float:
     return float(load_library().eggroll_default_scale(population, sigma, rank))
+
+
+def eggroll_normal_int_table():
+    """The 65536-entry int8 table of the paper's integer noise, as the library computes it on the host (numpy array)."""
+    import numpy as np
+    out = np.empty(65536, np.int8)
+    load_library().eggroll_normal_int_table(out.ctypes.data_as(ctypes.c_void_p))
+    return out
 
 
 def eggroll_int_threshold(alpha: float, n_terms: int, noise_std: float) -> int:

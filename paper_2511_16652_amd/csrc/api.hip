@@ -180,6 +180,37 @@ egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, 
     return forward_linear(c, key, *shape, io_dtype, y_dtype, sigma, act, W, X, Y, A_cache, B_cache, R_in, t_fixed);
 }
 
+// z >= 0 with P(|Z| >= z) = erfc(z / sqrt 2) = alpha, 0 < alpha < 1: Newton's method on g(z) = log erfc(z / sqrt 2) - log alpha,
+// which is concave and decreasing, so the iteration from z = 0 increases monotonically to the root
+double two_sided_quantile(double alpha)
+{
+    const double la = log(alpha), rs2 = 0.70710678118654752440, c = 0.79788456080286535588;  // sqrt(2/pi)
+    double z = 0.0;
+    for (int it = 0; it < 200; ++it) {
+        const double q = erfc(z * rs2);
+        const double step = (log(q) - la) * q / (c * exp(-0.5 * z * z));  // -g/g', g' = -c exp(-z^2/2) / q
+        z += step;
+        if (fabs(step) <= 1e-16 * (1.0 + z)) break;
+    }
+    return z;
+}
+
+// The paper's integer noise (App. "Adding EGGROLL Perturbations": int8 values round(16 z), z ~ N(0,1), drawn from a
+// pre-generated table that is indexed at random so that no floating point runs on the accelerator).  Table of 2^16
+// entries indexed by 16 random bits: entry k is the value at the midpoint of the k-th of 65536 equal-probability cells,
+// T[k] = round(16 Phi^-1((k + 1/2) / 65536)), rounded half away from zero and mirrored so that T[65535 - k] = -T[k]
+// exactly (zero mean, symmetric: Assumption 1).  The largest magnitude is 69.
+void normal_int_table(int8_t* out)
+{
+    for (int k = 32768; k < 65536; ++k) {
+        const double q = (65535.5 - (double)k) / 65536.0;          // upper-tail probability of the cell midpoint
+        const long v = lround(16.0 * two_sided_quantile(2.0 * q));  // P(|Z| >= z) = 2 q
+        const int8_t t = (int8_t)(v > 127 ? 127 : v);
+        out[k] = t;
+        out[65535 - k] = (int8_t)-t;
+    }
+}
+
 }  // namespace egg
 
 using namespace egg;
@@ -215,7 +246,7 @@ egg_status eggroll_destroy(eggroll_ctx* c)
     if (!c) return EGG_EINVAL;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut, &c->model, &c->model_g};
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut, &c->norm_tab, &c->model, &c->model_g};
     for (auto* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& b : c->retired) (void)hipFree(b.p);
@@ -282,9 +313,10 @@ egg_status eggroll_noise_gen(eggroll_ctx* c, egg_key key, const egg_shape* shape
     if (s != EGG_OK) return s;
     if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
     const bool ok = (dist == EGG_NORMAL && (dtype == EGG_F32 || dtype == EGG_BF16)) ||
-                    (dist == EGG_UNIFORM_INT && dtype == EGG_I8) || (dist == EGG_RAW && dtype == EGG_U32);
+                    ((dist == EGG_UNIFORM_INT || dist == EGG_NORMAL_INT16) && dtype == EGG_I8) || (dist == EGG_RAW && dtype == EGG_U32);
     if (!ok) return fail(c, EGG_EUNSUPPORTED, "noise_gen: dist %d with dtype %d", (int)dist, (int)dtype);
-    if (dist == EGG_UNIFORM_INT && (int_bound < 0 || int_bound > 127)) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (dist == EGG_UNIFORM_INT && !valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (dist == EGG_NORMAL_INT16) int_bound = EGG_INT_NOISE_NORMAL16;
     if ((A_out && !aligned16(A_out)) || (B_out && !aligned16(B_out))) return fail(c, EGG_EINVAL, "outputs must be 16-byte aligned");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     if (A_out) {
@@ -328,11 +360,11 @@ egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_s
     if (shape->d_out != shape->d_in && steps > 1) return fail(c, EGG_EUNSUPPORTED, "more than one step needs a square matrix");
     if (shape->d_out != shape->d_in && H_in == H_out) return fail(c, EGG_EINVAL, "H_in and H_out may alias only for a square matrix");
     if (shape->d_in % 16 || shape->d_out % 16) return fail(c, EGG_EUNSUPPORTED, "d_out and d_in must be multiples of 16");
-    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (!valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127] (and not EGG_INT_NOISE_NORMAL16)");
     if (corr_shift < 0 || corr_shift > 31 || out_shift < 0 || out_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
     if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");
     // int32 accumulators: |acc| <= d*127^2, |dot * A| <= d*127*bound^2
-    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * noise_max(int_bound) * noise_max(int_bound) > 0x7FFFFFFFLL)
         return fail(c, EGG_EUNSUPPORTED, "d too large for int32 accumulation");
     if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
@@ -357,10 +389,10 @@ egg_status eggroll_gru_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, i
     if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
     if (shape->d_out != shape->d_in) return fail(c, EGG_EUNSUPPORTED, "the cell's matrices are square");
     if (shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "D must be a multiple of 16");
-    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (!valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127] (and not EGG_INT_NOISE_NORMAL16)");
     if (corr_shift < 0 || corr_shift > 31 || out_shift < 0 || out_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
     if (steps < 1) return fail(c, EGG_EINVAL, "steps must be >= 1");
-    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+    if ((int64_t)shape->d_in * 127 * 127 + (int64_t)shape->d_in * 127 * noise_max(int_bound) * noise_max(int_bound) > 0x7FFFFFFFLL)
         return fail(c, EGG_EUNSUPPORTED, "D too large for int32 accumulation");
     if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
@@ -391,7 +423,7 @@ static egg_status validate_model_shape(eggroll_ctx* c, egg_key key, const egg_sh
     if ((uint64_t)key.layer + noise_layers > 0x80000000ull) return fail(c, EGG_EINVAL, "noise layers must stay below 2^31");
     if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
     if (shape->d_out != shape->d_in) return fail(c, EGG_EINVAL, "d_out and d_in must both be the width D");
-    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (!valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127] (and not EGG_INT_NOISE_NORMAL16)");
     if (corr_shift < 0 || corr_shift > 31) return fail(c, EGG_EINVAL, "shift outside [0,31]");
     if (shape->member_count > (int64_t(1) << 31) - 512) return fail(c, EGG_EUNSUPPORTED, "too many rows in one call");
     return EGG_OK;
@@ -434,7 +466,7 @@ egg_status eggroll_egg_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* 
         if (a < b + state_bytes && b < a + state_bytes) return fail(c, EGG_EINVAL, "S_in and S_out must not overlap");
     }
     // int32 accumulators of the widest contraction (4 D terms)
-    if ((int64_t)4 * D * 127 * 127 + (int64_t)4 * D * 127 * int_bound * int_bound > 0x7FFFFFFFLL)
+    if ((int64_t)4 * D * 127 * 127 + (int64_t)4 * D * 127 * noise_max(int_bound) * noise_max(int_bound) > 0x7FFFFFFFLL)
         return fail(c, EGG_EUNSUPPORTED, "D too large for int32 accumulation");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     return launch_egg_forward_i8(c, key, *shape, layers, int_bound, corr_shift, steps, *model, tokens, S_in, S_out, logits);
@@ -463,13 +495,13 @@ egg_status eggroll_egg_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* s
     if (shape->d_out != shape->d_in) return fail(c, EGG_EINVAL, "d_out and d_in must both be the width D");
     const int D = shape->d_in;
     if (D % 16) return fail(c, EGG_EUNSUPPORTED, "D must be a multiple of 16");
-    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (!valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127] (and not EGG_INT_NOISE_NORMAL16)");
     if (threshold < 0) return fail(c, EGG_EINVAL, "threshold must be >= 0");
     if (!fitness || !model || !model->emb || !model->head) return fail(c, EGG_EINVAL, "NULL pointer argument");
     if (layers > 0 && (!model->gru_w || !model->mlp1 || !model->mlp2)) return fail(c, EGG_EINVAL, "NULL pointer argument");
     if (!aligned16(model->emb) || !aligned16(model->head) || !aligned16(model->gru_w) || !aligned16(model->mlp1) || !aligned16(model->mlp2))
         return fail(c, EGG_EINVAL, "model pointers must be 16-byte aligned");
-    if (shape->member_count * (int64_t)int_bound * int_bound > 0x7FFFFFFFLL)
+    if (shape->member_count * (int64_t)noise_max(int_bound) * noise_max(int_bound) > 0x7FFFFFFFLL)
         return fail(c, EGG_EUNSUPPORTED, "population too large for int32 accumulation");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     auto one = [&](uint32_t layer, int d_out, int d_in, int8_t* theta) {
@@ -530,10 +562,10 @@ egg_status eggroll_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape
     if (!aligned16(theta) || !aligned16(E_out)) return fail(c, EGG_EINVAL, "theta and E_out must be 16-byte aligned");
     if (shape->rank != 1) return fail(c, EGG_EUNSUPPORTED, "integer path is rank 1");
     if (shape->d_out % 16 || shape->d_in % 16) return fail(c, EGG_EUNSUPPORTED, "d_out and d_in must be multiples of 16");
-    if (int_bound < 0 || int_bound > 127) return fail(c, EGG_EINVAL, "int_bound outside [0,127]");
+    if (!valid_int_bound(int_bound)) return fail(c, EGG_EINVAL, "int_bound outside [0,127] (and not EGG_INT_NOISE_NORMAL16)");
     if (threshold < 0) return fail(c, EGG_EINVAL, "threshold must be >= 0");
     // int32 E: |E| <= N * bound^2
-    if (shape->member_count * (int64_t)int_bound * int_bound > 0x7FFFFFFFLL)
+    if (shape->member_count * (int64_t)noise_max(int_bound) * noise_max(int_bound) > 0x7FFFFFFFLL)
         return fail(c, EGG_EUNSUPPORTED, "population too large for int32 accumulation");
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     return launch_update_i8(c, make_stream_key(key.seed, key.step, key.layer, 0),
@@ -541,20 +573,16 @@ egg_status eggroll_update_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape
                             theta, E_out);
 }
 
+void eggroll_normal_int_table(int8_t* out)
+{
+    if (out) egg::normal_int_table(out);
+}
+
 int64_t eggroll_int_threshold(double alpha, int64_t n_terms, double noise_std)
 {
     if (!(alpha > 0.0)) return INT64_MAX;
     if (alpha >= 1.0 || n_terms <= 0 || !(noise_std > 0.0)) return 0;
-    // z with erfc(z / sqrt 2) = alpha: Newton's method on g(z) = log erfc(z / sqrt 2) - log alpha, which is
-    // concave and decreasing, so the iteration from z = 0 increases monotonically to the root
-    const double la = log(alpha), rs2 = 0.70710678118654752440, c = 0.79788456080286535588;  // sqrt(2/pi)
-    double z = 0.0;
-    for (int it = 0; it < 200; ++it) {
-        const double q = erfc(z * rs2);
-        const double step = (log(q) - la) * q / (c * exp(-0.5 * z * z));  // -g/g', g' = -c exp(-z^2/2) / q
-        z += step;
-        if (fabs(step) <= 1e-16 * (1.0 + z)) break;
-    }
+    const double z = two_sided_quantile(alpha);
     const int64_t first = (int64_t)(noise_std * z);  // truncation
     const int64_t second = (int64_t)llround(noise_std * sqrt((double)n_terms));
     return first * second;

@@ -36,6 +36,7 @@ struct eggroll_ctx {
     Buf gru;          // integer GRU cell: factors of its four matrices, gate and matmul intermediates
     Buf zero_page;    // 256 zero bytes (K-tail loads of the GEMM core)
     Buf lut;          // integer log-likelihood: EXP2 table and the thresholds that invert LOG2
+    Buf norm_tab;     // integer normal noise: the 65536-entry table round(16 z) (uploaded on first use)
     Buf model;        // multi-layer drivers: activations of one chunk of members
     Buf model_g;      // multi-layer updates: fp32 G of the matrix being updated
     // buffers that a later, larger call outgrew: kept until eggroll_trim / eggroll_destroy, because work already
@@ -82,6 +83,12 @@ inline const char* shaped_name(eggroll_ctx* c, const char* base, int d_out, int 
     snprintf(buf, sizeof buf, "%s[%dx%d]", base, d_out, d_in);
     return c->shaped_names.emplace(buf, 0).first->first.c_str();
 }
+
+// int_bound arguments: a bound in [0, 127] (uniform integers) or EGG_INT_NOISE_NORMAL16 (the table of round(16 z))
+inline bool valid_int_bound(int b) { return (b >= 0 && b <= 127) || b == EGG_INT_NOISE_NORMAL16; }
+// largest |value| the selected integer noise can take: 16 * Phi^-1(1 - 2^-17) rounds to 69 for the table
+inline int noise_max(int b) { return b == EGG_INT_NOISE_NORMAL16 ? 69 : b; }
+void normal_int_table(int8_t* out);  // host: fills the 65536 entries
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -532,11 +532,12 @@ static egg_status launch_i8_stream(eggroll_ctx* c, const int8_t* W, int d_out, c
 static egg_status dispatch_i8(eggroll_ctx* c, const int8_t* W, int d_out, int d_in, int64_t rows, int int_bound, const Operand& Q,
                               const I8Args& ea)
 {
-    // |u . B_i| <= d_in * 127 * int_bound: below 2^23 the correction product fits the 24-bit multiplier
-    const bool dot24 = (int64_t)d_in * 127 * int_bound < (int64_t(1) << 23);
+    // |u . B_i| <= d_in * 127 * (largest noise magnitude): below 2^23 the correction product fits the 24-bit multiplier
+    const int nmax = noise_max(int_bound);
+    const bool dot24 = (int64_t)d_in * 127 * nmax < (int64_t(1) << 23);
     // the streaming kernel folds the two shifts into one: needs |acc| 2^cs + |dot A| inside int32 and clamp bounds that fit
     const int sh = ea.corr_shift + ea.out_shift;
-    const bool fold_ok = sh <= 23 && (((int64_t)d_in * 127 * 127) << ea.corr_shift) + (int64_t)d_in * 127 * int_bound * int_bound < (int64_t(1) << 31);
+    const bool fold_ok = sh <= 23 && (((int64_t)d_in * 127 * 127) << ea.corr_shift) + (int64_t)d_in * 127 * nmax * nmax < (int64_t(1) << 31);
     if (d_in == 256 && rows >= 2048 && fold_ok)
     {
         const int mode = ea.gate | (ea.dots_next ? 4 : 0);

@@ -130,6 +130,32 @@ def test_forward_65536_members_in_full(ctx):
     assert (logits == want).all()
 
 
+def test_forward_with_the_papers_integer_noise(ctx):
+    """The integer model with the paper's own noise setting: round(16 z) factors from the table and the correction
+    shifted by 4 + sigma_hat = 8 (App. "Adding EGGROLL Perturbations"), antithetic pairs, bit for bit; and its update."""
+    import torch
+    D, L, N, T = 256, 2, 4096, 2
+    P = inputs.egg_model(D, L, 4300)
+    tok = inputs.egg_tokens(T, N, 4301)
+    S = np.random.default_rng(4302).integers(-60, 61, (L, N, D)).astype(np.int8)
+    logits, S_out = run_model(ctx, P, D, L, N, T, 0, 1, tok, S, bound=eb.EGG_INT_NOISE_NORMAL16, cs=8)
+    want, S_want = oracle.egg_forward_i8(SEED, STEP, LAYER, 0, N, D, L, oracle.BOUND_NORMAL16, 8, P, tok, S, antithetic=True)
+    assert (S_out == S_want).all() and (logits == want).all()
+    plain, _ = oracle.egg_forward_i8(SEED, STEP, LAYER, 0, 64, D, L, 0, 8, P, tok[:, :64], S[:, :64], antithetic=True)
+    assert (want[:, :64] != plain).mean() > 0.02          # the perturbation is visible in the logits
+    pairs = N // 2
+    F = np.random.default_rng(4303).choice(np.array([-1, 0, 1], np.int8), pairs)
+    thr = eb.eggroll_int_threshold(0.25, pairs, 16.0)
+    model = {k: dev(v) for k, v in P.items()}
+    ctx.eggroll_egg_update_i8(eb.make_key(SEED, STEP, LAYER), eb.make_shape(0, pairs, 1, D, D, 1), L, eb.EGG_INT_NOISE_NORMAL16,
+                              dev(F), thr, model)
+    torch.cuda.synchronize()
+    t_ref, _ = oracle.update_i8(SEED, STEP, LAYER + 1 + 4, 0, pairs, 4 * D, D, oracle.BOUND_NORMAL16, F, thr, P["mlp1"][0])
+    assert (model["mlp1"][0].cpu().numpy() == t_ref).all()
+    t_ref, _ = oracle.update_i8(SEED, STEP, LAYER, 0, pairs, 256, D, oracle.BOUND_NORMAL16, F, thr, P["emb"])
+    assert (model["emb"].cpu().numpy() == t_ref).all()
+
+
 def test_forward_noise_matters_and_pairs_mirror(ctx):
     # without noise members with the same token history agree; with antithetic noise the two members of
     # a pair differ from each other and from the unperturbed run

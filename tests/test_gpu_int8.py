@@ -98,3 +98,39 @@ def test_rectangular_single_step_bit_exact(ctx, d_out, d_in, N, anti):
     with pytest.raises(eb.EggrollError):   # a rectangular matrix cannot be iterated
         ctx.eggroll_perturbed_forward_i8(eb.make_key(3, 1, 4), eb.make_shape(6, N, 1, d_out, d_in, 1), 8, 4, 7, 2,
                                          torch.from_numpy(W).cuda(), torch.from_numpy(H).cuda(), out)
+
+
+def test_table_noise_bit_exact(ctx):
+    """The paper's own integer noise (EGG_INT_NOISE_NORMAL16) through noise_gen, the perturbed matmul at the paper's
+    shifts (corr_shift = 4 + sigma_hat = 8), a short recurrence, and the integer update."""
+    import torch
+    T16 = eb.EGG_INT_NOISE_NORMAL16
+    n, d_out, d_in = 9, 130, 77
+    A = torch.empty((n, d_out, 1), dtype=torch.int8, device="cuda")
+    B = torch.empty((n, d_in, 1), dtype=torch.int8, device="cuda")
+    ctx.eggroll_noise_gen(eb.make_key(3, 1, 4), eb.make_shape(2 ** 32 - 20, n, 1, d_out, d_in, 1), eb.EGG_I8, eb.EGG_NORMAL_INT16, 0, A, B)
+    a, b = A.cpu().numpy(), B.cpu().numpy()
+    for m in range(n):
+        assert (a[m].reshape(-1) == oracle.noise_int(3, 1, 4, 0, 2 ** 32 - 20 + m, 0, d_out, oracle.BOUND_NORMAL16)).all()
+        assert (b[m].reshape(-1) == oracle.noise_int(3, 1, 4, 1, 2 ** 32 - 20 + m, 0, d_in, oracle.BOUND_NORMAL16)).all()
+    for d, N, steps, anti in ((256, 4096, 3, 0), (1024, 600, 2, 1), (96, 130, 4, 0)):
+        wl = inputs.make_int8("t", d, N, steps, 9 + d)
+        W, H = torch.from_numpy(wl.W).cuda(), torch.from_numpy(wl.H0).cuda()
+        out = torch.empty_like(H)
+        ctx.eggroll_perturbed_forward_i8(eb.make_key(0, 0, 5), eb.make_shape(0, N, 1, d, d, 1, antithetic=anti), T16, 8, 4 + int(np.log2(d)) // 2,
+                                         steps, W, H, out)
+        torch.cuda.synchronize()
+        ref = oracle.forward_i8(0, 0, 5, 0, N, d, oracle.BOUND_NORMAL16, 8, 4 + int(np.log2(d)) // 2, steps, wl.W, wl.H0, antithetic=bool(anti))
+        assert (out.cpu().numpy() == ref).all(), (d, N)
+        assert (ref != oracle.forward_i8(0, 0, 5, 0, N, d, 0, 8, 4 + int(np.log2(d)) // 2, steps, wl.W, wl.H0)).mean() > 0.01   # the noise matters
+    N, d = 1000, 128
+    wl = inputs.make_int8("u", d, N, 1, 77)
+    F = np.random.default_rng(4).choice(np.array([-1, 0, 1], np.int8), N)
+    tau = eb.eggroll_int_threshold(0.3, N, 16.0)
+    theta = torch.from_numpy(wl.W.copy()).cuda()
+    E = torch.empty((d, d), dtype=torch.int32, device="cuda")
+    ctx.eggroll_update_i8(eb.make_key(0, 0, 5), eb.make_shape(0, N, 1, d, d, 1), T16, torch.from_numpy(F).cuda(), tau, theta, E)
+    torch.cuda.synchronize()
+    t_ref, e_ref = oracle.update_i8(0, 0, 5, 0, N, d, d, oracle.BOUND_NORMAL16, F, tau, wl.W)
+    assert (E.cpu().numpy() == e_ref).all() and (theta.cpu().numpy() == t_ref).all()
+    assert 0.15 < (t_ref != wl.W).mean() < 0.45
