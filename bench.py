@@ -87,15 +87,14 @@ def prewarm(fn, seconds=0.4):
 
 
 def timed(fn, steps, warmup):
-    import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        fn()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    """Median seconds per call over `steps` calls, each bracketed by HIP events on the current stream (the stream the
+    library's context was created on).  The full {"mean", "median", "min"} record of the last call is kept in LAST_TIMING."""
+    global LAST_TIMING
+    LAST_TIMING = timed_events(fn, steps, warmup)
+    return LAST_TIMING["median"]
+
+
+LAST_TIMING = None
 
 
 def timed_events(fn, steps, warmup):
@@ -531,8 +530,12 @@ def linear_workload(args):
 
     prewarm(step_cached)
     t_cached = timed(step_cached, args.steps, args.warmup)
+    rec = {"step_cached": LAST_TIMING}
     t_regen = timed(step_regen, args.steps, args.warmup)
+    rec["step_regenerated"] = LAST_TIMING
     t_panel = timed(step_panel, args.steps, args.warmup) if panel_ok else float("inf")
+    if panel_ok:
+        rec["step_panel"] = LAST_TIMING
     # the timed step is whichever of the flows is fastest on this workload; all are reported
     step, t_step, flow = min(((step_cached, t_cached, "cached"), (step_regen, t_regen, "regenerated"),
                               (step_panel, t_panel, "B kept as packed panel")), key=lambda x: x[1])
@@ -605,6 +608,8 @@ def linear_workload(args):
                "update": 1e3 * t_upd, "update_regenerating": 1e3 * t_upd_nc, "torch_matmul": 1e3 * t_mm,
                "step_cached": 1e3 * t_cached, "step_regenerated": 1e3 * t_regen,
                "step_panel": 1e3 * t_panel if panel_ok else None},
+        "timing": {"method": "HIP events around each step on the library's stream; ms figures are medians", "steps_s": rec},
+        "measured_ceilings": measured_ceilings(),
         "roofline": {"bound": "mfma", "kernel": gemm_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak,
                      "traffic": profiled_traffic(args.workload, ("MmaBf16" if wl.dtype == "bf16" else "MmaF32", "FwdEpi"))},
