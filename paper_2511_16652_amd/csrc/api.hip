@@ -231,6 +231,7 @@ egg_status eggroll_create(eggroll_ctx** out, int device, void* hip_stream)
     if (!c) return EGG_ENOMEM;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    if (prop.multiProcessorCount > 0) c->compute_units = prop.multiProcessorCount;
     egg_status s = reserve(c, c->zero_page, 256);
     if (s == EGG_OK && hipMemsetAsync(c->zero_page.p, 0, 256, c->stream) != hipSuccess) s = EGG_EHIP;
     if (s != EGG_OK) {

@@ -18,6 +18,7 @@ struct eggroll_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     std::string err;
+    int compute_units = 256;  // of the device (grid size of persistent kernels)
     int cache_layout = 0;  // egg_cache_layout of the forward/update caches
     bool conservative_waits = false;  // diagnostic: kernels with counted s_waitcnt wait for everything instead
 

@@ -38,36 +38,50 @@ __device__ __forceinline__ void gelu_bf16_grade4(float (&y)[4])
     for (int e = 0; e < 4; ++e) y[e] *= fmaf(xc[e], p[e], 0.5f);
 }
 
+// Arguments of the forward epilogue (the same for every instantiation).
+struct FwdArgs {
+    StreamKey ka;
+    uint32_t member_begin;
+    int S, d_out;
+    float c;  // sigma / sqrt(r); 0 switches the correction off
+    int act, y_bf16;
+    void* Y;
+    const float* t;
+    void* A_buf;  // REGEN: optional cache to fill; otherwise the materialised factors to read
+    int wtm_pitch;  // RowStager2B::pitch of the launched wave tile
+    int stage_a;    // !REGEN: the tile's slice of A fits the LDS tail and is staged there
+    int mma_corr;   // !REGEN, bf16, S % CORR_COLS == 0: the correction is folded in by one extra MFMA per block
+    int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
+    const void* resid;  // optional [R][d_out] of the output dtype, added after the activation (residual stream)
+};
+
 // Where the lane's factor entries A_i[m..m+3][0..RANK-1] come from:
 //   REGEN  (rank 1, one row per member): regenerated in registers from the counter stream -- each
 //          entry of A is needed by exactly one lane of the grid, so nothing is stored or re-read;
 //   otherwise read from a materialised [member][d_out][RANK] buffer (written just before by the
 //          noise kernel, the caller's A_cache if one was given): with S rows per member the buffer
 //          is RANK/S of the output size, and every entry is generated once instead of S times.
-template <bool BF16, int RANK, bool REGEN>
+// BLK: rows/columns of the MFMA block the kernel is built from (a lane owns column lane & (BLK-1) of a block).
+// LEAN != 0: a store-only epilogue for bf16 outputs whose correction is either off (c == 0) or already folded into
+// the accumulators by extra_mma; the activation and the residual are fixed at compile time (bit 1: GELU, bit 2:
+// residual).  The general epilogue decides all of that at run time and carries the code of every case (counter RNG,
+// erff, staged and direct factor reads) 32 times per wave: about 80 KB, more than the instruction cache that two
+// compute units share, and it runs once per tile -- measured at 13 us behind a 50 us main loop, against 5 us for
+// the lean form.
+enum { LEAN_ON = 1, LEAN_GELU = 2, LEAN_RESID = 4 };
+template <bool BF16, int RANK, bool REGEN, int BLK = 32, int LEAN = 0>
 struct FwdEpi {
+    static_assert(LEAN == 0 || (BF16 && !REGEN), "the lean epilogue stores bf16 and regenerates nothing");
     typedef float value_t;
-    struct Args {
-        StreamKey ka;
-        uint32_t member_begin;
-        int S, d_out;
-        float c;  // sigma / sqrt(r); 0 switches the correction off
-        int act, y_bf16;
-        void* Y;
-        const float* t;
-        void* A_buf;  // REGEN: optional cache to fill; otherwise the materialised factors to read
-        int wtm_pitch;  // RowStager2B::pitch of the launched wave tile
-        int stage_a;    // !REGEN: the tile's slice of A fits the LDS tail and is staged there
-        int mma_corr;   // !REGEN, bf16, S % 32 == 0: the correction is folded in by one extra MFMA per block
-        int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
-        const void* resid;  // optional [R][d_out] of the output dtype, added after the activation (residual stream)
-    };
+    typedef FwdArgs Args;
     static constexpr int A_STAGE_BYTES = 48 * 1024;
     static constexpr bool REGEN_MODE = REGEN;
     static constexpr bool IS_BF16 = BF16;
     static constexpr int RANK_ELEMS_BYTES = RANK * (BF16 ? 2 : 4);
     const Args a;
-    RowStager2B sty, sta;  // staging slices: bf16 Y block, and (REGEN, bf16) the A_i block kept for the update
+    // staging slices: bf16 Y block, and (REGEN, bf16) the A_i block kept for the update
+    typedef std::conditional_t<LEAN != 0, RowStagerSwz, RowStager2B> stager_t;
+    stager_t sty, sta;
     float tc[RANK];
     uint32_t member;
     int64_t ml_member;
@@ -75,22 +89,30 @@ struct FwdEpi {
     int64_t first_member = 0;
     int tile_m0 = 0, tile_rows = 0;
 
-    // When every 32-column block belongs to one member (S a multiple of 32), the rank-r correction of
-    // a 32x32 block is itself a small GEMM, Y[m][n] += sum_l A_i[m][l] * (c t[n][l]), and one more
-    // 32x32x16 MFMA per block adds it to the accumulators: its 16 K-slots hold A_i[m][0..r) twice and
+    // When every column block belongs to one member (S a multiple of CORR_COLS), the rank-r correction of
+    // a block is itself a small GEMM, Y[m][n] += sum_l A_i[m][l] * (c t[n][l]), and one more
+    // MFMA per block adds it to the accumulators: 16 of its K-slots hold A_i[m][0..r) twice and
     // the fp32 value c*t split into two bf16 halves (hi, then lo = the rounding remainder), so the
     // products stay accurate to about 2^-16.  The epilogue that follows is then the plain store.
     static constexpr int AW = RANK >= 2 ? RANK / 2 : 1;  // 32-bit words of one A_i[m][0..RANK) row in bf16
-    static constexpr bool PREFETCH = RANK <= 4;  // rank 8 would not fit the register budget: it loads late
-    uint32_t pf_a[PREFETCH ? 4 : 1][4][AW];   // prefetched A rows of the lane, per (row block, column block)
-    float pf_t[4][RANK];                      // prefetched t of the lane's columns
+    // register prefetch (general epilogue); rank 8 would not fit the register budget: it loads late.  The store-only
+    // epilogue parks the operands in its LDS slice instead (see prefetch).
+    static constexpr bool PREFETCH = RANK <= 4 && LEAN == 0;
+    static constexpr int LDS_T = 0, LDS_A = 2048;  // byte offsets of t[64][RANK] fp32 and A_i[128][RANK] bf16 in the slice
+    // prefetched A rows of the lane, per (row block, group of CORR_COLS columns that share one member), and the
+    // prefetched t of the lane's columns, per column block.  With 16x16 blocks a wave tile has twice the row
+    // blocks; one member per 64 columns (the width of every wave tile launched here) keeps the register count.
+    static constexpr int CORR_COLS = BLK == 32 ? 32 : 64;
+    static constexpr int PF_MB = 128 / BLK, PF_NB = 128 / BLK, PF_NG = 128 / CORR_COLS;
+    uint32_t pf_a[PREFETCH ? PF_MB : 1][PF_NG][AW];
+    float pf_t[PF_NB][RANK];
 
     template <int NB>
     __device__ __forceinline__ void fetch_t(int nw0, int lane, int n_rows)
     {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const int nc = min(nw0 + j * 32 + (lane & 31), n_rows - 1);
+            const int nc = min(nw0 + j * BLK + (lane & (BLK - 1)), n_rows - 1);
 #pragma unroll
             for (int l = 0; l < RANK; ++l) pf_t[j][l] = a.t[(int64_t)nc * RANK + l];
         }
@@ -109,14 +131,36 @@ struct FwdEpi {
     template <int MB, int NB>
     __device__ __forceinline__ void prefetch(int mw0, int nw0, int lane, int n_rows)
     {
-        if constexpr (!REGEN && BF16 && PREFETCH) {
-            static_assert(MB <= 4 && NB <= 4, "prefetch storage");
+        if constexpr (LEAN != 0 && RANK <= 8) {
+            // Store-only epilogue: the wave tile (128 rows x 64 columns, one member) needs t[nw0..+64)[0..r) and
+            // A_i[mw0..+128)[0..r): two contiguous runs of 256 r bytes, brought into the wave's staging slice by 2 r
+            // direct-to-LDS loads of one dword per lane.  No register holds them through the last stage; extra_mma
+            // reads its fragments from the slice.  (The slice is idle here: the previous tile's flush is behind us.)
+            static_assert(MB * BLK == 128 && NB * BLK == 64 && BLK == 16, "slice layout is that of a 128 x 64 wave tile");
+            if (!a.mma_corr || nw0 >= n_rows || mw0 >= a.d_out) return;
+            const int64_t member_l = (int64_t)nw0 / a.S;
+            const uint32_t* tsrc = (const uint32_t*)(a.t + (int64_t)nw0 * RANK);
+            const uint32_t* asrc = (const uint32_t*)((const uint16_t*)a.A_buf + (member_l * a.d_out + mw0) * RANK);
+            const int t_last = min(n_rows - nw0, 64) * RANK - 1;           // last valid dword of the t run
+            const int a_last = min(a.d_out - mw0, 128) * RANK / 2 - 1;     // of the A run (d_out is a multiple of 4)
+#pragma unroll
+            for (int k = 0; k < RANK; ++k) {
+                __builtin_amdgcn_global_load_lds((egg_glb_void*)(tsrc + min(k * 64 + lane, t_last)),
+                                                 (egg_lds_void*)(sty.base + LDS_T + k * 256), 4, 0, 0);
+            }
+#pragma unroll
+            for (int k = 0; k < RANK; ++k) {
+                __builtin_amdgcn_global_load_lds((egg_glb_void*)(asrc + min(k * 64 + lane, a_last)),
+                                                 (egg_lds_void*)(sty.base + LDS_A + k * 256), 4, 0, 0);
+            }
+        } else if constexpr (!REGEN && BF16 && PREFETCH) {
+            static_assert(MB <= PF_MB && NB <= PF_NB && NB * BLK <= PF_NG * CORR_COLS, "prefetch storage");
             if (!a.mma_corr) return;
             fetch_t<NB>(nw0, lane, n_rows);
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
+            for (int g = 0; g < (NB * BLK + CORR_COLS - 1) / CORR_COLS; ++g)
 #pragma unroll
-                for (int i = 0; i < MB; ++i) fetch_a(pf_a[i][j], mw0 + i * 32 + (lane & 31), nw0 + j * 32, n_rows);
+                for (int i = 0; i < MB; ++i) fetch_a(pf_a[i][g], mw0 + i * BLK + (lane & (BLK - 1)), nw0 + g * CORR_COLS, n_rows);
         }
     }
 
@@ -125,8 +169,17 @@ struct FwdEpi {
     {
         if constexpr (!REGEN && BF16 && RANK <= 8) {
             if (!a.mma_corr) return;
-            if constexpr (!PREFETCH) fetch_t<NB>(nw0, lane, n_rows);
-            const int half = lane >> 5;  // K-slots 0..7 (hi part of c*t) or 8..15 (lo part)
+            if constexpr (LEAN != 0) {
+                if (nw0 >= n_rows || mw0 >= a.d_out) return;  // nothing of this wave tile is stored
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int l = 0; l < RANK; ++l) pf_t[j][l] = *(const float*)(sty.base + LDS_T + ((j * BLK + (lane & (BLK - 1))) * RANK + l) * 4);
+            } else if constexpr (!PREFETCH) {
+                fetch_t<NB>(nw0, lane, n_rows);
+            }
+            // K-slots 0..7 (hi part of c*t), 8..15 (lo part); the 16x16x32 block has 16 more, left at zero
+            const int half = lane / BLK;
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 uint32_t tb[4] = {0u, 0u, 0u, 0u};
@@ -135,7 +188,7 @@ struct FwdEpi {
                 for (int l = 0; l < RANK; ++l) {
                     const float v = a.c * pf_t[j][l];
                     const float hi = round_bf16(v);
-                    ct[l] = half ? v - hi : hi;
+                    ct[l] = half == 0 ? hi : (half == 1 ? v - hi : 0.f);
                 }
 #pragma unroll
                 for (int l = 0; l < RANK; l += 2) tb[l >> 1] = pack_bf16x2(ct[l], l + 1 < RANK ? ct[l + 1] : 0.f);
@@ -143,12 +196,18 @@ struct FwdEpi {
 #pragma unroll
                 for (int i = 0; i < MB; ++i) {
                     u32x4 afrag = {0u, 0u, 0u, 0u};
-                    if constexpr (PREFETCH) {
+                    if constexpr (LEAN != 0) {
+                        const char* ar = sty.base + LDS_A + (i * BLK + (lane & (BLK - 1))) * RANK * 2;
+                        if constexpr (RANK == 1) afrag[0] = *(const uint16_t*)ar;
+                        else
 #pragma unroll
-                        for (int w = 0; w < AW; ++w) afrag[w] = pf_a[i][j][w];
+                            for (int w = 0; w < AW; ++w) afrag[w] = *(const uint32_t*)(ar + 4 * w);
+                    } else if constexpr (PREFETCH) {
+#pragma unroll
+                        for (int w = 0; w < AW; ++w) afrag[w] = pf_a[i][j * BLK / CORR_COLS][w];
                     } else {
                         uint32_t tmp[AW];
-                        fetch_a(tmp, mw0 + i * 32 + (lane & 31), nw0 + j * 32, n_rows);
+                        fetch_a(tmp, mw0 + i * BLK + (lane & (BLK - 1)), nw0 + j * BLK, n_rows);
 #pragma unroll
                         for (int w = 0; w < AW; ++w) afrag[w] = tmp[w];
                     }
@@ -164,7 +223,7 @@ struct FwdEpi {
     template <int NT, int BM, int BN>
     __device__ __forceinline__ bool tile_begin(char* lds_tail, int m0, int n0, int tid, int n_rows)
     {
-        if constexpr (REGEN) {
+        if constexpr (REGEN || LEAN != 0) {
             return false;
         } else {
             if (!a.stage_a || a.c == 0.f || a.mma_corr) return false;
@@ -191,15 +250,17 @@ struct FwdEpi {
     __device__ __forceinline__ int tile_stride() const { return bm_rows; }
 
     // bf16 outputs are staged through LDS; the regenerated bf16 factors too when a cache is kept
-    static constexpr __host__ __device__ int lds_per_wave(int wtm) { return (REGEN && BF16 ? 2 : 1) * RowStager2B::bytes(wtm); }
+    static constexpr __host__ __device__ int lds_per_wave(int wtm) { return (REGEN && BF16 ? 2 : 1) * stager_t::bytes(wtm); }
 
     __device__ __forceinline__ FwdEpi(const Args& a_, char* slice, int lane)
-        : a(a_), sty{slice, lane}, sta{slice + RowStager2B::bytes((a_.wtm_pitch - 16) / 2), lane}
+        : a(a_), sty{slice, lane, lane & (BLK - 1)},
+          sta{slice + (LEAN != 0 ? 0 : RowStager2B::bytes((a_.wtm_pitch - 16) / 2)), lane, lane & (BLK - 1)}
     {
     }
 
     __device__ __forceinline__ void column(int n, bool valid)
     {
+        if constexpr (LEAN != 0) return;
         if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
         member = a.member_begin + (uint32_t)ml_member;
@@ -211,6 +272,18 @@ struct FwdEpi {
     {
         const bool live = valid && m < a.d_out;  // m and d_out are multiples of 4
         float y[4] = {v[0], v[1], v[2], v[3]};
+        if constexpr (LEAN != 0) {
+            if constexpr ((LEAN & LEAN_GELU) != 0) gelu_bf16_grade4(y);
+            if constexpr ((LEAN & LEAN_RESID) != 0) {
+                if (live) {
+                    const uint2 rv = *(const uint2*)((const uint16_t*)a.resid + (int64_t)n * a.d_out + m);
+                    y[0] += bf16_lo(rv.x); y[1] += bf16_hi(rv.x);
+                    y[2] += bf16_lo(rv.y); y[3] += bf16_hi(rv.y);
+                }
+            }
+            sty.put(a.wtm_pitch, ml, pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+            return;
+        }
         if (live && a.c != 0.f && !(!REGEN && a.mma_corr)) {
             float z[4 * RANK];
             const int64_t aoff = (ml_member * a.d_out + m) * RANK;  // element offset of A_i[m][0]
@@ -312,10 +385,10 @@ struct FwdEpi {
     template <int WTM>
     __device__ __forceinline__ void flush(int mw0, int nb0, int n_rows)
     {
-        if (a.y_bf16) sty.template flush<WTM>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
+        if (LEAN != 0 || a.y_bf16) sty.template flush<WTM, BLK>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
         if constexpr (REGEN && BF16) {
             // REGEN means one row per member, so local member index == row index: same addressing as Y
-            if (a.A_buf && a.c != 0.f) sta.template flush<WTM>((uint16_t*)a.A_buf, a.d_out, mw0, nb0, n_rows, a.d_out);
+            if (a.A_buf && a.c != 0.f) sta.template flush<WTM, BLK>((uint16_t*)a.A_buf, a.d_out, mw0, nb0, n_rows, a.d_out);
         }
     }
 };
@@ -324,14 +397,14 @@ template <class MT, int BM, int BN, int WM, int WN, class Epi>
 static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
                               typename Epi::Args ea)
 {
-    ea.wtm_pitch = RowStager2B::pitch(BM / WM);
+    ea.wtm_pitch = Epi::stager_t::pitch(BM / WM);
     auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, false, Epi>;
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     size_t lds = gemm_lds_bytes<BM, BN>();
     size_t epi_lds = (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
     ea.stage_a = 0;
     // (rank <= 8: the 16 K-slots of the extra MFMA hold r factor entries beside the hi and lo halves of c t)
-    ea.mma_corr = (!Epi::REGEN_MODE && Epi::IS_BF16 && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % 32 == 0) ? 1 : 0;
+    ea.mma_corr = (!Epi::REGEN_MODE && Epi::IS_BF16 && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % Epi::CORR_COLS == 0) ? 1 : 0;
     if (!Epi::REGEN_MODE && ea.c != 0.f && !ea.mma_corr) {
         const size_t need = (size_t)(BN / ea.S + 2) * BM * Epi::RANK_ELEMS_BYTES;
         // 16-byte copies: every member slice must start and end on a 16-byte boundary
@@ -352,12 +425,36 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     return check_hip(c, hipGetLastError(), name);
 }
 
+// The persistent kernel for store-only epilogues: one workgroup per compute unit walks the tiles.
+template <class MT, int BM, int BN, int WM, int WN, class Epi>
+static egg_status launch_gemm_persistent(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
+                                         typename Epi::Args ea)
+{
+    ea.wtm_pitch = Epi::stager_t::pitch(BM / WM);
+    auto kern = gemm_nt_persistent_kernel<MT, BM, BN, WM, WN, Epi>;
+    const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
+    const size_t lds = gemm_lds_bytes<BM, BN>() + (size_t)WM * WN * Epi::lds_per_wave(BM / WM);
+    ea.stage_a = 0;
+    ea.mma_corr = (Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % Epi::CORR_COLS == 0) ? 1 : 0;
+    if (ea.c != 0.f && !ea.mma_corr) return fail(c, EGG_EINVAL, "store-only epilogue launched with a correction left to apply");
+    if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, lds, "gemm smem attr");
+    if (st != EGG_OK) return st;
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    if (total > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "too many tiles");
+    const unsigned grid = (unsigned)(total < c->compute_units ? total : c->compute_units);
+    KernelScope ks(c, shaped_name(c, name, P.rows, kchunks * 8));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, c->stream, P, Q, kchunks, tiles_m, tiles_n,
+                       (const char*)c->zero_page.p, ea);
+    return check_hip(c, hipGetLastError(), name);
+}
+
 template <bool BF16, int RANK, bool REGEN>
 static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype yd, float sigma,
                                    egg_act act, const void* W, const void* X, void* Y, const float* t, void* A_buf,
                                    const void* resid)
 {
-    typedef FwdEpi<BF16, RANK, REGEN> Epi;
+    typedef FwdEpi<BF16, RANK, REGEN, BF16 ? 16 : 32> Epi;
     const int esz = BF16 ? 2 : 4;
     const int64_t R = s.member_count * (int64_t)s.rows_per_member;
     // antithetic pairs: the epilogue sees pairs as members of 2S rows (noise id = row / 2S); the sign of
@@ -371,15 +468,30 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
-            return launch_gemm<MmaBf16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
+            // bf16 out and nothing left to correct in the epilogue (unperturbed, or the correction folds into the
+            // accumulators): the store-only epilogue with the activation and the residual fixed at compile time
+            const bool folded = !REGEN && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % Epi::CORR_COLS == 0;
+            if (yd == EGG_BF16 && (ea.c == 0.f || folded) && kchunks % 8 == 0) {
+                constexpr int LR = (REGEN || RANK > 8) ? 1 : RANK;
+#define EGG_LEAN(L) \
+    return launch_gemm_persistent<MmaBf16Blk16, 256, 256, 2, 4, FwdEpi<true, LR, false, 16, L>>(c, "forward_gemm_bf16", P, Q, kchunks, ea)
+                switch ((act == EGG_ACT_GELU ? LEAN_GELU : 0) | (resid ? LEAN_RESID : 0)) {
+                    case 0: EGG_LEAN(LEAN_ON);
+                    case LEAN_GELU: EGG_LEAN(LEAN_ON | LEAN_GELU);
+                    case LEAN_RESID: EGG_LEAN(LEAN_ON | LEAN_RESID);
+                    default: EGG_LEAN(LEAN_ON | LEAN_GELU | LEAN_RESID);
+                }
+#undef EGG_LEAN
+            }
+            return launch_gemm<MmaBf16Blk16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
         }
         // few rows against a large layer (the paper's own benchmark shape, batch 1024 on 8192 x 8192): tall
         // tiles keep one workgroup per CU busy where 256 x 256 tiles would leave half the chip idle
         const int64_t tall_tiles = ((s.d_out + 255) / 256) * ((R + 127) / 128);
         if (tall_tiles >= 192) {
-            return launch_gemm<MmaBf16, 256, 128, 4, 2, Epi>(c, "forward_gemm_bf16_tall", P, Q, kchunks, ea);
+            return launch_gemm<MmaBf16Blk16, 256, 128, 4, 2, Epi>(c, "forward_gemm_bf16_tall", P, Q, kchunks, ea);
         }
-        return launch_gemm<MmaBf16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
+        return launch_gemm<MmaBf16Blk16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
     } else {
         return launch_gemm<MmaF32, 128, 128, 2, 2, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);
     }
