@@ -45,23 +45,28 @@ def parse():
 
 
 def profiled_traffic(workload, markers):
-    """HBM bytes per launch of the dominant kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE,
-    scaled by a copy of known size): the traffic table of profiles/<workload>_kernels.md, row of the
-    kernel whose name holds every marker.  None when no such profile is in the tree."""
+    """HBM bytes per launch of the dominant kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, scaled by kernels of
+    known traffic in the same profile): the traffic table of profiles/<workload>_kernels.md, rows of the kernels whose name
+    holds every marker, averaged over their dispatches.  None when no such profile is in the tree."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "%s_kernels.md" % workload)
     if not os.path.exists(path):
         return None
     in_table = False
+    total = launches = 0
     for line in open(path):
         if line.startswith("## HBM traffic"):
             in_table = True
+        elif line.startswith("## "):
+            in_table = False
         elif in_table and line.startswith("|") and all(m in line for m in markers):
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             try:
-                return int(cells[-1])
+                n, b = int(cells[1]), int(cells[-1])
             except ValueError:
-                return None
-    return None
+                continue
+            total += n * b
+            launches += n
+    return total // launches if launches else None
 
 
 def calibration_copy():

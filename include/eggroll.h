@@ -157,6 +157,26 @@ egg_status eggroll_perturbed_forward_add(eggroll_ctx* ctx, egg_key key, const eg
                                          const void* R_in, void* Y, void* A_cache, void* B_cache);
 
 /*
+ * (2c) The same layer between other perturbed layers, without reading activations twice (App. "Arithmetic Intensity
+ * Analysis": the R x r projections are the only intermediate the method adds to a layer's traffic).
+ *   R_in:   optional residual as in (2a); NULL = none.
+ *   t_in:   optional [R][rank] fp32 (device), the projections X B_i of THIS layer as an earlier call delivered them
+ *           through its t_next; NULL = the projection pass of (2) reads X and forms them.  Read only when sigma > 0.
+ *   want_next != 0: additionally t_next[row] = sum_j Y[row][j] * B'_{member(row)}[j] (fp32, device, [R]), where B'
+ *           are the rank-1 factors B of the layer with noise id next_layer (same seed and step; its d_in is this d_out),
+ *           formed from the very bf16 values stored to Y -- what that layer's own projection pass would compute,
+ *           summed in another order.  This form exists for io_dtype = y_dtype = EGG_BF16, rank 1, act = EGG_ACT_GELU,
+ *           R_in = NULL, sigma > 0, no antithetic pairs, rows_per_member and d_in multiples of 64, and at least 192
+ *           output tiles of 256 x 256; anything else returns EGG_EUNSUPPORTED before any work is enqueued, and the
+ *           caller uses plain calls.  The factors B' are drawn into context scratch.
+ * Factor caches are not written by this entry point.
+ */
+egg_status eggroll_perturbed_forward_chained(eggroll_ctx* ctx, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                             egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                             const void* R_in, void* Y, const float* t_in, int want_next,
+                                             uint32_t next_layer, float* t_next);
+
+/*
  * Layout of the factor caches that eggroll_perturbed_forward writes and eggroll_update reads on this context
  * (default EGG_CACHE_ROWS: exactly what eggroll_noise_gen writes, [member][d][rank]).
  * EGG_CACHE_PANEL keeps only B, already in the form the update's contraction consumes (Sec. 4.2,
@@ -349,6 +369,18 @@ egg_status eggroll_embed_rows_bf16(eggroll_ctx* ctx, int64_t rows, int d, int vo
 egg_status eggroll_rmsnorm_bf16(eggroll_ctx* ctx, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y);
 egg_status eggroll_causal_attention_bf16(eggroll_ctx* ctx, int64_t members, int rows_per_member, int heads, int head_dim,
                                          const void* Q, const void* K, const void* V, void* O);
+
+/*
+ * The same attention, and additionally the rank-1 projections of its output for the perturbed layer that reads it
+ * (the o-projection): t_next[row] = sum_j O[row][j] * B_{member(row)}[j] (fp32, device, [members * rows_per_member]),
+ * B = the factors B of the layer (key.seed, key.step, key.layer) for members member_begin .. member_begin + members - 1
+ * over d_in = heads * head_dim, formed from the bf16 values stored to O (the heads' shares are added in head order).
+ * Pass t_next as t_in of eggroll_perturbed_forward_chained for that layer: O is then not read by a projection pass.
+ * The factors are drawn into context scratch.
+ */
+egg_status eggroll_causal_attention_project_bf16(eggroll_ctx* ctx, egg_key key, int64_t member_begin, int64_t members,
+                                                 int rows_per_member, int heads, int head_dim, const void* Q, const void* K,
+                                                 const void* V, void* O, float* t_next);
 egg_status eggroll_token_loglik_bf16(eggroll_ctx* ctx, int64_t members, int rows_per_member, int vocab, const void* logits,
                                      const int32_t* tokens, float* out);
 

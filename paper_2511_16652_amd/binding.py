@@ -23,8 +23,8 @@ EXPORTS = ["eggroll_create", "eggroll_destroy", "eggroll_strerror", "eggroll_las
            "eggroll_perturbed_forward_i8", "eggroll_gru_i8", "eggroll_layernorm_i8", "eggroll_embed_i8",
            "eggroll_egg_forward_i8", "eggroll_loglik_i8", "eggroll_egg_update_i8", "eggroll_update", "eggroll_update_i8",
            "eggroll_int_threshold", "eggroll_profile_enable", "eggroll_profile_read",
-           "eggroll_scratch_generation", "eggroll_trim", "eggroll_set_conservative_waits", "eggroll_normal_int_table", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add",
-           "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_token_loglik_bf16",
+           "eggroll_scratch_generation", "eggroll_trim", "eggroll_set_conservative_waits", "eggroll_normal_int_table", "eggroll_perturbed_forward_noalloc", "eggroll_perturbed_forward_add", "eggroll_perturbed_forward_chained",
+           "eggroll_embed_rows_bf16", "eggroll_rmsnorm_bf16", "eggroll_causal_attention_bf16", "eggroll_causal_attention_project_bf16", "eggroll_token_loglik_bf16",
            "eggroll_mlp_stack_forward", "eggroll_mlp_stack_update", "eggroll_decoder_forward", "eggroll_decoder_update"]
 
 
@@ -128,12 +128,16 @@ def load_library() -> ctypes.CDLL:
     lib.eggroll_trim.restype = i32
     lib.eggroll_perturbed_forward_add.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp, vp]
     lib.eggroll_perturbed_forward_add.restype = i32
+    lib.eggroll_perturbed_forward_chained.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, i32, vp, vp, vp, vp, vp, i32, ctypes.c_uint32, vp]
+    lib.eggroll_perturbed_forward_chained.restype = i32
     lib.eggroll_embed_rows_bf16.argtypes = [vp, i64, i32, i32, vp, vp, vp]
     lib.eggroll_embed_rows_bf16.restype = i32
     lib.eggroll_rmsnorm_bf16.argtypes = [vp, i64, i32, f32, vp, vp, vp]
     lib.eggroll_rmsnorm_bf16.restype = i32
     lib.eggroll_causal_attention_bf16.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.eggroll_causal_attention_bf16.restype = i32
+    lib.eggroll_causal_attention_project_bf16.argtypes = [vp, EggKey, i64, i64, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.eggroll_causal_attention_project_bf16.restype = i32
     lib.eggroll_token_loglik_bf16.argtypes = [vp, i64, i32, i32, vp, vp, vp]
     lib.eggroll_token_loglik_bf16.restype = i32
     lib.eggroll_mlp_stack_forward.argtypes = [vp, EggKey, P(EggShape), i32, i32, f32, vp, vp, vp, vp, i64]
@@ -238,6 +242,12 @@ class Context:
             self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act,
             _ptr(W), _ptr(X), _ptr(R_in), _ptr(Y), _ptr(A_cache), _ptr(B_cache)))
 
+    def eggroll_perturbed_forward_chained(self, key, shape, sigma, act, W, X, Y, R_in=None, t_in=None, next_layer=None, t_next=None):
+        """next_layer given: t_next receives the next layer's rank-1 projections of Y."""
+        self._check(self._lib.eggroll_perturbed_forward_chained(
+            self._h, key, ctypes.byref(shape), _dtype_code(W), _dtype_code(Y), float(sigma), act, _ptr(W), _ptr(X), _ptr(R_in), _ptr(Y),
+            _ptr(t_in), 0 if next_layer is None else 1, int(next_layer or 0), _ptr(t_next)))
+
     def eggroll_embed_rows_bf16(self, rows, d, vocab, emb, tokens, X):
         self._check(self._lib.eggroll_embed_rows_bf16(self._h, int(rows), int(d), int(vocab), _ptr(emb), _ptr(tokens), _ptr(X)))
 
@@ -247,6 +257,11 @@ class Context:
     def eggroll_causal_attention_bf16(self, members, rows_per_member, heads, head_dim, Q, K, V, O):
         self._check(self._lib.eggroll_causal_attention_bf16(
             self._h, int(members), int(rows_per_member), int(heads), int(head_dim), _ptr(Q), _ptr(K), _ptr(V), _ptr(O)))
+
+    def eggroll_causal_attention_project_bf16(self, key, member_begin, members, rows_per_member, heads, head_dim, Q, K, V, O, t_next):
+        self._check(self._lib.eggroll_causal_attention_project_bf16(
+            self._h, key, int(member_begin), int(members), int(rows_per_member), int(heads), int(head_dim), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
+            _ptr(t_next)))
 
     def eggroll_token_loglik_bf16(self, members, rows_per_member, vocab, logits, tokens, out):
         self._check(self._lib.eggroll_token_loglik_bf16(

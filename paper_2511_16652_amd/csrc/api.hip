@@ -116,7 +116,7 @@ egg_status validate_shape(eggroll_ctx* c, const egg_shape* s, bool need_rows, bo
 // projection pre-pass + shared GEMM with the correction epilogue for one validated linear layer
 egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
                           egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
-                          float* t_fixed, const float* t_ready)
+                          float* t_fixed, const float* t_ready, const NextProjection* next)
 {
     const bool panel = c->cache_layout == EGG_CACHE_PANEL;
     const int64_t R = shape.member_count * (int64_t)shape.rows_per_member;
@@ -136,14 +136,15 @@ egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, e
         if (s != EGG_OK) return s;
     }
     return launch_forward_gemm(c, make_stream_key(key.seed, key.step, key.layer, 0), shape, io_dtype, y_dtype, sigma, act, W, X, Y,
-                               t, A_cache, resid);
+                               t, A_cache, resid, next);
 }
 
 // validation shared by the forward entry points; t_fixed != NULL: the projections go to that buffer of t_capacity
 // values and nothing may be allocated on the way
 egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype, egg_dtype y_dtype,
                                 float sigma, egg_act act, const void* W, const void* X, const void* R_in, bool need_r, void* Y,
-                                void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity)
+                                void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity, const float* t_in, bool want_next,
+                                uint32_t next_layer, float* t_next)
 {
     if (!c) return EGG_EINVAL;
     egg_status s = validate_shape(c, shape, true, true);
@@ -176,8 +177,29 @@ egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, 
         if (!regen && !A_cache)
             return fail(c, EGG_EINVAL, "more than one row per member or rank > 1 materialises A_i: pass A_cache (this entry point does not allocate)");
     }
+    if (t_in && B_cache) return fail(c, EGG_EINVAL, "given projections skip the pass that would fill B_cache: pass one or the other");
+    if (want_next) {
+        if (!t_next) return fail(c, EGG_EINVAL, "t_next must be non-NULL");
+        if (next_layer >> 31) return fail(c, EGG_EINVAL, "next_layer must be < 2^31");
+        if (!forward_fuses_next_projection(*shape, io_dtype, y_dtype, sigma, act, R_in != nullptr))
+            return fail(c, EGG_EUNSUPPORTED,
+                        "the next layer's projections are formed only by bf16 rank-1 GELU layers without residual, sigma > 0, 64 | rows_per_member, "
+                        "64 | d_in and at least 192 output tiles of 256 x 256");
+    }
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
-    return forward_linear(c, key, *shape, io_dtype, y_dtype, sigma, act, W, X, Y, A_cache, B_cache, R_in, t_fixed);
+    NextProjection np{nullptr, t_next};
+    if (want_next) {
+        // the next layer's B factors over this layer's outputs, exactly what eggroll_noise_gen writes for that layer
+        const size_t bytes = (size_t)shape->member_count * shape->d_out * 2;
+        s = reserve(c, c->next_b, bytes);
+        if (s != EGG_OK) return s;
+        s = launch_noise(c, make_stream_key(key.seed, key.step, next_layer, 1), (uint32_t)shape->member_begin, shape->member_count,
+                         shape->d_out, EGG_BF16, EGG_NORMAL, 0, c->next_b.p);
+        if (s != EGG_OK) return s;
+        np.B = c->next_b.p;
+    }
+    return forward_linear(c, key, *shape, io_dtype, y_dtype, sigma, act, W, X, Y, A_cache, B_cache, R_in, t_fixed,
+                          sigma != 0.0f ? t_in : nullptr, want_next ? &np : nullptr);
 }
 
 // z >= 0 with P(|Z| >= z) = erfc(z / sqrt 2) = alpha, 0 < alpha < 1: Newton's method on g(z) = log erfc(z / sqrt 2) - log alpha,
@@ -247,7 +269,7 @@ egg_status eggroll_destroy(eggroll_ctx* c)
     if (!c) return EGG_EINVAL;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut, &c->norm_tab, &c->model, &c->model_g};
+    eggroll_ctx::Buf* bufs[] = {&c->t_buf, &c->a_buf, &c->b_buf, &c->fnorm, &c->pack_a, &c->pack_b, &c->i8_a, &c->i8_b, &c->i8_h, &c->gru, &c->zero_page, &c->lut, &c->norm_tab, &c->model, &c->model_g, &c->proj_part, &c->next_b};
     for (auto* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& b : c->retired) (void)hipFree(b.p);
@@ -345,6 +367,15 @@ egg_status eggroll_perturbed_forward_add(eggroll_ctx* c, egg_key key, const egg_
                                          const void* R_in, void* Y, void* A_cache, void* B_cache)
 {
     return checked_forward(c, key, shape, io_dtype, y_dtype, sigma, act, W, X, R_in, true, Y, A_cache, B_cache, nullptr, 0);
+}
+
+egg_status eggroll_perturbed_forward_chained(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype,
+                                             egg_dtype y_dtype, float sigma, egg_act act, const void* W, const void* X,
+                                             const void* R_in, void* Y, const float* t_in, int want_next, uint32_t next_layer,
+                                             float* t_next)
+{
+    return checked_forward(c, key, shape, io_dtype, y_dtype, sigma, act, W, X, R_in, false, Y, nullptr, nullptr, nullptr, 0, t_in,
+                           want_next != 0, next_layer, t_next);
 }
 
 egg_status eggroll_perturbed_forward_i8(eggroll_ctx* c, egg_key key, const egg_shape* shape, int int_bound,

@@ -48,6 +48,27 @@ egg_status eggroll_causal_attention_bf16(eggroll_ctx* c, int64_t members, int ro
     return launch_attention(c, members, rows_per_member, heads, head_dim, Q, K, V, O);
 }
 
+egg_status eggroll_causal_attention_project_bf16(eggroll_ctx* c, egg_key key, int64_t member_begin, int64_t members, int rows_per_member,
+                                                 int heads, int head_dim, const void* Q, const void* K, const void* V, void* O,
+                                                 float* t_next)
+{
+    if (!c) return EGG_EINVAL;
+    if (members < 0 || rows_per_member <= 0 || heads <= 0 || head_dim <= 0) return fail(c, EGG_EINVAL, "members, rows_per_member, heads or head_dim out of range");
+    if (member_begin < 0 || member_begin + members > (int64_t(1) << 32)) return fail(c, EGG_EINVAL, "member ids must stay below 2^32");
+    if (key.layer >> 31) return fail(c, EGG_EINVAL, "layer must be < 2^31");
+    if (!ok_ptr(Q) || !ok_ptr(K) || !ok_ptr(V) || !ok_ptr(O) || !t_next) return fail(c, EGG_EINVAL, "pointers must be non-NULL (tensors 16-byte aligned)");
+    if (O == Q || O == K || O == V) return fail(c, EGG_EINVAL, "O must not overlap Q, K or V");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
+    if (members == 0) return EGG_OK;
+    // the consuming layer's rank-1 factors B over the model width, exactly what eggroll_noise_gen writes for that layer
+    const int64_t d = (int64_t)heads * head_dim;
+    egg_status s = reserve(c, c->next_b, (size_t)members * d * 2);
+    if (s != EGG_OK) return s;
+    s = launch_noise(c, make_stream_key(key.seed, key.step, key.layer, 1), (uint32_t)member_begin, members, d, EGG_BF16, EGG_NORMAL, 0, c->next_b.p);
+    if (s != EGG_OK) return s;
+    return launch_attention(c, members, rows_per_member, heads, head_dim, Q, K, V, O, c->next_b.p, t_next);
+}
+
 egg_status eggroll_token_loglik_bf16(eggroll_ctx* c, int64_t members, int rows_per_member, int vocab, const void* logits,
                                      const int32_t* tokens, float* out)
 {

@@ -40,6 +40,8 @@ struct eggroll_ctx {
     Buf norm_tab;     // integer normal noise: the 65536-entry table round(16 z) (uploaded on first use)
     Buf model;        // multi-layer drivers: activations of one chunk of members
     Buf model_g;      // multi-layer updates: fp32 G of the matrix being updated
+    Buf proj_part;    // fused next-layer projection: per (128-row slab of d_out, row) partial sums
+    Buf next_b;       // fused next-layer projection through the C ABI: the next layer's factors B'[member][d_out]
     // buffers that a later, larger call outgrew: kept until eggroll_trim / eggroll_destroy, because work already
     // enqueued -- or a HIP graph captured earlier -- may still hold their addresses
     std::vector<Buf> retired;
@@ -100,25 +102,38 @@ egg_status launch_noise(eggroll_ctx* c, const StreamKey& k, uint32_t member_begi
                         egg_dtype dtype, egg_dist dist, int int_bound, void* out);
 egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
                           float* t, void* B_cache, bool panel);
+// A layer whose output feeds the next perturbed layer directly (up-projection -> down-projection) can form that
+// layer's rank-1 projections in its own epilogue, from the bf16 values it stores: B = the next layer's factors
+// [member][d_out] bf16, t = where the projections go.  Supported where forward_fuses_next_projection says so.
+struct NextProjection {
+    const void* B;
+    float* t;
+};
+bool forward_fuses_next_projection(const egg_shape& s, egg_dtype io, egg_dtype yd, float sigma, egg_act act, bool resid);
 egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
                                float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
-                               void* A_cache, const void* resid = nullptr);
+                               void* A_cache, const void* resid = nullptr, const NextProjection* next = nullptr);
 egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& kb, const egg_shape& s,
                          egg_dtype noise_dtype, const float* fitness, float scale, int accumulate, float* G, void* W,
                          egg_dtype w_dtype, float lr, const void* A_cache, const void* B_cache, bool b_panel);
 egg_status forward_linear(eggroll_ctx* c, egg_key key, const egg_shape& shape, egg_dtype io_dtype, egg_dtype y_dtype, float sigma,
                           egg_act act, const void* W, const void* X, void* Y, void* A_cache, void* B_cache, const void* resid,
-                          float* t_fixed = nullptr, const float* t_ready = nullptr);
+                          float* t_fixed = nullptr, const float* t_ready = nullptr, const NextProjection* next = nullptr);
 egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, egg_dtype io_dtype, egg_dtype y_dtype,
                            float sigma, egg_act act, const void* W, const void* X, const void* R_in, bool need_r, void* Y,
-                           void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity);
+                           void* A_cache, void* B_cache, float* t_fixed, size_t t_capacity, const float* t_in = nullptr,
+                           bool want_next = false, uint32_t next_layer = 0, float* t_next = nullptr);
 // unperturbed glue of the decoder workload
 egg_status launch_embed_rows(eggroll_ctx* c, int64_t rows, int d, int vocab, const void* emb, const int32_t* tokens, void* X);
 egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y);
 egg_status launch_rmsnorm_proj(eggroll_ctx* c, int64_t rows, int S, int d, float eps, const void* gain, const void* X, void* Y, int nc,
                                const void* const* B, float* const* t);
+// Bo != NULL: also t_next[row] = sum_j O[row][j] * Bo[member][j] (Bo: [members][heads * head_dim] bf16, rank-1 factors of the
+// layer that reads O)
 egg_status launch_attention(eggroll_ctx* c, int64_t members, int S, int heads, int head_dim, const void* Q, const void* K,
-                            const void* V, void* O);
+                            const void* V, void* O, const void* Bo = nullptr, float* t_next = nullptr);
+// t[n] = sum over slabs p of part[p][n], in slab order
+egg_status launch_sum_slabs(eggroll_ctx* c, const float* part, int slabs, int64_t R, float* t);
 egg_status launch_token_loglik(eggroll_ctx* c, int64_t members, int S, int vocab, const void* logits, const int32_t* tokens, float* out);
 // multi-layer drivers
 egg_status launch_mlp_stack_forward(eggroll_ctx* c, egg_key key, const egg_shape& s, int L, int d_ff, float sigma,

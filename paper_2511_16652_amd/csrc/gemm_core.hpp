@@ -637,14 +637,14 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_persistent_kernel(Oper
             const int n = cn0 + wn * WTN + j * BLK + (lane_e & (BLK - 1));
             const bool nvalid = n < Q.rows;
             epi.column(n, nvalid);
-#pragma unroll
-            for (int i = 0; i < MB; ++i) {
+            static_for<0, MB>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value;
                 const int ml = i * BLK + (lane_e >> 4) * 4;
                 typename Epi::value_t v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
-                epi.store4(cm0 + wm * WTM + ml, n, v, nvalid, ml);
-            }
+                epi.template store4_at<i>(cm0 + wm * WTM + ml, n, v, nvalid, ml);
+            });
             epi.template flush<WTM>(cm0 + wm * WTM, cn0 + wn * WTN + j * BLK, Q.rows);
         });
         if (next >= total) break;

@@ -120,12 +120,17 @@ struct AttnCfg {
 template <int HD>
 __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                         const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int S,
-                                                        int heads, int64_t ld, float scale_log2)
+                                                        int heads, int64_t ld, float scale_log2,
+                                                        const uint16_t* __restrict__ Bo, float* __restrict__ part, int64_t rows_total)
 {
+    // Bo != NULL: the rows written here feed a perturbed layer (the o-projection) whose rank-1 factors are Bo[member][heads * HD];
+    // the head's share of that layer's projections, sum over its HD columns of O[row][col] * Bo[col] (from the bf16 values stored),
+    // goes to part[head][row] and a small pass adds the heads in order -- so the attention output is not read a second time.
     typedef AttnCfg<HD> C;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* sK = smem;
     char* sV = smem + C::SMAX * C::KP;
+    char* sB = smem + C::LDS;  // HD bf16 of Bo for this (member, head)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t member = blockIdx.x / heads;
@@ -135,6 +140,7 @@ __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restri
     const int SP = (S + 31) & ~31;
     constexpr int CPR = HD / 8;  // 16-byte chunks per row
 
+    if (Bo && tid < CPR) *(uint4*)(sB + tid * 16) = *(const uint4*)(Bo + (member * heads + head) * (int64_t)HD + tid * 8);
     for (int idx = tid; idx < SP * CPR; idx += 512) {
         const int row = idx / CPR, ch = idx - row * CPR;
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -225,16 +231,26 @@ __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restri
         }
     }
     const float inv = 1.0f / (lrun + __shfl_xor(lrun, 32, 64));
-    if (qrow < S) {
-        uint16_t* orow = O + base + (int64_t)qrow * ld;
+    uint16_t* orow = O + base + (int64_t)qrow * ld;
+    float tp = 0.f;
 #pragma unroll
-        for (int mb = 0; mb < HD / 32; ++mb)
+    for (int mb = 0; mb < HD / 32; ++mb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint2 o = make_uint2(pack_bf16x2(oacc[mb][4 * q] * inv, oacc[mb][4 * q + 1] * inv),
-                                           pack_bf16x2(oacc[mb][4 * q + 2] * inv, oacc[mb][4 * q + 3] * inv));
-                *(uint2*)(orow + mb * 32 + 8 * q + 4 * h) = o;
+        for (int q = 0; q < 4; ++q) {
+            const uint2 o = make_uint2(pack_bf16x2(oacc[mb][4 * q] * inv, oacc[mb][4 * q + 1] * inv),
+                                       pack_bf16x2(oacc[mb][4 * q + 2] * inv, oacc[mb][4 * q + 3] * inv));
+            if (qrow < S) *(uint2*)(orow + mb * 32 + 8 * q + 4 * h) = o;
+            if (Bo) {
+                const uint2 bv = *(const uint2*)(sB + (mb * 32 + 8 * q + 4 * h) * 2);
+                tp = fmaf(bf16_lo(o.x), bf16_lo(bv.x), tp);
+                tp = fmaf(bf16_hi(o.x), bf16_hi(bv.x), tp);
+                tp = fmaf(bf16_lo(o.y), bf16_lo(bv.y), tp);
+                tp = fmaf(bf16_hi(o.y), bf16_hi(bv.y), tp);
             }
+        }
+    if (Bo) {
+        tp += __shfl_xor(tp, 32, 64);  // the two lane halves hold the two halves of every 8 columns
+        if (h == 0 && qrow < S) part[(int64_t)head * rows_total + member * S + qrow] = tp;
     }
 }
 
@@ -335,30 +351,41 @@ egg_status launch_rmsnorm_proj(eggroll_ctx* c, int64_t rows, int S, int d, float
 
 template <int HD>
 static egg_status launch_attention_t(eggroll_ctx* c, int64_t members, int S, int heads, const void* Q, const void* K,
-                                     const void* V, void* O)
+                                     const void* V, void* O, const void* Bo, float* part)
 {
     auto kern = attention_kernel<HD>;
-    egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)AttnCfg<HD>::LDS, "attention smem attr");
+    constexpr size_t LDS = (size_t)AttnCfg<HD>::LDS + HD * 2;
+    egg_status st = ensure_dynamic_lds(c, (const void*)kern, LDS, "attention smem attr");
     if (st != EGG_OK) return st;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     KernelScope ks(c, "attention");
-    hipLaunchKernelGGL(kern, dim3((unsigned)(members * heads)), dim3(512), AttnCfg<HD>::LDS, c->stream, (const uint16_t*)Q,
-                       (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)O, S, heads, (int64_t)heads * HD, scale_log2);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(members * heads)), dim3(512), LDS, c->stream, (const uint16_t*)Q,
+                       (const uint16_t*)K, (const uint16_t*)V, (uint16_t*)O, S, heads, (int64_t)heads * HD, scale_log2,
+                       (const uint16_t*)Bo, part, members * S);
     return check_hip(c, hipGetLastError(), "attention launch");
 }
 
 egg_status launch_attention(eggroll_ctx* c, int64_t members, int S, int heads, int head_dim, const void* Q, const void* K,
-                            const void* V, void* O)
+                            const void* V, void* O, const void* Bo, float* t_next)
 {
     if (members == 0) return EGG_OK;
+    float* part = nullptr;
+    if (Bo) {
+        egg_status st = reserve(c, c->proj_part, (size_t)heads * members * S * sizeof(float));
+        if (st != EGG_OK) return st;
+        part = (float*)c->proj_part.p;
+    }
+    egg_status st = EGG_EUNSUPPORTED;
     if (S < 1 || S > 256) return fail(c, EGG_EUNSUPPORTED, "attention: rows_per_member %d outside [1, 256]", S);
     if (members * heads > 0x7FFFFFFF) return fail(c, EGG_EUNSUPPORTED, "attention: too many (member, head) pairs in one call");
     switch (head_dim) {
-        case 32: return launch_attention_t<32>(c, members, S, heads, Q, K, V, O);
-        case 64: return launch_attention_t<64>(c, members, S, heads, Q, K, V, O);
-        case 128: return launch_attention_t<128>(c, members, S, heads, Q, K, V, O);
+        case 32: st = launch_attention_t<32>(c, members, S, heads, Q, K, V, O, Bo, part); break;
+        case 64: st = launch_attention_t<64>(c, members, S, heads, Q, K, V, O, Bo, part); break;
+        case 128: st = launch_attention_t<128>(c, members, S, heads, Q, K, V, O, Bo, part); break;
+        default: return fail(c, EGG_EUNSUPPORTED, "attention: head dimension %d not in {32, 64, 128}", head_dim);
     }
-    return fail(c, EGG_EUNSUPPORTED, "attention: head dimension %d not in {32, 64, 128}", head_dim);
+    if (st != EGG_OK || !Bo) return st;
+    return launch_sum_slabs(c, part, heads, members * S, t_next);
 }
 
 egg_status launch_token_loglik(eggroll_ctx* c, int64_t members, int S, int vocab, const void* logits, const int32_t* tokens, float* out)

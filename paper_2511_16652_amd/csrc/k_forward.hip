@@ -53,6 +53,8 @@ struct FwdArgs {
     int mma_corr;   // !REGEN, bf16, S % CORR_COLS == 0: the correction is folded in by one extra MFMA per block
     int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
     const void* resid;  // optional [R][d_out] of the output dtype, added after the activation (residual stream)
+    const void* next_B;  // LEAN_PROJ: the next layer's factors B[member][d_out] (bf16, rank 1)
+    float* next_part;    // LEAN_PROJ: partial projections [d_out / 128 slabs][R]
 };
 
 // Where the lane's factor entries A_i[m..m+3][0..RANK-1] come from:
@@ -68,7 +70,11 @@ struct FwdArgs {
 // erff, staged and direct factor reads) 32 times per wave: about 80 KB, more than the instruction cache that two
 // compute units share, and it runs once per tile -- measured at 13 us behind a 50 us main loop, against 5 us for
 // the lean form.
-enum { LEAN_ON = 1, LEAN_GELU = 2, LEAN_RESID = 4 };
+// bit 3 (LEAN_PROJ): the rows this layer stores are the input of the next perturbed layer, whose rank-1 projection
+// t'[n] = sum_m Y[n][m] B'[m] is formed here from the very bf16 values that are stored, so that Y is not read again
+// by a projection pass: a lane adds its 4 x 8 products per column, the four lane groups of a column are summed by two
+// shuffles, and the sum over the wave tile's 128 rows goes to a slab-partial that a small pass adds up in fixed order.
+enum { LEAN_ON = 1, LEAN_GELU = 2, LEAN_RESID = 4, LEAN_PROJ = 8 };
 template <bool BF16, int RANK, bool REGEN, int BLK = 32, int LEAN = 0>
 struct FwdEpi {
     static_assert(LEAN == 0 || (BF16 && !REGEN), "the lean epilogue stores bf16 and regenerates nothing");
@@ -99,6 +105,11 @@ struct FwdEpi {
     // epilogue parks the operands in its LDS slice instead (see prefetch).
     static constexpr bool PREFETCH = RANK <= 4 && LEAN == 0;
     static constexpr int LDS_T = 0, LDS_A = 2048;  // byte offsets of t[64][RANK] fp32 and A_i[128][RANK] bf16 in the slice
+    static constexpr int LDS_NB = 3072;            // LEAN_PROJ (rank 1): the next layer's B'[128] bf16
+    static constexpr bool PROJ = (LEAN & LEAN_PROJ) != 0;
+    static_assert(!PROJ || RANK == 1, "the fused next-layer projection is the rank-1 form");
+    uint2 nb[PROJ ? 8 : 1];  // B' of the lane's rows, per row block (4 bf16 each)
+    float tn = 0.f;          // the lane's part of t'[n] for the current column
     // prefetched A rows of the lane, per (row block, group of CORR_COLS columns that share one member), and the
     // prefetched t of the lane's columns, per column block.  With 16x16 blocks a wave tile has twice the row
     // blocks; one member per 64 columns (the width of every wave tile launched here) keeps the register count.
@@ -153,6 +164,10 @@ struct FwdEpi {
                 __builtin_amdgcn_global_load_lds((egg_glb_void*)(asrc + min(k * 64 + lane, a_last)),
                                                  (egg_lds_void*)(sty.base + LDS_A + k * 256), 4, 0, 0);
             }
+            if constexpr (PROJ) {
+                const uint32_t* bsrc = (const uint32_t*)((const uint16_t*)a.next_B + member_l * a.d_out + mw0);
+                __builtin_amdgcn_global_load_lds((egg_glb_void*)(bsrc + min(lane, a_last)), (egg_lds_void*)(sty.base + LDS_NB), 4, 0, 0);
+            }
         } else if constexpr (!REGEN && BF16 && PREFETCH) {
             static_assert(MB <= PF_MB && NB <= PF_NB && NB * BLK <= PF_NG * CORR_COLS, "prefetch storage");
             if (!a.mma_corr) return;
@@ -171,6 +186,11 @@ struct FwdEpi {
             if (!a.mma_corr) return;
             if constexpr (LEAN != 0) {
                 if (nw0 >= n_rows || mw0 >= a.d_out) return;  // nothing of this wave tile is stored
+                if constexpr (PROJ) {
+                    // into registers now: the slice becomes the staging area of the stores
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) nb[i] = *(const uint2*)(sty.base + LDS_NB + (i * BLK + (lane / BLK) * 4) * 2);
+                }
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -260,12 +280,35 @@ struct FwdEpi {
 
     __device__ __forceinline__ void column(int n, bool valid)
     {
+        if constexpr (PROJ) tn = 0.f;
         if constexpr (LEAN != 0) return;
         if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
         member = a.member_begin + (uint32_t)ml_member;
 #pragma unroll
         for (int l = 0; l < RANK; ++l) tc[l] = a.c * a.t[(int64_t)n * RANK + l];
+    }
+
+    // the persistent kernel names the row block (a compile-time index into per-block registers)
+    template <int I>
+    __device__ __forceinline__ void store4_at(int m, int n, const float (&v)[4], bool valid, int ml)
+    {
+        if constexpr (PROJ) {
+            float y[4] = {v[0], v[1], v[2], v[3]};
+            if constexpr ((LEAN & LEAN_GELU) != 0) gelu_bf16_grade4(y);
+            static_assert((LEAN & LEAN_RESID) == 0, "not combined with the residual form");
+            const uint32_t p0 = pack_bf16x2(y[0], y[1]), p1 = pack_bf16x2(y[2], y[3]);
+            if (valid && m < a.d_out) {
+                float acc = bf16_lo(p0) * bf16_lo(nb[I].x);
+                acc = fmaf(bf16_hi(p0), bf16_hi(nb[I].x), acc);
+                acc = fmaf(bf16_lo(p1), bf16_lo(nb[I].y), acc);
+                acc = fmaf(bf16_hi(p1), bf16_hi(nb[I].y), acc);
+                tn += acc;
+            }
+            sty.put(a.wtm_pitch, ml, p0, p1);
+        } else {
+            store4(m, n, v, valid, ml);
+        }
     }
 
     __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid, int ml)
@@ -386,6 +429,13 @@ struct FwdEpi {
     __device__ __forceinline__ void flush(int mw0, int nb0, int n_rows)
     {
         if (LEAN != 0 || a.y_bf16) sty.template flush<WTM, BLK>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
+        if constexpr (PROJ) {
+            static_assert(WTM == 128 && BLK == 16, "slabs of 128 rows, four lane groups per column");
+            float tsum = tn + __shfl_xor(tn, 16, 64);
+            tsum += __shfl_xor(tsum, 32, 64);
+            const int n = nb0 + (sty.lane & 15);
+            if (sty.lane < 16 && n < n_rows && mw0 < a.d_out) a.next_part[(int64_t)(mw0 >> 7) * n_rows + n] = tsum;
+        }
         if constexpr (REGEN && BF16) {
             // REGEN means one row per member, so local member index == row index: same addressing as Y
             if (a.A_buf && a.c != 0.f) sta.template flush<WTM, BLK>((uint16_t*)a.A_buf, a.d_out, mw0, nb0, n_rows, a.d_out);
@@ -425,6 +475,31 @@ static egg_status launch_gemm(eggroll_ctx* c, const char* name, const Operand& P
     return check_hip(c, hipGetLastError(), name);
 }
 
+// t[n] = sum over the 128-row slabs of d_out of the partial projections, in slab order (a fixed order: run-to-run identical)
+__global__ __launch_bounds__(256) void sum_slabs_kernel(const float* __restrict__ part, int slabs, int64_t R, float* __restrict__ t)
+{
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= R) return;
+    float acc = 0.f;
+    for (int p = 0; p < slabs; ++p) acc += part[(int64_t)p * R + n];
+    t[n] = acc;
+}
+
+egg_status launch_sum_slabs(eggroll_ctx* c, const float* part, int slabs, int64_t R, float* t)
+{
+    KernelScope ks(c, "project_sum_slabs");
+    hipLaunchKernelGGL(sum_slabs_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, c->stream, part, slabs, R, t);
+    return check_hip(c, hipGetLastError(), "project_sum_slabs");
+}
+
+bool forward_fuses_next_projection(const egg_shape& s, egg_dtype io, egg_dtype yd, float sigma, egg_act act, bool resid)
+{
+    const int64_t R = s.member_count * (int64_t)s.rows_per_member;
+    const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
+    return io == EGG_BF16 && yd == EGG_BF16 && sigma != 0.f && s.rank == 1 && !s.antithetic && act == EGG_ACT_GELU && !resid &&
+           s.rows_per_member % 64 == 0 && s.rows_per_member > 1 && big_tiles >= 192 && s.d_in % 64 == 0;
+}
+
 // The persistent kernel for store-only epilogues: one workgroup per compute unit walks the tiles.
 template <class MT, int BM, int BN, int WM, int WN, class Epi>
 static egg_status launch_gemm_persistent(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
@@ -452,7 +527,7 @@ static egg_status launch_gemm_persistent(eggroll_ctx* c, const char* name, const
 template <bool BF16, int RANK, bool REGEN>
 static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype yd, float sigma,
                                    egg_act act, const void* W, const void* X, void* Y, const float* t, void* A_buf,
-                                   const void* resid)
+                                   const void* resid, const NextProjection* next)
 {
     typedef FwdEpi<BF16, RANK, REGEN, BF16 ? 16 : 32> Epi;
     const int esz = BF16 ? 2 : 4;
@@ -464,13 +539,31 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
     Operand Q{(const char*)X, (int64_t)s.d_in * esz, 16, (int)R};
     const int kchunks = s.d_in * esz / 16;
     typename Epi::Args ea{ka, (uint32_t)(s.member_begin / anti), s.rows_per_member * anti, s.d_out, sigma / sqrtf((float)s.rank),
-                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0, (REGEN && s.antithetic) ? 1 : 0, resid};
+                          (int)act, yd == EGG_BF16 ? 1 : 0, Y, t, A_buf, 0, 0, 0, (REGEN && s.antithetic) ? 1 : 0, resid,
+                          nullptr, nullptr};
     if constexpr (BF16) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
         if (big_tiles >= 192) {
             // bf16 out and nothing left to correct in the epilogue (unperturbed, or the correction folds into the
             // accumulators): the store-only epilogue with the activation and the residual fixed at compile time
             const bool folded = !REGEN && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % Epi::CORR_COLS == 0;
+            if (next) {
+                // the fused next-layer projection exists in one form: rank 1, folded correction, GELU, no residual
+                if constexpr (!REGEN && RANK == 1) {
+                    if (forward_fuses_next_projection(s, EGG_BF16, yd, sigma, act, resid != nullptr)) {
+                        const int slabs = (s.d_out + 127) / 128;
+                        egg_status st = reserve(c, c->proj_part, (size_t)slabs * R * sizeof(float));
+                        if (st != EGG_OK) return st;
+                        ea.next_B = next->B;
+                        ea.next_part = (float*)c->proj_part.p;
+                        st = launch_gemm_persistent<MmaBf16Blk16, 256, 256, 2, 4, FwdEpi<true, 1, false, 16, LEAN_ON | LEAN_GELU | LEAN_PROJ>>(
+                            c, "forward_gemm_bf16", P, Q, kchunks, ea);
+                        if (st != EGG_OK) return st;
+                        return launch_sum_slabs(c, (const float*)c->proj_part.p, slabs, R, next->t);
+                    }
+                }
+                return fail(c, EGG_EINVAL, "this layer cannot form the next layer's projections (ask forward_fuses_next_projection first)");
+            }
             if (yd == EGG_BF16 && (ea.c == 0.f || folded) && kchunks % 8 == 0) {
                 constexpr int LR = (REGEN || RANK > 8) ? 1 : RANK;
 #define EGG_LEAN(L) \
@@ -485,6 +578,7 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
             }
             return launch_gemm<MmaBf16Blk16, 256, 256, 2, 4, Epi>(c, "forward_gemm_bf16", P, Q, kchunks, ea);
         }
+        if (next) return fail(c, EGG_EINVAL, "this layer cannot form the next layer's projections (ask forward_fuses_next_projection first)");
         // few rows against a large layer (the paper's own benchmark shape, batch 1024 on 8192 x 8192): tall
         // tiles keep one workgroup per CU busy where 256 x 256 tiles would leave half the chip idle
         const int64_t tall_tiles = ((s.d_out + 255) / 256) * ((R + 127) / 128);
@@ -493,20 +587,21 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
         }
         return launch_gemm<MmaBf16Blk16, 128, 128, 2, 2, Epi>(c, "forward_gemm_bf16_small", P, Q, kchunks, ea);
     } else {
+        if (next) return fail(c, EGG_EINVAL, "this layer cannot form the next layer's projections (ask forward_fuses_next_projection first)");
         return launch_gemm<MmaF32, 128, 128, 2, 2, Epi>(c, "forward_gemm_f32", P, Q, kchunks, ea);
     }
 }
 
 egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_shape& s, egg_dtype io, egg_dtype yd,
                                float sigma, egg_act act, const void* W, const void* X, void* Y, const float* t,
-                               void* A_cache, const void* resid)
+                               void* A_cache, const void* resid, const NextProjection* next)
 {
     const bool bf = io == EGG_BF16;
     // rank 1 with one row per member (or the unperturbed pass): regenerate in the epilogue
     // (with antithetic pairs a kept cache has one entry per pair, not per row: that goes the materialised way)
     if (sigma == 0.f || (s.rank == 1 && s.rows_per_member == 1 && !(s.antithetic && A_cache))) {
-        return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid)
-                  : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid);
+        return bf ? launch_forward_t<true, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid, next)
+                  : launch_forward_t<false, 1, true>(c, ka, s, yd, sigma, act, W, X, Y, t, A_cache, resid, next);
     }
     // otherwise materialise A once (into the caller's cache if there is one) and read it back
     void* A_buf = A_cache;
@@ -520,7 +615,7 @@ egg_status launch_forward_gemm(eggroll_ctx* c, const StreamKey& ka, const egg_sh
     egg_status st = launch_noise(c, ka, (uint32_t)(s.member_begin / anti), s.member_count / anti, (int64_t)s.d_out * s.rank, io,
                                  EGG_NORMAL, 0, A_buf);
     if (st != EGG_OK) return st;
-#define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf, resid)
+#define EGG_FWD(B, R) return launch_forward_t<B, R, false>(c, ka, s, yd, sigma, act, W, X, Y, t, A_buf, resid, next)
     if (bf) {
         switch (s.rank) {
             case 1: EGG_FWD(true, 1);

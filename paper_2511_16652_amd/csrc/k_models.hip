@@ -102,7 +102,7 @@ egg_status launch_decoder_forward(eggroll_ctx* c, egg_key key, const egg_shape& 
     // rank 1: the normalisation passes form the projections of the layers that read their output (q, k, v; up; head),
     // so those layers' inputs are not read a second time by a projection pass
     const bool fuse_proj = sigma != 0.0f && s.rank == 1;
-    if (fuse_proj) need += 3 * (pad((size_t)cm * d * 2) + pad(rows_max * sizeof(float)));
+    if (fuse_proj) need += 3 * (pad((size_t)cm * d * 2) + pad(rows_max * sizeof(float))) + pad((size_t)cm * ff * 2) + pad(rows_max * sizeof(float));
     egg_status st = reserve(c, c->model, need);
     if (st != EGG_OK) return st;
     const size_t dd = (size_t)d * d * 2, dff = (size_t)d * ff * 2;
@@ -125,9 +125,15 @@ egg_status launch_decoder_forward(eggroll_ctx* c, egg_key key, const egg_shape& 
                 Bf[j] = cv.take((size_t)cm * d * 2);
                 tf[j] = (float*)cv.take(rows_max * sizeof(float));
             }
+        void* Bdn = nullptr;   // the down-projection's factors over d_ff and its projections, formed by the up-projection's epilogue
+        float* tdn = nullptr;
+        if (fuse_proj) {
+            Bdn = cv.take((size_t)cm * ff * 2);
+            tdn = (float*)cv.take(rows_max * sizeof(float));
+        }
         // factors B_i of the layer with noise id `layer` for this chunk's members, as the projection pass would draw them
-        auto gen_b = [&](uint32_t layer, void* out) {
-            return launch_noise(c, make_stream_key(key.seed, key.step, layer, 1), (uint32_t)(s.member_begin + m0), n, d, EGG_BF16, EGG_NORMAL, 0, out);
+        auto gen_b = [&](uint32_t layer, void* out, int len) {
+            return launch_noise(c, make_stream_key(key.seed, key.step, layer, 1), (uint32_t)(s.member_begin + m0), n, len, EGG_BF16, EGG_NORMAL, 0, out);
         };
         egg_shape sq = s;
         sq.member_begin = s.member_begin + m0;
@@ -144,24 +150,30 @@ egg_status launch_decoder_forward(eggroll_ctx* c, egg_key key, const egg_shape& 
             auto kk = [&](uint32_t j) { return egg_key{key.seed, key.step, lid + j}; };
             if (fuse_proj) {
                 for (uint32_t j = 0; j < 3; ++j)
-                    if ((st = gen_b(lid + j, Bf[j])) != EGG_OK) return st;
+                    if ((st = gen_b(lid + j, Bf[j], d)) != EGG_OK) return st;
                 if ((st = launch_rmsnorm_proj(c, rows, S, d, cfg.rms_eps, (const char*)w.norm1 + (size_t)l * d * 2, x, h, 3, Bf, tf)) != EGG_OK) return st;
             } else if ((st = launch_rmsnorm(c, rows, d, cfg.rms_eps, (const char*)w.norm1 + (size_t)l * d * 2, x, h)) != EGG_OK) return st;
             if ((st = forward_linear(c, kk(0), sq, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.wq + l * dd, h, q, nullptr, nullptr, nullptr, nullptr, tf[0])) != EGG_OK) return st;
             if ((st = forward_linear(c, kk(1), sq, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.wk + l * dd, h, k, nullptr, nullptr, nullptr, nullptr, tf[1])) != EGG_OK) return st;
             if ((st = forward_linear(c, kk(2), sq, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.wv + l * dd, h, v, nullptr, nullptr, nullptr, nullptr, tf[2])) != EGG_OK) return st;
-            if ((st = launch_attention(c, n, S, cfg.heads, hd, q, k, v, h)) != EGG_OK) return st;
-            if ((st = forward_linear(c, kk(3), sq, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.wo + l * dd, h, x, nullptr, nullptr, x)) != EGG_OK) return st;
+            // the attention kernel forms the o-projection's projections of the rows it writes
+            if (fuse_proj && (st = gen_b(lid + 3, Bf[0], d)) != EGG_OK) return st;
+            if ((st = launch_attention(c, n, S, cfg.heads, hd, q, k, v, h, fuse_proj ? Bf[0] : nullptr, fuse_proj ? tf[0] : nullptr)) != EGG_OK) return st;
+            if ((st = forward_linear(c, kk(3), sq, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.wo + l * dd, h, x, nullptr, nullptr, x, nullptr, fuse_proj ? tf[0] : nullptr)) != EGG_OK) return st;
             if (fuse_proj) {
-                if ((st = gen_b(lid + 4, Bf[0])) != EGG_OK) return st;
+                if ((st = gen_b(lid + 4, Bf[0], d)) != EGG_OK) return st;
                 if ((st = launch_rmsnorm_proj(c, rows, S, d, cfg.rms_eps, (const char*)w.norm2 + (size_t)l * d * 2, x, h, 1, Bf, tf)) != EGG_OK) return st;
             } else if ((st = launch_rmsnorm(c, rows, d, cfg.rms_eps, (const char*)w.norm2 + (size_t)l * d * 2, x, h)) != EGG_OK) return st;
-            if ((st = forward_linear(c, kk(4), sup, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, (const char*)w.w_up + l * dff, h, u, nullptr, nullptr, nullptr, nullptr, tf[0])) != EGG_OK) return st;
-            if ((st = forward_linear(c, kk(5), sdn, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.w_down + l * dff, u, x, nullptr, nullptr, x)) != EGG_OK) return st;
+            // the up-projection's epilogue also projects what it stores onto the down-projection's factors, where it can
+            const bool fuse_dn = fuse_proj && forward_fuses_next_projection(sup, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, false);
+            NextProjection np{Bdn, tdn};
+            if (fuse_dn && (st = gen_b(lid + 5, Bdn, ff)) != EGG_OK) return st;
+            if ((st = forward_linear(c, kk(4), sup, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, (const char*)w.w_up + l * dff, h, u, nullptr, nullptr, nullptr, nullptr, tf[0], fuse_dn ? &np : nullptr)) != EGG_OK) return st;
+            if ((st = forward_linear(c, kk(5), sdn, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)w.w_down + l * dff, u, x, nullptr, nullptr, x, nullptr, fuse_dn ? tdn : nullptr)) != EGG_OK) return st;
         }
         const egg_key kh{key.seed, key.step, key.layer + 6u * (uint32_t)L};
         if (fuse_proj) {
-            if ((st = gen_b(kh.layer, Bf[0])) != EGG_OK) return st;
+            if ((st = gen_b(kh.layer, Bf[0], d)) != EGG_OK) return st;
             if ((st = launch_rmsnorm_proj(c, rows, S, d, cfg.rms_eps, w.norm_f, x, h, 1, Bf, tf)) != EGG_OK) return st;
         } else if ((st = launch_rmsnorm(c, rows, d, cfg.rms_eps, w.norm_f, x, h)) != EGG_OK) return st;
         if ((st = forward_linear(c, kh, shd, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, w.head, h, lg, nullptr, nullptr, nullptr, nullptr, tf[0])) != EGG_OK) return st;

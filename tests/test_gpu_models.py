@@ -135,6 +135,27 @@ def test_causal_attention(ctx, members, S, heads, hd):
         assert np.array_equal(to_numpy(O2)[keep], got[keep])
 
 
+@pytest.mark.parametrize("members,S,heads,hd", [(5, 40, 2, 64), (3, 256, 4, 128), (7, 33, 3, 32)])
+def test_attention_with_the_next_layers_projections(ctx, members, S, heads, hd):
+    """The by-product of the attention kernel: its stored rows times the consuming layer's factors B, per member."""
+    import torch
+    d, mb, layer = heads * hd, 11, 44
+    rng = np.random.default_rng(members * S)
+    q, k, v = (bf16_dev(rng.standard_normal((members * S, d))) for _ in range(3))
+    o, o2 = torch.empty_like(q), torch.empty_like(q)
+    t = torch.full((members * S,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.eggroll_causal_attention_project_bf16(eb.make_key(2, 5, layer), mb, members, S, heads, hd, q, k, v, o, t)
+    ctx.eggroll_causal_attention_bf16(members, S, heads, hd, q, k, v, o2)
+    B = torch.empty((members, d, 1), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_noise_gen(eb.make_key(2, 5, layer), eb.make_shape(mb, members, S, d, d, 1), eb.EGG_BF16, eb.EGG_NORMAL, 0, None, B)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
+    ref = np.einsum("msd,md->ms", to_numpy(o).astype(np.float64).reshape(members, S, d), to_numpy(B).astype(np.float64)[:, :, 0])
+    got = t.cpu().numpy().astype(np.float64).reshape(members, S)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - ref) <= 1e-5 * (np.abs(ref) + np.sqrt(np.mean(ref ** 2)))).all()
+
+
 @pytest.mark.parametrize("members,S,V", [(3, 7, 40), (2, 1, 64), (5, 16, 1000), (2, 3, 32000)])
 def test_token_loglik(ctx, members, S, V):
     import torch
@@ -211,6 +232,57 @@ def test_mlp_stack_update(ctx):
             assert not np.array_equal(got, W0[l])
 
 
+def test_chained_layers_next_projection_from_the_epilogue(ctx):
+    """Up-projection whose epilogue also forms the next layer's rank-1 projections (from the bf16 values it stores), and
+    the next layer fed those projections instead of running its own projection pass."""
+    import torch
+    N, S, d, ff, sigma, l_up, l_dn, mb = 192, 64, 256, 1024, 0.05, 21, 34, 6
+    R = N * S
+    wl = inputs.make_linear("up", "bf16", ff, d, N, S, 1, sigma, 71, layer=l_up)
+    W2 = inputs.round_to_bf16((np.random.default_rng(72).standard_normal((d, ff)) / np.sqrt(ff)).astype(np.float32))
+    Wd, Xd, W2d = bf16_dev(wl.W), bf16_dev(wl.X), bf16_dev(W2)
+    U = torch.empty((R, ff), dtype=torch.bfloat16, device="cuda")
+    t_next = torch.full((R,), float("nan"), dtype=torch.float32, device="cuda")
+    key_up, key_dn = eb.make_key(3, 1, l_up), eb.make_key(3, 1, l_dn)
+    s_up, s_dn = eb.make_shape(mb, N, S, ff, d, 1), eb.make_shape(mb, N, S, d, ff, 1)
+    ctx.eggroll_perturbed_forward_chained(key_up, s_up, sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
+    torch.cuda.synchronize()
+    # the layer itself
+    ref = oracle.forward(3, 1, l_up, mb, N, S, ff, d, 1, oracle.NOISE_BF16, sigma, oracle.ACT_GELU, wl.W, wl.X)
+    assert_close(to_numpy(U), ref, 1e-2, "up-projection")
+    U2 = torch.empty_like(U)
+    ctx.eggroll_perturbed_forward(key_up, s_up, sigma, eb.EGG_ACT_GELU, Wd, Xd, U2)
+    torch.cuda.synchronize()
+    assert torch.equal(U.view(torch.int16), U2.view(torch.int16))   # the extra output changes nothing of Y
+    # its by-product: the stored rows times the next layer's factors B', per member.  B' as the noise entry point writes it
+    # (held to the oracle's stream in test_gpu_noise: a bf16 factor may be the neighbouring rounding of the same normal for
+    # about 1e-5 of the entries, and one such entry moves a projection by 1e-3), rows as this call stored them.
+    Bn = torch.empty((N, ff, 1), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_noise_gen(eb.make_key(3, 1, l_dn), eb.make_shape(mb, N, S, d, ff, 1), eb.EGG_BF16, eb.EGG_NORMAL, 0, None, Bn)
+    torch.cuda.synchronize()
+    Bn = to_numpy(Bn).astype(np.float64)[:, :, 0]
+    Bo = np.stack([oracle.noise_matrix(3, 1, l_dn, 1, mb + m, ff, 1, oracle.NOISE_BF16)[:, 0] for m in range(0, N, 37)])
+    assert (Bn[::37] != Bo).mean() < 1e-3 and np.abs(Bn[::37] - Bo).max() <= 2.0 ** -7 * np.abs(Bo).max()
+    un = to_numpy(U).astype(np.float64).reshape(N, S, ff)
+    t_ref = np.einsum("msf,mf->ms", un, Bn)
+    got = t_next.cpu().numpy().astype(np.float64).reshape(N, S)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - t_ref) <= 2e-5 * (np.abs(t_ref) + np.sqrt(np.mean(t_ref ** 2)))).all()
+    # the next layer on those projections: same result as with its own projection pass, and right by the oracle
+    Y1, Y2 = torch.empty((R, d), dtype=torch.bfloat16, device="cuda"), torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_perturbed_forward_chained(key_dn, s_dn, sigma, eb.EGG_ACT_NONE, W2d, U, Y1, t_in=t_next)
+    ctx.eggroll_perturbed_forward(key_dn, s_dn, sigma, eb.EGG_ACT_NONE, W2d, U, Y2)
+    torch.cuda.synchronize()
+    ref2 = oracle.forward(3, 1, l_dn, mb, N, S, d, ff, 1, oracle.NOISE_BF16, sigma, 0, W2, to_numpy(U))
+    assert_close(to_numpy(Y1), ref2, 1e-2, "down-projection on delivered projections")
+    same_bits_or_reordered_sum(Y1, Y2, False, "delivered against own projections")
+    # forms that do not exist are refused before anything runs
+    with pytest.raises(eb.EggrollError):
+        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, N, S, ff, d, 2), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
+    with pytest.raises(eb.EggrollError):
+        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, 8, S, ff, d, 1), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
+
+
 # ---------------------------------------------------------------------------------------------------------
 def _decoder_inputs(V, d, ff, L, N, S, seed):
     P = inputs.decoder_params(V, d, ff, L, seed, norm_jitter=0.2)
@@ -218,7 +290,22 @@ def _decoder_inputs(V, d, ff, L, N, S, seed):
     return P, tok
 
 
-@pytest.mark.parametrize("V,d,heads,ff,L,N,S,chunk", [(512, 128, 2, 256, 2, 6, 40, 0), (64, 64, 2, 136, 1, 5, 32, 2)])
+def same_bits_or_reordered_sum(got, want, exact, what):
+    """The driver against the chain of single-layer calls.  Where the up-projection's epilogue forms the down-projection's
+    projections itself (rank 1, 64 | S, enough tiles), those are summed in another order than the projection pass sums
+    them: a few outputs then sit on the other side of a bf16 rounding boundary; everywhere else the bits are the same."""
+    import torch
+    if exact:
+        assert torch.equal(got.view(torch.int16) if got.dtype == torch.bfloat16 else got, want.view(torch.int16) if want.dtype == torch.bfloat16 else want), what
+        return
+    g, w = got.float(), want.float()
+    diff = (g - w).abs()
+    assert float((diff > 0).float().mean()) < 5e-2, what
+    assert bool((diff <= 2.0 ** -6 * (w.abs() + w.pow(2).mean().sqrt())).all()), what
+
+
+@pytest.mark.parametrize("V,d,heads,ff,L,N,S,chunk", [(512, 128, 2, 256, 2, 6, 40, 0), (64, 64, 2, 136, 1, 5, 32, 2),
+                                                      (512, 256, 2, 1024, 2, 192, 64, 0), (256, 256, 2, 1024, 1, 200, 64, 192)])
 def test_decoder_layers_teacher_forced_and_end_to_end(ctx, V, d, heads, ff, L, N, S, chunk):
     import torch
     sigma, base, mb, rank = 0.02, 100, 4, 1
@@ -282,15 +369,22 @@ def test_decoder_layers_teacher_forced_and_end_to_end(ctx, V, d, heads, ff, L, N
     ll2 = torch.empty_like(ll)
     ctx.eggroll_decoder_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, 0 + d, d, rank), cfg, Wd, sigma, tokd, logits, ll2, chunk)
     torch.cuda.synchronize()
-    assert torch.equal(logits.view(torch.int16), lg.view(torch.int16)) and torch.equal(ll2, ll)
+    exact = not (S % 64 == 0 and (ff // 256) * ((min(N, chunk or N) * S) // 256) >= 192)   # the fused projection's conditions
+    same_bits_or_reordered_sum(logits, lg, exact, "driver logits against the chain")
+    if exact:
+        assert torch.equal(ll2, ll)
+    else:
+        assert float((ll2 - ll).abs().max()) < 2e-2
     ll3 = torch.empty_like(ll)
     ctx.eggroll_decoder_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), cfg, Wd, sigma, tokd, None, ll3, chunk)
     torch.cuda.synchronize()
-    assert torch.equal(ll3, ll)
+    assert torch.equal(ll3, ll2)
 
     # end to end against the oracle's own chain
     lo, llo = models.decoder_forward(0, 0, base, range(mb, mb + N), tok, P, heads, EPS, rank, sigma)
-    fro = assert_close(lgn, lo.reshape(R, V), 3e-2, "decoder logits end to end")
+    # per entry: a 5-sigma bound on the accumulated bf16 roundings of the depth (it widens with the number of entries
+    # looked at); the Frobenius ratio below carries the claim
+    fro = assert_close(lgn, lo.reshape(R, V), 3e-2 if R * V < 1e6 else 6e-2, "decoder logits end to end")
     assert fro < 1.5e-2
     assert np.abs(ll.cpu().numpy() - llo.reshape(-1)).max() < 0.05
     # sigma = 0 run of the same pipeline: members with equal tokens agree bit for bit; against the unperturbed oracle
