@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--members", type=int, default=None, help="cfg4/cfg5: population override (for quick runs; the headline uses the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 64 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+                    help="also run a plain elementwise kernel of known traffic, 64 MiB read + 64 MiB written (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-antithetic", action="store_true", help="linear workloads: skip the antithetic-pair legs (one update kernel shape per profile)")
     a = ap.parse_args()
     heavy = a.workload in ("cfg4", "cfg5")
     if a.steps is None:
@@ -70,13 +71,14 @@ def profiled_traffic(workload, markers):
 
 
 def calibration_copy():
-    """A copy kernel of known size inside the same profile (reads 64 MiB, writes 64 MiB): what
-    FETCH_SIZE / WRITE_SIZE report for it gives the scale of each counter."""
+    """An elementwise kernel of known traffic inside the same profile (dst = src + 1 over 16 Mi floats: reads 64 MiB,
+    writes 64 MiB; its name holds "FunctorOnSelf_add"): what FETCH_SIZE / WRITE_SIZE report for it gives the scale of
+    each counter."""
     import torch
-    src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    src = torch.ones(16 << 20, dtype=torch.float32, device="cuda")
     dst = torch.empty_like(src)
     for _ in range(3):
-        dst.copy_(src)
+        torch.add(src, 1.0, out=dst)
     torch.cuda.synchronize()
 
 
@@ -555,7 +557,7 @@ def linear_workload(args):
     # of pair p, the update contracts over N/2 pairs with one fitness value per pair.  Reported beside the
     # headline, never as `value`.
     anti = None
-    if wl.N % 2 == 0:
+    if wl.N % 2 == 0 and not args.no_antithetic:
         shape_a = eb.make_shape(0, wl.N, wl.S, wl.d_out, wl.d_in, wl.rank, antithetic=1)
         shape_p = eb.make_shape(0, wl.N // 2, 1, wl.d_out, wl.d_in, wl.rank)
         fit_p = (fit[0::2] - fit[1::2]).contiguous()

@@ -22,7 +22,9 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
 }
 
 // ---- RMS normalisation: Y[row][k] = X[row][k] * gain[k] / sqrt(mean_k X[row][k]^2 + eps) -------------
-// One wave per row; the second pass over the row re-reads it from cache.  HBM-bound: 2 d bytes in, 2 d out.
+// One wave per row.  Rows of up to 4096 values stay in the wave's registers between the sum of squares and the scaling
+// (CPL = 16-byte chunks per lane, known at compile time); longer rows are read a second time.  (Counters showed the
+// second read coming back from beyond the L2 for 0.6-0.9 of the row.)  HBM-bound: 2 d bytes in, 2 d out.
 __device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8])
 {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -43,7 +45,7 @@ struct NormProj {
     int S;  // rows per member
 };
 
-template <int NC>
+template <int NC, int CPL>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ X, const uint4* __restrict__ gain,
                                                       uint4* __restrict__ Y, int64_t rows, int chunks, float inv_d, float eps,
                                                       NormProj np)
@@ -53,11 +55,29 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     if (row >= rows) return;
     const uint4* xr = X + row * chunks;
     float ss = 0.f;
-    for (int c = lane; c < chunks; c += 64) {
-        float x[8];
-        unpack8(xr[c], x);
+    uint4 keep[CPL > 0 ? CPL : 1];  // CPL > 0: chunks <= 64 CPL (the launcher's choice); same order of accumulation either way
+    if constexpr (CPL > 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+        for (int i = 0; i < CPL; ++i) {
+            const int c = lane + 64 * i;
+            keep[i] = c < chunks ? xr[c] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+            float x[8];
+            unpack8(keep[i], x);
+            if (lane + 64 * i < chunks) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+            }
+        }
+    } else {
+        for (int c = lane; c < chunks; c += 64) {
+            float x[8];
+            unpack8(xr[c], x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
@@ -67,9 +87,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     float acc[NC > 0 ? NC : 1];
 #pragma unroll
     for (int q = 0; q < (NC > 0 ? NC : 1); ++q) acc[q] = 0.f;
-    for (int c = lane; c < chunks; c += 64) {
+    constexpr int TRIPS = CPL > 0 ? CPL : 1 << 30;
+#pragma unroll
+    for (int i = 0; i < TRIPS; ++i) {
+        const int c = lane + 64 * i;
+        if (c >= chunks) break;
         float x[8], g[8];
-        unpack8(xr[c], x);
+        unpack8(CPL > 0 ? keep[CPL > 0 ? i : 0] : xr[c], x);
         unpack8(gain[c], g);
         uint4 o;
         o.x = pack_bf16x2(x[0] * r * g[0], x[1] * r * g[1]);
@@ -318,12 +342,25 @@ egg_status launch_embed_rows(eggroll_ctx* c, int64_t rows, int d, int vocab, con
     return check_hip(c, hipGetLastError(), "embed_rows launch");
 }
 
+// rows of up to 2048 / 4096 values are held in registers (4 / 8 chunks per lane), longer ones take the two-pass form
+template <int NC>
+static void launch_rmsnorm_nc(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y, const NormProj& np)
+{
+    const dim3 g((unsigned)((rows + 3) / 4)), b(256);
+    const int chunks = d / 8;
+#define EGG_NORM(CPL) \
+    hipLaunchKernelGGL((rmsnorm_kernel<NC, CPL>), g, b, 0, c->stream, (const uint4*)X, (const uint4*)gain, (uint4*)Y, rows, chunks, 1.0f / (float)d, eps, np)
+    if (chunks <= 256) EGG_NORM(4);
+    else if (chunks <= 512) EGG_NORM(8);
+    else EGG_NORM(0);
+#undef EGG_NORM
+}
+
 egg_status launch_rmsnorm(eggroll_ctx* c, int64_t rows, int d, float eps, const void* gain, const void* X, void* Y)
 {
     if (rows == 0) return EGG_OK;
     KernelScope ks(c, "rmsnorm");
-    hipLaunchKernelGGL(rmsnorm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->stream, (const uint4*)X,
-                       (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, NormProj{});
+    launch_rmsnorm_nc<0>(c, rows, d, eps, gain, X, Y, NormProj{});
     return check_hip(c, hipGetLastError(), "rmsnorm launch");
 }
 
@@ -339,11 +376,10 @@ egg_status launch_rmsnorm_proj(eggroll_ctx* c, int64_t rows, int S, int d, float
     }
     np.S = S;
     KernelScope ks(c, "rmsnorm_project");
-    const dim3 g((unsigned)((rows + 3) / 4)), b(256);
     if (nc == 1)
-        hipLaunchKernelGGL(rmsnorm_kernel<1>, g, b, 0, c->stream, (const uint4*)X, (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, np);
+        launch_rmsnorm_nc<1>(c, rows, d, eps, gain, X, Y, np);
     else if (nc == 3)
-        hipLaunchKernelGGL(rmsnorm_kernel<3>, g, b, 0, c->stream, (const uint4*)X, (const uint4*)gain, (uint4*)Y, rows, d / 8, 1.0f / (float)d, eps, np);
+        launch_rmsnorm_nc<3>(c, rows, d, eps, gain, X, Y, np);
     else
         return fail(c, EGG_EINVAL, "rmsnorm_proj: %d consumers", nc);
     return check_hip(c, hipGetLastError(), "rmsnorm_project launch");
