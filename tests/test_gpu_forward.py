@@ -96,6 +96,50 @@ def test_ragged_shapes(ctx, shape):
         assert_close_bf16_factors(y0, ref_forward(wl, member_begin=3, W=Z), "W=0 " + str(shape))
 
 
+PERSISTENT = [  # d_out, d_in, N, S, rank, act, residual: >= 192 tiles of 256 x 256, bf16 in and out, 64 | S and 64 | d_in --
+    # the persistent kernel with the store-only epilogue; tile edges ragged in both directions
+    (1028, 128, 163, 64, 1, 0, False),
+    (1028, 192, 163, 64, 4, 1, False),
+    (772, 64, 131, 128, 8, 0, True),
+    (1284, 128, 81, 128, 2, 1, True),
+    (2052, 64, 25, 256, 1, 1, False),
+]
+
+
+@pytest.mark.parametrize("case", PERSISTENT)
+def test_persistent_kernel_ragged_tiles(ctx, case):
+    """One workgroup per compute unit walking several tiles each, last row and column tiles partial, every store-only epilogue
+    variant (plain, GELU, residual, both), perturbed and unperturbed."""
+    import torch
+    d_out, d_in, N, S, r, act, resid = case
+    wl = inputs.make_linear("p", "bf16", d_out, d_in, N, S, r, 0.05, 90 + d_out)
+    wl.noise_seed, wl.step, wl.layer = 7, 3, 12
+    R = N * S
+    assert ((d_out + 255) // 256) * ((R + 255) // 256) >= 192 and (R % 256 or d_out % 256)
+    dW, dX = to_device(wl.W, "bf16"), to_device(wl.X, "bf16")
+    Rn = inputs.round_to_bf16(np.random.default_rng(d_out).standard_normal((R, d_out)).astype(np.float32)) if resid else None
+    key, shape = eb.make_key(7, 3, 12), eb.make_shape(5, N, S, d_out, d_in, r)
+    for sigma in (0.05, 0.0):
+        Y = torch.full((R, d_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+        guard = torch.full((4096,), 7.0, dtype=torch.bfloat16, device="cuda")   # allocated right behind Y: stays untouched
+        if resid:
+            ctx.eggroll_perturbed_forward_add(key, shape, sigma, act, dW, dX, to_device(Rn, "bf16"), Y)
+        else:
+            ctx.eggroll_perturbed_forward(key, shape, sigma, act, dW, dX, Y)
+        torch.cuda.synchronize()
+        ref = oracle.forward(7, 3, 12, 5, N, S, d_out, d_in, r, oracle.NOISE_BF16, sigma, act, wl.W, wl.X)
+        if resid:
+            ref = ref + Rn.astype(np.float64)
+        assert_close(to_numpy(Y), ref, 1e-2, "%s sigma %g" % (case, sigma))
+        assert bool((guard == 7.0).all())
+    # the correction on its own (W = 0): what the folded extra MFMA adds, at the tolerance of the bf16 factors
+    Y0 = torch.empty((R, d_out), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_perturbed_forward(key, shape, 0.05, 0, torch.zeros_like(dW), dX, Y0)
+    torch.cuda.synchronize()
+    ref0 = oracle.forward(7, 3, 12, 5, N, S, d_out, d_in, r, oracle.NOISE_BF16, 0.05, 0, np.zeros_like(wl.W), wl.X)
+    assert_close(to_numpy(Y0), ref0, 1e-2, "W = 0 %s" % (case,))
+
+
 def test_big_tile_path_bf16(ctx):
     # enough 256x256 tiles to take the large-tile kernel; K = 136 leaves a partial K-tile
     wl = inputs.make_linear("big", "bf16", 3072, 136, 4096, 1, 1, 0.02, 78)
