@@ -87,13 +87,10 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
     float acc[NC > 0 ? NC : 1];
 #pragma unroll
     for (int q = 0; q < (NC > 0 ? NC : 1); ++q) acc[q] = 0.f;
-    constexpr int TRIPS = CPL > 0 ? CPL : 1 << 30;
-#pragma unroll
-    for (int i = 0; i < TRIPS; ++i) {
-        const int c = lane + 64 * i;
-        if (c >= chunks) break;
+    // one 16-byte chunk of the row: scale, store, and add its share of the fused projections
+    auto chunk = [&](int c, const uint4& xv) __attribute__((always_inline)) {
         float x[8], g[8];
-        unpack8(CPL > 0 ? keep[CPL > 0 ? i : 0] : xr[c], x);
+        unpack8(xv, x);
         unpack8(gain[c], g);
         uint4 o;
         o.x = pack_bf16x2(x[0] * r * g[0], x[1] * r * g[1]);
@@ -112,6 +109,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
                 for (int e = 0; e < 8; ++e) acc[q] = fmaf(y[e], b[e], acc[q]);
             }
         }
+    };
+    if constexpr (CPL > 0) {
+#pragma unroll
+        for (int i = 0; i < CPL; ++i)
+            if (lane + 64 * i < chunks) chunk(lane + 64 * i, keep[i]);
+    } else {
+        for (int c = lane; c < chunks; c += 64) chunk(c, xr[c]);   // (not unrolled: the trip count is a run-time value)
     }
     if constexpr (NC > 0) {
 #pragma unroll
