@@ -23,7 +23,8 @@
  * Threefry-2x32-20 engine; the normal transform against N(0,1) moments / KS and the K_0 product density of the
  * mean-field appendix; the integer map exhaustively; forward/update against brute-force numpy,
  * closed forms and the identities of Sec. 4.2.  Parity against the authors' own JAX noise stream
- * is unpinned: the paper does not publish its stream and it need not be matched.
+ * is unpinned: the paper does not publish its stream and it need not be matched.  Parity unpinned as well:
+ * the rounding mode of the EXP2 / LOG2 table entries of oracle_loglik_i8 (see there).
  *
  * Build: gcc -O2 -fopenmp -fPIC -shared -o liboracle.so eggroll_oracle.c -lm
  */
@@ -739,7 +740,8 @@ int oracle_egg_forward_i8(uint64_t seed, uint32_t step, uint32_t layer, int64_t 
  *   EXP2[i] = 16 * 2^(i/16),   LOG2[s] = 16 * log2(s / 16)
  * the log-likelihood of token t' in units of 1/16 bit (logits count sixteenths of a bit).  Reading: both
  * tables hold their formula rounded to the nearest integer (the paper calls them integer lookup tables and
- * does not say how the entries are rounded).  logits: int8 [rows][256], targets: uint8 [rows]; out: int32
+ * does not say how the entries are rounded): for that choice parity is unpinned -- the pin holds the result to
+ * the real log-softmax within 1.5/16 bit, which any rounding of the entries satisfies.  logits: int8 [rows][256], targets: uint8 [rows]; out: int32
  * [rows], added to what is there when accumulate != 0 (a member's fitness is the sum over its tokens).
  */
 void oracle_loglik_i8(int64_t rows, const int8_t* logits, const uint8_t* targets, int accumulate, int32_t* out)
