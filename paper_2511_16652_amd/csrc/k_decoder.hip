@@ -168,22 +168,53 @@ __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restri
     const int SP = (S + 31) & ~31;
     constexpr int CPR = HD / 8;  // 16-byte chunks per row
 
+    // The wave's query rows first (they are needed last): 32 rows, the lane's half of every 16 columns.
+    const int nqb = SP / 32;
+    const int qb = wave < 4 ? wave : 11 - wave;
+    const int n = lane & 31, h = lane >> 5;
+    const int qrow = qb * 32 + n;
+    u32x4 qf[HD / 16];
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) {
+        qf[ks] = u32x4{0u, 0u, 0u, 0u};
+        if (qb < nqb && qrow < S) qf[ks] = *(const u32x4*)(Qg + (int64_t)qrow * ld + (2 * ks + h) * 8);
+    }
     if (Bo && tid < CPR) *(uint4*)(sB + tid * 16) = *(const uint4*)(Bo + (member * heads + head) * (int64_t)HD + tid * 8);
-    for (int idx = tid; idx < SP * CPR; idx += 512) {
+    // K and V of the head pass through registers on their way to LDS.  Every load of a thread is issued before the first
+    // LDS write (fixed trip counts for S = SMAX, predicated), so the workgroup pays the memory latency once, not per 16 bytes.
+    constexpr int KIT = C::SMAX * CPR / 512, VIT = (C::SMAX / 64) * CPR / 8;
+    static_assert(C::SMAX * CPR % 512 == 0 && (C::SMAX / 64) * CPR % 8 == 0, "whole passes of the workgroup");
+    uint4 kreg[KIT], vreg[VIT];
+#pragma unroll
+    for (int i = 0; i < KIT; ++i) {
+        const int idx = i * 512 + tid;
         const int row = idx / CPR, ch = idx - row * CPR;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row < S) v = *(const uint4*)(Kg + (int64_t)row * ld + ch * 8);
-        *(uint4*)(sK + row * C::KP + ch * 16) = v;
+        kreg[i] = make_uint4(0, 0, 0, 0);
+        if (row < S) kreg[i] = *(const uint4*)(Kg + (int64_t)row * ld + ch * 8);
     }
     // V: a wave's 64 lanes take 64 consecutive keys of one 8-column chunk, so each 2-byte transposed store
     // instruction writes 128 contiguous bytes of one V^T row
-    for (int it = wave; it < (SP / 64 + (SP % 64 ? 1 : 0)) * CPR; it += 8) {
+#pragma unroll
+    for (int i = 0; i < VIT; ++i) {
+        const int it = i * 8 + wave;
+        const int kg = it / CPR, ch = it - kg * CPR;
+        const int key = kg * 64 + lane;
+        vreg[i] = make_uint4(0, 0, 0, 0);
+        if (key < S) vreg[i] = *(const uint4*)(Vg + (int64_t)key * ld + ch * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < KIT; ++i) {
+        const int idx = i * 512 + tid;
+        const int row = idx / CPR, ch = idx - row * CPR;
+        if (row < SP) *(uint4*)(sK + row * C::KP + ch * 16) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VIT; ++i) {
+        const int it = i * 8 + wave;
         const int kg = it / CPR, ch = it - kg * CPR;
         const int key = kg * 64 + lane;
         if (key < SP) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (key < S) v = *(const uint4*)(Vg + (int64_t)key * ld + ch * 8);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            const uint32_t w[4] = {vreg[i].x, vreg[i].y, vreg[i].z, vreg[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 *(uint16_t*)(sV + (ch * 8 + 2 * e) * C::VP + key * 2) = (uint16_t)(w[e] & 0xFFFFu);
@@ -192,18 +223,7 @@ __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restri
         }
     }
     __syncthreads();
-
-    const int nqb = SP / 32;
-    const int qb = wave < 4 ? wave : 11 - wave;
     if (qb >= nqb) return;  // no barrier follows
-    const int n = lane & 31, h = lane >> 5;
-    const int qrow = qb * 32 + n;
-    u32x4 qf[HD / 16];
-#pragma unroll
-    for (int ks = 0; ks < HD / 16; ++ks) {
-        qf[ks] = u32x4{0u, 0u, 0u, 0u};
-        if (qrow < S) qf[ks] = *(const u32x4*)(Qg + (int64_t)qrow * ld + (2 * ks + h) * 8);
-    }
     f32x16 oacc[HD / 32];
 #pragma unroll
     for (int mb = 0; mb < HD / 32; ++mb)
