@@ -104,7 +104,10 @@ def test_embed_rows(ctx):
 
 
 @pytest.mark.parametrize("members,S,heads,hd", [(3, 1, 2, 32), (2, 5, 3, 64), (2, 32, 2, 128), (3, 100, 2, 128),
-                                               (2, 256, 2, 128), (1, 255, 1, 64), (2, 64, 4, 32)])
+                                               (2, 256, 2, 128), (1, 255, 1, 64), (2, 64, 4, 32),
+                                               # full-length members, more (member, head) items than compute units: the
+                                               # persistent kernel's workgroups walk one or two items each
+                                               (40, 256, 8, 64), (17, 256, 16, 128)])
 def test_causal_attention(ctx, members, S, heads, hd):
     import torch
     d = heads * hd
@@ -135,7 +138,7 @@ def test_causal_attention(ctx, members, S, heads, hd):
         assert np.array_equal(to_numpy(O2)[keep], got[keep])
 
 
-@pytest.mark.parametrize("members,S,heads,hd", [(5, 40, 2, 64), (3, 256, 4, 128), (7, 33, 3, 32)])
+@pytest.mark.parametrize("members,S,heads,hd", [(5, 40, 2, 64), (3, 256, 4, 128), (7, 33, 3, 32), (33, 256, 8, 64)])
 def test_attention_with_the_next_layers_projections(ctx, members, S, heads, hd):
     """The by-product of the attention kernel: its stored rows times the consuming layer's factors B, per member."""
     import torch
