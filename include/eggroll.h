@@ -162,10 +162,10 @@ egg_status eggroll_perturbed_forward_add(eggroll_ctx* ctx, egg_key key, const eg
  *   R_in:   optional residual as in (2a); NULL = none.
  *   t_in:   optional [R][rank] fp32 (device), the projections X B_i of THIS layer as an earlier call delivered them
  *           through its t_next; NULL = the projection pass of (2) reads X and forms them.  Read only when sigma > 0.
- *   want_next != 0: additionally t_next[row] = sum_j Y[row][j] * B'_{member(row)}[j] (fp32, device, [R]), where B'
- *           are the rank-1 factors B of the layer with noise id next_layer (same seed and step; its d_in is this d_out),
- *           formed from the very bf16 values stored to Y -- what that layer's own projection pass would compute,
- *           summed in another order.  This form exists for io_dtype = y_dtype = EGG_BF16, rank 1, act = EGG_ACT_GELU,
+ *   want_next != 0: additionally t_next[row][l] = sum_j Y[row][j] * B'_{member(row)}[j][l] (fp32, device, [R][rank]),
+ *           where B' are the factors B of the layer with noise id next_layer (same seed, step and rank; its d_in is this
+ *           d_out), formed from the very bf16 values stored to Y -- what that layer's own projection pass would compute,
+ *           summed in another order.  This form exists for io_dtype = y_dtype = EGG_BF16, rank 1, 2 or 4, act = EGG_ACT_GELU,
  *           R_in = NULL, sigma > 0, no antithetic pairs, rows_per_member and d_in multiples of 64, and at least 192
  *           output tiles of 256 x 256; anything else returns EGG_EUNSUPPORTED before any work is enqueued, and the
  *           caller uses plain calls.  The factors B' are drawn into context scratch.

@@ -183,18 +183,18 @@ egg_status checked_forward(eggroll_ctx* c, egg_key key, const egg_shape* shape, 
         if (next_layer >> 31) return fail(c, EGG_EINVAL, "next_layer must be < 2^31");
         if (!forward_fuses_next_projection(*shape, io_dtype, y_dtype, sigma, act, R_in != nullptr))
             return fail(c, EGG_EUNSUPPORTED,
-                        "the next layer's projections are formed only by bf16 rank-1 GELU layers without residual, sigma > 0, 64 | rows_per_member, "
+                        "the next layer's projections are formed only by bf16 GELU layers of rank 1, 2 or 4 without residual, sigma > 0, 64 | rows_per_member, "
                         "64 | d_in and at least 192 output tiles of 256 x 256");
     }
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, EGG_EHIP, "hipSetDevice");
     NextProjection np{nullptr, t_next};
     if (want_next) {
         // the next layer's B factors over this layer's outputs, exactly what eggroll_noise_gen writes for that layer
-        const size_t bytes = (size_t)shape->member_count * shape->d_out * 2;
+        const size_t bytes = (size_t)shape->member_count * shape->d_out * shape->rank * 2;
         s = reserve(c, c->next_b, bytes);
         if (s != EGG_OK) return s;
         s = launch_noise(c, make_stream_key(key.seed, key.step, next_layer, 1), (uint32_t)shape->member_begin, shape->member_count,
-                         shape->d_out, EGG_BF16, EGG_NORMAL, 0, c->next_b.p);
+                         (int64_t)shape->d_out * shape->rank, EGG_BF16, EGG_NORMAL, 0, c->next_b.p);
         if (s != EGG_OK) return s;
         np.B = c->next_b.p;
     }

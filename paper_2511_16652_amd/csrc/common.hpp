@@ -103,8 +103,9 @@ egg_status launch_noise(eggroll_ctx* c, const StreamKey& k, uint32_t member_begi
 egg_status launch_project(eggroll_ctx* c, const StreamKey& kb, const egg_shape& s, egg_dtype io, const void* X,
                           float* t, void* B_cache, bool panel);
 // A layer whose output feeds the next perturbed layer directly (up-projection -> down-projection) can form that
-// layer's rank-1 projections in its own epilogue, from the bf16 values it stores: B = the next layer's factors
-// [member][d_out] bf16, t = where the projections go.  Supported where forward_fuses_next_projection says so.
+// layer's projections (same rank, 1, 2 or 4) in its own epilogue, from the bf16 values it stores: B = the next layer's
+// factors [member][d_out][rank] bf16, t = where the projections [rows][rank] go.  Supported where
+// forward_fuses_next_projection says so.
 struct NextProjection {
     const void* B;
     float* t;

@@ -53,8 +53,8 @@ struct FwdArgs {
     int mma_corr;   // !REGEN, bf16, S % CORR_COLS == 0: the correction is folded in by one extra MFMA per block
     int pair_share; // REGEN with antithetic pairs: neighbouring lanes share their factors
     const void* resid;  // optional [R][d_out] of the output dtype, added after the activation (residual stream)
-    const void* next_B;  // LEAN_PROJ: the next layer's factors B[member][d_out] (bf16, rank 1)
-    float* next_part;    // LEAN_PROJ: partial projections [d_out / 128 slabs][R]
+    const void* next_B;  // LEAN_PROJ: the next layer's factors B[member][d_out][rank] (bf16; its rank is this layer's)
+    float* next_part;    // LEAN_PROJ: partial projections [d_out / 128 slabs][R][rank]
 };
 
 // Where the lane's factor entries A_i[m..m+3][0..RANK-1] come from:
@@ -75,6 +75,19 @@ struct FwdArgs {
 // by a projection pass: a lane adds its 4 x 8 products per column, the four lane groups of a column are summed by two
 // shuffles, and the sum over the wave tile's 128 rows goes to a slab-partial that a small pass adds up in fixed order.
 enum { LEAN_ON = 1, LEAN_GELU = 2, LEAN_RESID = 4, LEAN_PROJ = 8 };
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// sum over the 16 lanes of a DPP row, left in every lane of the row
+__device__ __forceinline__ float row_sum16(float x)
+{
+#define EGG_DPP_ADD(CTRL) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+    EGG_DPP_ADD(0xB1)   // quad_perm [1, 0, 3, 2]
+    EGG_DPP_ADD(0x4E)   // quad_perm [2, 3, 0, 1]
+    EGG_DPP_ADD(0x141)  // row_half_mirror: the other quad of the half row
+    EGG_DPP_ADD(0x140)  // row_mirror: the other half row
+#undef EGG_DPP_ADD
+    return x;
+}
 template <bool BF16, int RANK, bool REGEN, int BLK = 32, int LEAN = 0>
 struct FwdEpi {
     static_assert(LEAN == 0 || (BF16 && !REGEN), "the lean epilogue stores bf16 and regenerates nothing");
@@ -105,11 +118,18 @@ struct FwdEpi {
     // epilogue parks the operands in its LDS slice instead (see prefetch).
     static constexpr bool PREFETCH = RANK <= 4 && LEAN == 0;
     static constexpr int LDS_T = 0, LDS_A = 2048;  // byte offsets of t[64][RANK] fp32 and A_i[128][RANK] bf16 in the slice
-    static constexpr int LDS_NB = 3072;            // LEAN_PROJ (rank 1): the next layer's B'[128] bf16
+    static constexpr int LDS_NB = 3072;            // LEAN_PROJ: the next layer's B'[128][RANK] bf16
     static constexpr bool PROJ = (LEAN & LEAN_PROJ) != 0;
-    static_assert(!PROJ || RANK == 1, "the fused next-layer projection is the rank-1 form");
-    uint2 nb[PROJ ? 8 : 1];  // B' of the lane's rows, per row block (4 bf16 each)
-    float tn = 0.f;          // the lane's part of t'[n] for the current column
+    static_assert(!PROJ || RANK == 1 || RANK == 2 || RANK == 4, "the three runs of 256 RANK bytes fill the wave's 4 KB slice at rank 4");
+    // Rank 1: B' of the lane's 4 rows of a row block as two bf16 pairs along the rows -- (r0, r1) and (r2, r3), the packing
+    // of the values on their way to the store -- so that a column's share is two packed dot products per row block.
+    // Rank 2 and 4 would need 16 RANK registers that way; there the products are formed when the staged rows are read back
+    // for the store (flush): a lane then holds 8 consecutive outputs of one row, always the same 8 of the wave tile's 128,
+    // and needs B' of those 8 only: bp[l][q] = (B'[8 cc + 2q][l], B'[8 cc + 2q + 1][l]), cc = lane % 16.
+    static constexpr bool PROJ_ROWS = PROJ && RANK == 1, PROJ_FLUSH = PROJ && RANK > 1;
+    uint32_t nb[PROJ_ROWS ? 8 : 1][2];
+    uint32_t bp[PROJ_FLUSH ? RANK : 1][4];
+    float tn = 0.f;  // rank 1: the lane's part of t'[n] for the current column
     // prefetched A rows of the lane, per (row block, group of CORR_COLS columns that share one member), and the
     // prefetched t of the lane's columns, per column block.  With 16x16 blocks a wave tile has twice the row
     // blocks; one member per 64 columns (the width of every wave tile launched here) keeps the register count.
@@ -165,8 +185,12 @@ struct FwdEpi {
                                                  (egg_lds_void*)(sty.base + LDS_A + k * 256), 4, 0, 0);
             }
             if constexpr (PROJ) {
-                const uint32_t* bsrc = (const uint32_t*)((const uint16_t*)a.next_B + member_l * a.d_out + mw0);
-                __builtin_amdgcn_global_load_lds((egg_glb_void*)(bsrc + min(lane, a_last)), (egg_lds_void*)(sty.base + LDS_NB), 4, 0, 0);
+                const uint32_t* bsrc = (const uint32_t*)((const uint16_t*)a.next_B + (member_l * a.d_out + mw0) * RANK);
+#pragma unroll
+                for (int k = 0; k < RANK; ++k) {
+                    __builtin_amdgcn_global_load_lds((egg_glb_void*)(bsrc + min(k * 64 + lane, a_last)),
+                                                     (egg_lds_void*)(sty.base + LDS_NB + k * 256), 4, 0, 0);
+                }
             }
         } else if constexpr (!REGEN && BF16 && PREFETCH) {
             static_assert(MB <= PF_MB && NB <= PF_NB && NB * BLK <= PF_NG * CORR_COLS, "prefetch storage");
@@ -188,8 +212,34 @@ struct FwdEpi {
                 if (nw0 >= n_rows || mw0 >= a.d_out) return;  // nothing of this wave tile is stored
                 if constexpr (PROJ) {
                     // into registers now: the slice becomes the staging area of the stores
+                    if constexpr (PROJ_ROWS) {
 #pragma unroll
-                    for (int i = 0; i < MB; ++i) nb[i] = *(const uint2*)(sty.base + LDS_NB + (i * BLK + (lane / BLK) * 4) * 2);
+                        for (int i = 0; i < MB; ++i) {
+                            const uint2 w = *(const uint2*)(sty.base + LDS_NB + (i * BLK + (lane / BLK) * 4) * 2);
+                            nb[i][0] = w.x;
+                            nb[i][1] = w.y;
+                        }
+                    } else {
+                        const int cc = lane & 15;
+                        const int rows_left = a.d_out - (mw0 + cc * 8);  // rows past d_out hold copies: their factors count as 0
+                        const char* br = sty.base + LDS_NB + cc * 8 * RANK * 2;  // 8 rows x RANK bf16, l fastest
+                        uint32_t w[4 * RANK];
+#pragma unroll
+                        for (int k = 0; k < RANK; ++k) {
+                            const u32x4 v = *(const u32x4*)(br + 16 * k);
+                            w[4 * k] = v[0]; w[4 * k + 1] = v[1]; w[4 * k + 2] = v[2]; w[4 * k + 3] = v[3];
+                        }
+                        constexpr int WPR = RANK / 2;  // dwords per row
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int lp = 0; lp < WPR; ++lp) {
+                                const uint32_t ra = w[(2 * q) * WPR + lp], rb = w[(2 * q + 1) * WPR + lp];  // rows 2q, 2q + 1: (l, l + 1)
+                                const bool in = 2 * q < rows_left;
+                                bp[2 * lp][q] = in ? ((ra & 0xFFFFu) | (rb << 16)) : 0u;
+                                bp[2 * lp + 1][q] = in ? ((ra >> 16) | (rb & 0xFFFF0000u)) : 0u;
+                            }
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
@@ -280,7 +330,7 @@ struct FwdEpi {
 
     __device__ __forceinline__ void column(int n, bool valid)
     {
-        if constexpr (PROJ) tn = 0.f;
+        if constexpr (PROJ_ROWS) tn = 0.f;
         if constexpr (LEAN != 0) return;
         if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
@@ -298,12 +348,11 @@ struct FwdEpi {
             if constexpr ((LEAN & LEAN_GELU) != 0) gelu_bf16_grade4(y);
             static_assert((LEAN & LEAN_RESID) == 0, "not combined with the residual form");
             const uint32_t p0 = pack_bf16x2(y[0], y[1]), p1 = pack_bf16x2(y[2], y[3]);
-            if (valid && m < a.d_out) {
-                float acc = bf16_lo(p0) * bf16_lo(nb[I].x);
-                acc = fmaf(bf16_hi(p0), bf16_hi(nb[I].x), acc);
-                acc = fmaf(bf16_lo(p1), bf16_lo(nb[I].y), acc);
-                acc = fmaf(bf16_hi(p1), bf16_hi(nb[I].y), acc);
-                tn += acc;
+            if constexpr (PROJ_ROWS) {
+                if (valid && m < a.d_out) {
+                    tn = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p0), __builtin_bit_cast(bf16x2_t, nb[I][0]), tn, false);
+                    tn = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p1), __builtin_bit_cast(bf16x2_t, nb[I][1]), tn, false);
+                }
             }
             sty.put(a.wtm_pitch, ml, p0, p1);
         } else {
@@ -428,8 +477,47 @@ struct FwdEpi {
     template <int WTM>
     __device__ __forceinline__ void flush(int mw0, int nb0, int n_rows)
     {
-        if (LEAN != 0 || a.y_bf16) sty.template flush<WTM, BLK>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
-        if constexpr (PROJ) {
+        if constexpr (PROJ_FLUSH) {
+            // The stager's flush with the projections formed on the way out: the 16 lanes that read one staged row (8 outputs
+            // each) multiply them with their B' and add up across the row of lanes.
+            static_assert(WTM == 128 && BLK == 16, "16 chunks of 8 outputs per staged row, 4 rows per pass of the wave");
+            constexpr int P = stager_t::pitch(WTM);
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the wave's own LDS writes have landed
+            __builtin_amdgcn_wave_barrier();
+            const int cc = sty.lane & 15;
+            const int m = mw0 + cc * 8;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int r = it * 4 + (sty.lane >> 4);
+                const int n = nb0 + r;
+                const u32x4 v = *(const u32x4*)(sty.base + r * P + (((cc ^ r) & 15) << 4));
+                if (n < n_rows && m < a.d_out) {
+                    uint16_t* dst = (uint16_t*)a.Y + (int64_t)n * a.d_out + m;
+                    if (m + 8 <= a.d_out) *(u32x4*)dst = v;
+                    else *(uint2*)dst = make_uint2(v[0], v[1]);
+                }
+                const uint32_t vw[4] = {v[0], v[1], v[2], v[3]};  // (bit_cast of a vector element, v[q], reads element 0 whatever q is)
+                float ts[RANK];
+#pragma unroll
+                for (int l = 0; l < RANK; ++l) {
+                    ts[l] = 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        ts[l] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, vw[q]), __builtin_bit_cast(bf16x2_t, bp[l][q]), ts[l], false);
+                }
+#pragma unroll
+                for (int l = 0; l < RANK; ++l) ts[l] = row_sum16(ts[l]);
+                if (cc == 0 && n < n_rows && mw0 < a.d_out) {
+                    float* dst = a.next_part + ((int64_t)(mw0 >> 7) * n_rows + n) * RANK;
+                    if constexpr (RANK == 2) *(float2*)dst = make_float2(ts[0], ts[1]);
+                    else *(float4*)dst = make_float4(ts[0], ts[1], ts[2], ts[3]);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();  // the slice is reused by the next column block
+        } else {
+            if (LEAN != 0 || a.y_bf16) sty.template flush<WTM, BLK>((uint16_t*)a.Y, a.d_out, mw0, nb0, n_rows, a.d_out);
+        }
+        if constexpr (PROJ_ROWS) {
             static_assert(WTM == 128 && BLK == 16, "slabs of 128 rows, four lane groups per column");
             float tsum = tn + __shfl_xor(tn, 16, 64);
             tsum += __shfl_xor(tsum, 32, 64);
@@ -496,7 +584,7 @@ bool forward_fuses_next_projection(const egg_shape& s, egg_dtype io, egg_dtype y
 {
     const int64_t R = s.member_count * (int64_t)s.rows_per_member;
     const int64_t big_tiles = ((s.d_out + 255) / 256) * ((R + 255) / 256);
-    return io == EGG_BF16 && yd == EGG_BF16 && sigma != 0.f && s.rank == 1 && !s.antithetic && act == EGG_ACT_GELU && !resid &&
+    return io == EGG_BF16 && yd == EGG_BF16 && sigma != 0.f && (s.rank == 1 || s.rank == 2 || s.rank == 4) && !s.antithetic && act == EGG_ACT_GELU && !resid &&
            s.rows_per_member % 64 == 0 && s.rows_per_member > 1 && big_tiles >= 192 && s.d_in % 64 == 0;
 }
 
@@ -548,18 +636,19 @@ static egg_status launch_forward_t(eggroll_ctx* c, const StreamKey& ka, const eg
             // accumulators): the store-only epilogue with the activation and the residual fixed at compile time
             const bool folded = !REGEN && Epi::RANK_ELEMS_BYTES <= 16 && ea.c != 0.f && ea.S % Epi::CORR_COLS == 0;
             if (next) {
-                // the fused next-layer projection exists in one form: rank 1, folded correction, GELU, no residual
-                if constexpr (!REGEN && RANK == 1) {
+                // the fused next-layer projection exists in one form: rank 1, 2 or 4 (the next layer's too), folded correction,
+                // GELU, no residual
+                if constexpr (!REGEN && (RANK == 1 || RANK == 2 || RANK == 4)) {
                     if (forward_fuses_next_projection(s, EGG_BF16, yd, sigma, act, resid != nullptr)) {
                         const int slabs = (s.d_out + 127) / 128;
-                        egg_status st = reserve(c, c->proj_part, (size_t)slabs * R * sizeof(float));
+                        egg_status st = reserve(c, c->proj_part, (size_t)slabs * R * RANK * sizeof(float));
                         if (st != EGG_OK) return st;
                         ea.next_B = next->B;
                         ea.next_part = (float*)c->proj_part.p;
-                        st = launch_gemm_persistent<MmaBf16Blk16, 256, 256, 2, 4, FwdEpi<true, 1, false, 16, LEAN_ON | LEAN_GELU | LEAN_PROJ>>(
+                        st = launch_gemm_persistent<MmaBf16Blk16, 256, 256, 2, 4, FwdEpi<true, RANK, false, 16, LEAN_ON | LEAN_GELU | LEAN_PROJ>>(
                             c, "forward_gemm_bf16", P, Q, kchunks, ea);
                         if (st != EGG_OK) return st;
-                        return launch_sum_slabs(c, (const float*)c->proj_part.p, slabs, R, next->t);
+                        return launch_sum_slabs(c, (const float*)c->proj_part.p, slabs, R * RANK, next->t);
                     }
                 }
                 return fail(c, EGG_EINVAL, "this layer cannot form the next layer's projections (ask forward_fuses_next_projection first)");

@@ -32,7 +32,18 @@ egg_status launch_mlp_stack_forward(eggroll_ctx* c, egg_key key, const egg_shape
     const int d = s.d_in, S = s.rows_per_member;
     const int64_t cm = pick_chunk(s.member_count, S, chunk_members, int64_t(1) << 18);
     const size_t rows_max = (size_t)cm * S;
-    const size_t need = ((rows_max * d_ff * 2 + 255) & ~size_t(255)) + ((rows_max * d * 2 + 255) & ~size_t(255));
+    auto pad = [](size_t b) { return (b + 255) & ~size_t(255); };
+    // Rank 1: the up-projection's epilogue also projects what it stores onto the down-projection's factors, where it can, so
+    // that the widest activation is not read a second time by a projection pass.  (At rank 2 and 4 the form exists too, but
+    // measured on 2^18 rows of 2048 -> 8192 -> 2048 it only breaks even -- rank 4, 64 rows per member: 15.5 against 15.4 ms
+    // for the pair of layers; rank 2: 15.0 against 15.1 -- because the factors it reads have to be materialised first,
+    // 4096 x 8192 x 4 normals per chunk, where the projection pass draws them on the fly.)
+    egg_shape probe = s;
+    probe.member_count = cm;
+    probe.d_out = d_ff;
+    const bool fuse_dn = s.rank == 1 && forward_fuses_next_projection(probe, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, false);
+    size_t need = pad(rows_max * d_ff * 2) + pad(rows_max * d * 2);
+    if (fuse_dn) need += pad((size_t)cm * d_ff * s.rank * 2) + pad(rows_max * s.rank * sizeof(float));
     egg_status st = reserve(c, c->model, need);
     if (st != EGG_OK) return st;
     for (int64_t m0 = 0; m0 < s.member_count; m0 += cm) {
@@ -41,20 +52,31 @@ egg_status launch_mlp_stack_forward(eggroll_ctx* c, egg_key key, const egg_shape
         Carver cv{(char*)c->model.p};
         void* u = cv.take(rows_max * d_ff * 2);
         void* h = cv.take(rows_max * d * 2);
+        void* Bdn = fuse_dn ? cv.take((size_t)cm * d_ff * s.rank * 2) : nullptr;
+        float* tdn = fuse_dn ? (float*)cv.take(rows_max * s.rank * sizeof(float)) : nullptr;
         egg_shape up = s, dn = s;
         up.member_begin = dn.member_begin = s.member_begin + m0;
         up.member_count = dn.member_count = n;
         up.d_out = d_ff; up.d_in = d;
         dn.d_out = d; dn.d_in = d_ff;
+        // (a last chunk with fewer members may fall below the tile count the fused form needs)
+        const bool fuse = fuse_dn && forward_fuses_next_projection(up, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, false);
         const char* in = (const char*)X + r0 * d * 2;
         for (int l = 0; l < L; ++l) {
             const egg_key k1{key.seed, key.step, key.layer + 2u * (uint32_t)l}, k2{key.seed, key.step, key.layer + 2u * (uint32_t)l + 1u};
+            NextProjection np{Bdn, tdn};
+            if (fuse) {
+                // the down-projection's factors B_i over d_ff for this chunk's members, as its projection pass would draw them
+                st = launch_noise(c, make_stream_key(key.seed, key.step, k2.layer, 1), (uint32_t)up.member_begin, n, (int64_t)d_ff * s.rank,
+                                  EGG_BF16, EGG_NORMAL, 0, Bdn);
+                if (st != EGG_OK) return st;
+            }
             st = forward_linear(c, k1, up, EGG_BF16, EGG_BF16, sigma, EGG_ACT_GELU, (const char*)W1 + (size_t)l * d_ff * d * 2, in, u,
-                                nullptr, nullptr, nullptr);
+                                nullptr, nullptr, nullptr, nullptr, nullptr, fuse ? &np : nullptr);
             if (st != EGG_OK) return st;
             void* out = l == L - 1 ? (void*)((char*)Y + r0 * d * 2) : h;
             st = forward_linear(c, k2, dn, EGG_BF16, EGG_BF16, sigma, EGG_ACT_NONE, (const char*)W2 + (size_t)l * d * d_ff * 2, u, out,
-                                nullptr, nullptr, nullptr);
+                                nullptr, nullptr, nullptr, nullptr, fuse ? tdn : nullptr);
             if (st != EGG_OK) return st;
             in = (const char*)h;
         }

@@ -181,7 +181,11 @@ def _mlp_inputs(d, ff, L, N, S, seed):
     return P, X
 
 
-@pytest.mark.parametrize("d,ff,L,N,S,rank,chunk", [(128, 256, 3, 24, 32, 4, 0), (64, 136, 2, 13, 5, 2, 4), (256, 512, 2, 300, 1, 1, 128)])
+@pytest.mark.parametrize("d,ff,L,N,S,rank,chunk", [(128, 256, 3, 24, 32, 4, 0), (64, 136, 2, 13, 5, 2, 4), (256, 512, 2, 300, 1, 1, 128),
+                                                   # rank 1 and enough 256 x 256 tiles: W1's epilogue forms W2's projections
+                                                   # (the last chunk of the second case, 8 members, is too small for it)
+                                                   (256, 1024, 2, 192, 64, 1, 0), (256, 1024, 2, 200, 64, 1, 192),
+                                                   (256, 1024, 2, 192, 64, 4, 0)])
 def test_mlp_stack_layers_teacher_forced_and_end_to_end(ctx, d, ff, L, N, S, rank, chunk):
     import torch
     sigma, base, mb = 0.02, 40, 3
@@ -199,14 +203,18 @@ def test_mlp_stack_layers_teacher_forced_and_end_to_end(ctx, d, ff, L, N, S, ran
         ref = oracle.forward(0, 0, base + 2 * l + 1, mb, N, S, d, ff, rank, oracle.NOISE_BF16, sigma, 0, P["W2"][l], to_numpy(u))
         assert_close(to_numpy(h2), ref, 1e-2, "W2 of layer %d" % l)
         h = h2
-    # the driver is that chain: same bits, whatever the chunking
+    # the driver is that chain: same bits, whatever the chunking -- except where W1's epilogue forms W2's projections
+    # (another summation order than the projection pass)
     Y = torch.empty_like(Xd)
     ctx.eggroll_mlp_stack_forward(eb.make_key(0, 0, base), eb.make_shape(mb, N, S, d, d, rank), L, ff, sigma, W1, W2, Xd, Y, chunk)
     torch.cuda.synchronize()
-    assert torch.equal(Y.view(torch.int16), h.view(torch.int16))
+    fused = rank == 1 and S % 64 == 0 and (ff // 256) * ((min(N, chunk or N) * S) // 256) >= 192
+    same_bits_or_reordered_sum(Y, h, not fused, "MLP stack driver against the chain of single layers")
     # end to end against the oracle's own chain (no teacher forcing)
     Yo = models.mlp_stack_forward(0, 0, base, range(mb, mb + N), S, rank, sigma, P["W1"], P["W2"], X.reshape(N, S, d))
-    fro = assert_close(to_numpy(Y), Yo.reshape(N * S, d), 2e-2, "MLP stack end to end")
+    # (2 L bf16 roundings deep; the Frobenius ratio carries the bound, the per-entry one has to hold the tail of N S d
+    # entries: a few million in the larger cases)
+    fro = assert_close(to_numpy(Y), Yo.reshape(N * S, d), 3e-2 if N * S * d >= 1e6 else 2e-2, "MLP stack end to end")
     assert fro < 1e-2
     # sigma = 0: the unperturbed stack (every member the same function)
     Y0 = torch.empty_like(Xd)
@@ -235,23 +243,24 @@ def test_mlp_stack_update(ctx):
             assert not np.array_equal(got, W0[l])
 
 
-def test_chained_layers_next_projection_from_the_epilogue(ctx):
-    """Up-projection whose epilogue also forms the next layer's rank-1 projections (from the bf16 values it stores), and
+@pytest.mark.parametrize("rank", [1, 2, 4])
+def test_chained_layers_next_projection_from_the_epilogue(ctx, rank):
+    """Up-projection whose epilogue also forms the next layer's rank-r projections (from the bf16 values it stores), and
     the next layer fed those projections instead of running its own projection pass."""
     import torch
     N, S, d, ff, sigma, l_up, l_dn, mb = 192, 64, 256, 1024, 0.05, 21, 34, 6
     R = N * S
-    wl = inputs.make_linear("up", "bf16", ff, d, N, S, 1, sigma, 71, layer=l_up)
+    wl = inputs.make_linear("up", "bf16", ff, d, N, S, rank, sigma, 71, layer=l_up)
     W2 = inputs.round_to_bf16((np.random.default_rng(72).standard_normal((d, ff)) / np.sqrt(ff)).astype(np.float32))
     Wd, Xd, W2d = bf16_dev(wl.W), bf16_dev(wl.X), bf16_dev(W2)
     U = torch.empty((R, ff), dtype=torch.bfloat16, device="cuda")
-    t_next = torch.full((R,), float("nan"), dtype=torch.float32, device="cuda")
+    t_next = torch.full((R, rank), float("nan"), dtype=torch.float32, device="cuda")
     key_up, key_dn = eb.make_key(3, 1, l_up), eb.make_key(3, 1, l_dn)
-    s_up, s_dn = eb.make_shape(mb, N, S, ff, d, 1), eb.make_shape(mb, N, S, d, ff, 1)
+    s_up, s_dn = eb.make_shape(mb, N, S, ff, d, rank), eb.make_shape(mb, N, S, d, ff, rank)
     ctx.eggroll_perturbed_forward_chained(key_up, s_up, sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
     torch.cuda.synchronize()
     # the layer itself
-    ref = oracle.forward(3, 1, l_up, mb, N, S, ff, d, 1, oracle.NOISE_BF16, sigma, oracle.ACT_GELU, wl.W, wl.X)
+    ref = oracle.forward(3, 1, l_up, mb, N, S, ff, d, rank, oracle.NOISE_BF16, sigma, oracle.ACT_GELU, wl.W, wl.X)
     assert_close(to_numpy(U), ref, 1e-2, "up-projection")
     U2 = torch.empty_like(U)
     ctx.eggroll_perturbed_forward(key_up, s_up, sigma, eb.EGG_ACT_GELU, Wd, Xd, U2)
@@ -260,15 +269,15 @@ def test_chained_layers_next_projection_from_the_epilogue(ctx):
     # its by-product: the stored rows times the next layer's factors B', per member.  B' as the noise entry point writes it
     # (held to the oracle's stream in test_gpu_noise: a bf16 factor may be the neighbouring rounding of the same normal for
     # about 1e-5 of the entries, and one such entry moves a projection by 1e-3), rows as this call stored them.
-    Bn = torch.empty((N, ff, 1), dtype=torch.bfloat16, device="cuda")
-    ctx.eggroll_noise_gen(eb.make_key(3, 1, l_dn), eb.make_shape(mb, N, S, d, ff, 1), eb.EGG_BF16, eb.EGG_NORMAL, 0, None, Bn)
+    Bn = torch.empty((N, ff, rank), dtype=torch.bfloat16, device="cuda")
+    ctx.eggroll_noise_gen(eb.make_key(3, 1, l_dn), s_dn, eb.EGG_BF16, eb.EGG_NORMAL, 0, None, Bn)
     torch.cuda.synchronize()
-    Bn = to_numpy(Bn).astype(np.float64)[:, :, 0]
-    Bo = np.stack([oracle.noise_matrix(3, 1, l_dn, 1, mb + m, ff, 1, oracle.NOISE_BF16)[:, 0] for m in range(0, N, 37)])
+    Bn = to_numpy(Bn).astype(np.float64)
+    Bo = np.stack([oracle.noise_matrix(3, 1, l_dn, 1, mb + m, ff, rank, oracle.NOISE_BF16) for m in range(0, N, 37)])
     assert (Bn[::37] != Bo).mean() < 1e-3 and np.abs(Bn[::37] - Bo).max() <= 2.0 ** -7 * np.abs(Bo).max()
     un = to_numpy(U).astype(np.float64).reshape(N, S, ff)
-    t_ref = np.einsum("msf,mf->ms", un, Bn)
-    got = t_next.cpu().numpy().astype(np.float64).reshape(N, S)
+    t_ref = np.einsum("msf,mfl->msl", un, Bn)
+    got = t_next.cpu().numpy().astype(np.float64).reshape(N, S, rank)
     assert np.isfinite(got).all()
     assert (np.abs(got - t_ref) <= 2e-5 * (np.abs(t_ref) + np.sqrt(np.mean(t_ref ** 2)))).all()
     # the next layer on those projections: same result as with its own projection pass, and right by the oracle
@@ -276,14 +285,14 @@ def test_chained_layers_next_projection_from_the_epilogue(ctx):
     ctx.eggroll_perturbed_forward_chained(key_dn, s_dn, sigma, eb.EGG_ACT_NONE, W2d, U, Y1, t_in=t_next)
     ctx.eggroll_perturbed_forward(key_dn, s_dn, sigma, eb.EGG_ACT_NONE, W2d, U, Y2)
     torch.cuda.synchronize()
-    ref2 = oracle.forward(3, 1, l_dn, mb, N, S, d, ff, 1, oracle.NOISE_BF16, sigma, 0, W2, to_numpy(U))
+    ref2 = oracle.forward(3, 1, l_dn, mb, N, S, d, ff, rank, oracle.NOISE_BF16, sigma, 0, W2, to_numpy(U))
     assert_close(to_numpy(Y1), ref2, 1e-2, "down-projection on delivered projections")
     same_bits_or_reordered_sum(Y1, Y2, False, "delivered against own projections")
     # forms that do not exist are refused before anything runs
     with pytest.raises(eb.EggrollError):
-        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, N, S, ff, d, 2), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
+        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, N, S, ff, d, 8), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
     with pytest.raises(eb.EggrollError):
-        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, 8, S, ff, d, 1), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
+        ctx.eggroll_perturbed_forward_chained(key_up, eb.make_shape(mb, 8, S, ff, d, rank), sigma, eb.EGG_ACT_GELU, Wd, Xd, U, next_layer=l_dn, t_next=t_next)
 
 
 # ---------------------------------------------------------------------------------------------------------
@@ -295,7 +304,7 @@ def _decoder_inputs(V, d, ff, L, N, S, seed):
 
 def same_bits_or_reordered_sum(got, want, exact, what):
     """The driver against the chain of single-layer calls.  Where the up-projection's epilogue forms the down-projection's
-    projections itself (rank 1, 64 | S, enough tiles), those are summed in another order than the projection pass sums
+    projections itself (rank 1, 2 or 4, 64 | S, enough tiles), those are summed in another order than the projection pass sums
     them: a few outputs then sit on the other side of a bf16 rounding boundary; everywhere else the bits are the same."""
     import torch
     if exact:
