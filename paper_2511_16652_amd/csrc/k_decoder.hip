@@ -290,10 +290,9 @@ __global__ __launch_bounds__(512) void attention_kernel(const uint16_t* __restri
             if (qrow < S) *(uint2*)(orow + mb * 32 + 8 * q + 4 * h) = o;
             if (Bo) {
                 const uint2 bv = *(const uint2*)(sB + (mb * 32 + 8 * q + 4 * h) * 2);
-                tp = fmaf(bf16_lo(o.x), bf16_lo(bv.x), tp);
-                tp = fmaf(bf16_hi(o.x), bf16_hi(bv.x), tp);
-                tp = fmaf(bf16_lo(o.y), bf16_lo(bv.y), tp);
-                tp = fmaf(bf16_hi(o.y), bf16_hi(bv.y), tp);
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                tp = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.x), __builtin_bit_cast(bf16x2_t, bv.x), tp, false);
+                tp = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.y), __builtin_bit_cast(bf16x2_t, bv.y), tp, false);
             }
         }
     if (Bo) {
