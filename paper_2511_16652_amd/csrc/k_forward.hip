@@ -130,6 +130,21 @@ struct FwdEpi {
     uint32_t nb[PROJ_ROWS ? 8 : 1][2];
     uint32_t bp[PROJ_FLUSH ? RANK : 1][4];
     float tn = 0.f;  // rank 1: the lane's part of t'[n] for the current column
+    // Store-only epilogue with residual: the lane's 8 residual pieces (4 bf16 each, one per row block) of the current
+    // column block, and those of the next one, on their way while the current block is converted and staged.  Loaded
+    // unconditionally from clamped addresses: a predicated load is a branch, and the counted waits behind a branch
+    // degrade to "everything outstanding" -- the first version waited out one memory round trip per piece.
+    static constexpr bool RESID = LEAN != 0 && (LEAN & LEAN_RESID) != 0;
+    uint2 rcur[RESID ? 8 : 1], rnext[RESID ? 8 : 1];
+    int res_m0 = 0, res_rows = 0;  // first row of the lane's pieces in the wave tile; rows of the output (for the clamp)
+    __device__ __forceinline__ void load_residual(int n)
+    {
+        if constexpr (RESID) {
+            const uint16_t* rrow = (const uint16_t*)a.resid + (int64_t)min(n, res_rows - 1) * a.d_out;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rnext[i] = *(const uint2*)(rrow + min(res_m0 + i * BLK, a.d_out - 4));
+        }
+    }
     // prefetched A rows of the lane, per (row block, group of CORR_COLS columns that share one member), and the
     // prefetched t of the lane's columns, per column block.  With 16x16 blocks a wave tile has twice the row
     // blocks; one member per 64 columns (the width of every wave tile launched here) keeps the register count.
@@ -206,6 +221,12 @@ struct FwdEpi {
     template <class MT, int MB, int NB>
     __device__ __forceinline__ void extra_mma(typename MT::acc_t (&acc)[MB][NB], int mw0, int nw0, int lane, int n_rows)
     {
+        if constexpr (RESID) {
+            static_assert(MB == 8 && BLK == 16, "eight row blocks of 16 per wave tile");
+            res_m0 = mw0 + (lane / BLK) * 4;
+            res_rows = n_rows;
+            load_residual(nw0 + (lane & (BLK - 1)));  // column block 0; older than the next tile's loads, so a wait for it waits for nothing else
+        }
         if constexpr (!REGEN && BF16 && RANK <= 8) {
             if (!a.mma_corr) return;
             if constexpr (LEAN != 0) {
@@ -331,6 +352,11 @@ struct FwdEpi {
     __device__ __forceinline__ void column(int n, bool valid)
     {
         if constexpr (PROJ_ROWS) tn = 0.f;
+        if constexpr (RESID) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rcur[i] = rnext[i];
+            load_residual(n + BLK);  // the next column block (past the last one: a clamped re-read that is never used)
+        }
         if constexpr (LEAN != 0) return;
         if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
@@ -355,6 +381,14 @@ struct FwdEpi {
                 }
             }
             sty.put(a.wtm_pitch, ml, p0, p1);
+        } else if constexpr (RESID) {
+            float y[4] = {v[0], v[1], v[2], v[3]};
+            if constexpr ((LEAN & LEAN_GELU) != 0) gelu_bf16_grade4(y);
+            // each output element is read here and written by flush exactly once, so Y may be the residual buffer itself
+            // (rows and columns past the end hold clamped copies and are never stored)
+            y[0] += bf16_lo(rcur[I].x); y[1] += bf16_hi(rcur[I].x);
+            y[2] += bf16_lo(rcur[I].y); y[3] += bf16_hi(rcur[I].y);
+            sty.put(a.wtm_pitch, ml, pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
         } else {
             store4(m, n, v, valid, ml);
         }
