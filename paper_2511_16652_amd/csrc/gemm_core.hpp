@@ -235,7 +235,7 @@ constexpr size_t gemm_lds_bytes()
 // Epi requirements:
 //   struct Args (trivially copyable);  static constexpr int lds_per_wave(int wtm);
 //   __device__ Epi(const Args&, char* wave_lds_slice, int lane);
-//   __device__ void column(int n, bool valid);                       called once per owned column
+//   __device__ void column(int n, bool valid);                       called once per owned column (persistent kernel: column_at<J>, store4_at<I, J>)
 //   __device__ void store4(int m, int n, const T (&v)[4], bool col_valid, int ml);  rows m..m+3 of column n
 //   template <int WTM> __device__ void flush(int mw0, int nb0, int n_rows);   after each 32-column block
 //   template <int MB, int NB> __device__ void prefetch(int mw0, int nw0, int lane, int n_rows);   late in the main loop
@@ -622,8 +622,11 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_persistent_kernel(Oper
         // the barrier of the last stage had every wave's last fragment reads behind it: both stage buffers are free
         const int cm0 = m0, cn0 = n0;  // the finished tile
         const int next = tile + (int)gridDim.x;
-        if (next < total) {
-            tile_coords(next, tiles_m, tiles_n, tm, tn);
+        {
+            // Straight-line on purpose (past its last tile a workgroup fetches the finished tile's stages again, unused):
+            // behind a branch the compiler can no longer count these loads, and every wait of the epilogue for a load of
+            // its own would become a wait for all of them.
+            tile_coords(next < total ? next : tile, tiles_m, tiles_n, tm, tn);
             m0 = tm * BM;
             n0 = tn * BN;
             pb = P.base + (int64_t)m0 * P.row_stride;
@@ -636,14 +639,14 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_nt_persistent_kernel(Oper
             constexpr int j = decltype(jc)::value;
             const int n = cn0 + wn * WTN + j * BLK + (lane_e & (BLK - 1));
             const bool nvalid = n < Q.rows;
-            epi.column(n, nvalid);
+            epi.template column_at<j>(n, nvalid);
             static_for<0, MB>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value;
                 const int ml = i * BLK + (lane_e >> 4) * 4;
                 typename Epi::value_t v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
-                epi.template store4_at<i>(cm0 + wm * WTM + ml, n, v, nvalid, ml);
+                epi.template store4_at<i, j>(cm0 + wm * WTM + ml, n, v, nvalid, ml);
             });
             epi.template flush<WTM>(cm0 + wm * WTM, cn0 + wn * WTN + j * BLK, Q.rows);
         });

@@ -135,14 +135,17 @@ struct FwdEpi {
     // unconditionally from clamped addresses: a predicated load is a branch, and the counted waits behind a branch
     // degrade to "everything outstanding" -- the first version waited out one memory round trip per piece.
     static constexpr bool RESID = LEAN != 0 && (LEAN & LEAN_RESID) != 0;
-    uint2 rcur[RESID ? 8 : 1], rnext[RESID ? 8 : 1];
+    // Two sets, used alternately by the column blocks (named at compile time: no copies between them, which the scheduler
+    // would be free to hoist, with their wait, to right behind the loads).
+    uint2 rres[RESID ? 2 : 1][RESID ? 8 : 1];
     int res_m0 = 0, res_rows = 0;  // first row of the lane's pieces in the wave tile; rows of the output (for the clamp)
+    template <int SET>
     __device__ __forceinline__ void load_residual(int n)
     {
         if constexpr (RESID) {
             const uint16_t* rrow = (const uint16_t*)a.resid + (int64_t)min(n, res_rows - 1) * a.d_out;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rnext[i] = *(const uint2*)(rrow + min(res_m0 + i * BLK, a.d_out - 4));
+            for (int i = 0; i < 8; ++i) rres[SET][i] = *(const uint2*)(rrow + min(res_m0 + i * BLK, a.d_out - 4));
         }
     }
     // prefetched A rows of the lane, per (row block, group of CORR_COLS columns that share one member), and the
@@ -225,7 +228,7 @@ struct FwdEpi {
             static_assert(MB == 8 && BLK == 16, "eight row blocks of 16 per wave tile");
             res_m0 = mw0 + (lane / BLK) * 4;
             res_rows = n_rows;
-            load_residual(nw0 + (lane & (BLK - 1)));  // column block 0; older than the next tile's loads, so a wait for it waits for nothing else
+            load_residual<0>(nw0 + (lane & (BLK - 1)));  // column block 0; older than the next tile's loads, so a wait for it waits for nothing else
         }
         if constexpr (!REGEN && BF16 && RANK <= 8) {
             if (!a.mma_corr) return;
@@ -349,14 +352,17 @@ struct FwdEpi {
     {
     }
 
+    // the persistent kernel names the column block
+    template <int J>
+    __device__ __forceinline__ void column_at(int n, bool valid)
+    {
+        column(n, valid);
+        if constexpr (RESID) load_residual<(J + 1) & 1>(n + BLK);  // the next column block (past the last one: a clamped re-read that is never used)
+    }
+
     __device__ __forceinline__ void column(int n, bool valid)
     {
         if constexpr (PROJ_ROWS) tn = 0.f;
-        if constexpr (RESID) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) rcur[i] = rnext[i];
-            load_residual(n + BLK);  // the next column block (past the last one: a clamped re-read that is never used)
-        }
         if constexpr (LEAN != 0) return;
         if (!valid || a.c == 0.f || (!REGEN && a.mma_corr)) return;
         ml_member = n / a.S;
@@ -366,7 +372,7 @@ struct FwdEpi {
     }
 
     // the persistent kernel names the row block (a compile-time index into per-block registers)
-    template <int I>
+    template <int I, int J = 0>
     __device__ __forceinline__ void store4_at(int m, int n, const float (&v)[4], bool valid, int ml)
     {
         if constexpr (PROJ) {
@@ -386,8 +392,8 @@ struct FwdEpi {
             if constexpr ((LEAN & LEAN_GELU) != 0) gelu_bf16_grade4(y);
             // each output element is read here and written by flush exactly once, so Y may be the residual buffer itself
             // (rows and columns past the end hold clamped copies and are never stored)
-            y[0] += bf16_lo(rcur[I].x); y[1] += bf16_hi(rcur[I].x);
-            y[2] += bf16_lo(rcur[I].y); y[3] += bf16_hi(rcur[I].y);
+            y[0] += bf16_lo(rres[J & 1][I].x); y[1] += bf16_hi(rres[J & 1][I].x);
+            y[2] += bf16_lo(rres[J & 1][I].y); y[3] += bf16_hi(rres[J & 1][I].y);
             sty.put(a.wtm_pitch, ml, pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
         } else {
             store4(m, n, v, valid, ml);
