@@ -248,6 +248,18 @@ constexpr size_t gemm_lds_bytes()
 // middle of k-step 3; right behind it the direct-to-LDS loads of stage kt+2 go out into the buffer the
 // barrier retired, and the first fragments of stage kt+1 are read.
 // KMAJOR: both operands are K-packed panels (chunk-major stages); otherwise row-major operands.
+// an epilogue may take the column block as a compile-time index (column_at<J>) instead of column()
+template <class E, int J, class = void>
+struct has_column_at : std::false_type {};
+template <class E, int J>
+struct has_column_at<E, J, std::void_t<decltype(std::declval<E&>().template column_at<J>(0, true))>> : std::true_type {};
+template <int J, class E>
+__device__ __forceinline__ void epi_column(E& e, int n, bool valid)
+{
+    if constexpr (has_column_at<E, J>::value) e.template column_at<J>(n, valid);
+    else e.column(n, valid);
+}
+
 template <class MT, int BM, int BN, int WM, int WN, bool KMAJOR, class Epi, int WG_PER_CU = 1>
 __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand P, Operand Q, int kchunks, int tiles_m,
                                                                    int tiles_n, int ksplit, const char* zero_page,
@@ -435,7 +447,7 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
         constexpr int j = decltype(jc)::value;
         const int n = n0 + wn * WTN + j * BLK + (lane & (BLK - 1));
         const bool nvalid = n < Q.rows;
-        epi.column(n, nvalid);
+        epi_column<j>(epi, n, nvalid);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
 #pragma unroll

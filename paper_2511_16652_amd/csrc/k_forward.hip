@@ -210,6 +210,13 @@ struct FwdEpi {
                                                      (egg_lds_void*)(sty.base + LDS_NB + k * 256), 4, 0, 0);
                 }
             }
+        } else if constexpr (REGEN && BF16) {
+            // one row per member, factors regenerated in registers: the projections of the lane's columns are all the
+            // epilogue reads; fetched here (clamped, unconditional), they arrive under the last stage instead of one memory
+            // round trip per column block
+            static_assert(NB <= PF_NB, "prefetch storage");
+            if (a.c == 0.f) return;  // unperturbed: there are no projections (t is NULL)
+            fetch_t<NB>(nw0, lane, n_rows);
         } else if constexpr (!REGEN && BF16 && PREFETCH) {
             static_assert(MB <= PF_MB && NB <= PF_NB && NB * BLK <= PF_NG * CORR_COLS, "prefetch storage");
             if (!a.mma_corr) return;
@@ -356,7 +363,16 @@ struct FwdEpi {
     template <int J>
     __device__ __forceinline__ void column_at(int n, bool valid)
     {
-        column(n, valid);
+        if constexpr (REGEN && BF16 && LEAN == 0) {
+            static_assert(J < PF_NB, "prefetch storage");
+            if (!valid || a.c == 0.f) return;
+            ml_member = n / a.S;
+            member = a.member_begin + (uint32_t)ml_member;
+#pragma unroll
+            for (int l = 0; l < RANK; ++l) tc[l] = a.c * pf_t[J][l];  // fetched by prefetch()
+        } else {
+            column(n, valid);
+        }
         if constexpr (RESID) load_residual<(J + 1) & 1>(n + BLK);  // the next column block (past the last one: a clamped re-read that is never used)
     }
 
