@@ -253,6 +253,17 @@ template <class E, int J, class = void>
 struct has_column_at : std::false_type {};
 template <class E, int J>
 struct has_column_at<E, J, std::void_t<decltype(std::declval<E&>().template column_at<J>(0, true))>> : std::true_type {};
+// ... and the row block and group of a store (store4_blk<I, Q>) instead of store4()
+template <class E, class = void>
+struct has_store4_blk : std::false_type {};
+template <class E>
+struct has_store4_blk<E, std::void_t<decltype(&E::template store4_blk<0, 0>)>> : std::true_type {};
+template <int I, int Q, class E, class V>
+__device__ __forceinline__ void epi_store4(E& e, int m, int n, const V (&v)[4], bool valid, int ml)
+{
+    if constexpr (has_store4_blk<E>::value) e.template store4_blk<I, Q>(m, n, v, valid, ml);
+    else e.store4(m, n, v, valid, ml);
+}
 template <int J, class E>
 __device__ __forceinline__ void epi_column(E& e, int n, bool valid)
 {
@@ -448,18 +459,18 @@ __global__ __launch_bounds__(WM* WN * 64, WG_PER_CU) void gemm_nt_kernel(Operand
         const int n = n0 + wn * WTN + j * BLK + (lane & (BLK - 1));
         const bool nvalid = n < Q.rows;
         epi_column<j>(epi, n, nvalid);
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-#pragma unroll
-            for (int q = 0; q < (BLK == 32 ? 4 : 1); ++q) {
+        static_for<0, MB>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            static_for<0, (BLK == 32 ? 4 : 1)>([&](auto qc) __attribute__((always_inline)) {
+                constexpr int q = decltype(qc)::value;
                 // 32x32 block: four groups of 4 rows, 8 apart, offset by the lane half; 16x16: rows 4 (lane>>4) ..+3
                 const int ml = i * BLK + (BLK == 32 ? q * 8 + (lane >> 5) * 4 : (lane >> 4) * 4);  // row inside the wave tile
                 typename Epi::value_t v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-                epi.store4(m0 + wm * WTM + ml, n, v, nvalid, ml);
-            }
-        }
+                epi_store4<i, q>(epi, m0 + wm * WTM + ml, n, v, nvalid, ml);
+            });
+        });
         epi.template flush<WTM>(m0 + wm * WTM, n0 + wn * WTN + j * BLK, Q.rows);
     });
 }

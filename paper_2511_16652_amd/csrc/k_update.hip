@@ -192,21 +192,45 @@ __global__ __launch_bounds__(256) void gen_pack_r1_kernel(StreamKey key, uint32_
     o[1] = c1;
 }
 
-struct UpdEpi {
+struct UpdArgs {
+    float* G;
+    void* W;
+    const float* fnorm;
+    int d_out, d_in;
+    float scale, lr;
+    int accumulate, w_bf16;
+};
+
+// MBLK: row blocks (of 32) per wave tile.  G is row-major [d_out][d_in] and a column n is one k: the 32 lanes of a
+// half-wave already write 32 consecutive floats of one G row, so no staging is needed.
+template <int MBLK>
+struct UpdEpiT {
     typedef float value_t;
-    struct Args {
-        float* G;
-        void* W;
-        const float* fnorm;
-        int d_out, d_in;
-        float scale, lr;
-        int accumulate, w_bf16;
-    };
+    typedef UpdArgs Args;
     const Args a;
     float scale;
+    // W += lr G: the lane's MBLK x 16 elements of W in the current column block, read in one batch when the block begins
+    // (unconditional loads from clamped addresses; one load and one full wait per element otherwise)
+    float wv[MBLK * 16];
+    int row0 = 0;  // the lane's first row of the wave tile
     static constexpr __host__ __device__ int lds_per_wave(int) { return 0; }
-    __device__ __forceinline__ UpdEpi(const Args& a_, char*, int) : a(a_) { scale = a.scale * a.fnorm[0]; }
+    __device__ __forceinline__ UpdEpiT(const Args& a_, char*, int) : a(a_) { scale = a.scale * a.fnorm[0]; }
     __device__ __forceinline__ void column(int, bool) {}
+    template <int J>
+    __device__ __forceinline__ void column_at(int n, bool)
+    {
+        if (!a.W) return;
+        const int64_t nc = min(n, a.d_in - 1);
+        if (a.w_bf16) {
+            const uint16_t* w = (const uint16_t*)a.W + nc;
+#pragma unroll
+            for (int k = 0; k < MBLK * 16; ++k) wv[k] = bf16_bits_to_f32(w[(int64_t)min(row0 + (k >> 4) * 32 + ((k >> 2) & 3) * 8 + (k & 3), a.d_out - 1) * a.d_in]);
+        } else {
+            const float* w = (const float*)a.W + nc;
+#pragma unroll
+            for (int k = 0; k < MBLK * 16; ++k) wv[k] = w[(int64_t)min(row0 + (k >> 4) * 32 + ((k >> 2) & 3) * 8 + (k & 3), a.d_out - 1) * a.d_in];
+        }
+    }
     template <int WTM>
     __device__ __forceinline__ void flush(int, int, int) {}
     template <int NT, int BM, int BN>
@@ -214,10 +238,14 @@ struct UpdEpi {
     template <class MT, int MB, int NB>
     __device__ __forceinline__ void extra_mma(typename MT::acc_t (&)[MB][NB], int, int, int, int) {}
     template <int MB, int NB>
-    __device__ __forceinline__ void prefetch(int, int, int, int) {}
-    // G is row-major [d_out][d_in] and a column n is one k: the 32 lanes of a half-wave already write
-    // 32 consecutive floats of one G row, so no staging is needed
-    __device__ __forceinline__ void store4(int m, int n, const float (&v)[4], bool valid, int)
+    __device__ __forceinline__ void prefetch(int mw0, int, int lane, int)
+    {
+        static_assert(MB == MBLK, "row blocks per wave tile");
+        row0 = mw0 + (lane >> 5) * 4;
+    }
+    // rows m .. m + 3 (row block I, group Q of the block) of column n
+    template <int I, int Q>
+    __device__ __forceinline__ void store4_blk(int m, int n, const float (&v)[4], bool valid, int)
     {
         if (!valid || m >= a.d_out) return;
 #pragma unroll
@@ -227,13 +255,9 @@ struct UpdEpi {
             if (a.accumulate) g += a.G[idx];
             a.G[idx] = g;
             if (a.W) {
-                if (a.w_bf16) {
-                    uint16_t* w = (uint16_t*)a.W + idx;
-                    *w = f32_to_bf16_bits(fmaf(a.lr, g, bf16_bits_to_f32(*w)));
-                } else {
-                    float* w = (float*)a.W + idx;
-                    *w = fmaf(a.lr, g, *w);
-                }
+                const float w_new = fmaf(a.lr, g, wv[(I * 4 + Q) * 4 + e]);
+                if (a.w_bf16) ((uint16_t*)a.W)[idx] = f32_to_bf16_bits(w_new);
+                else ((float*)a.W)[idx] = w_new;
             }
         }
     }
@@ -241,12 +265,13 @@ struct UpdEpi {
 
 template <class MT, int BM, int BN, int WM, int WN>
 static egg_status launch_upd_gemm(eggroll_ctx* c, const char* name, const Operand& P, const Operand& Q, int kchunks,
-                                  const UpdEpi::Args& ea)
+                                  const UpdArgs& ea)
 {
     const int tiles_m = (P.rows + BM - 1) / BM, tiles_n = (Q.rows + BN - 1) / BN;
     const size_t lds = gemm_lds_bytes<BM, BN>();
     if (!operand_offsets_fit(P, BM) || !operand_offsets_fit(Q, BN)) return fail(c, EGG_EUNSUPPORTED, "operand strides too large for 32-bit tile offsets");
-    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpi>;
+    static_assert(MT::BLK == 32, "the epilogue indexes 32-row blocks");
+    auto kern = gemm_nt_kernel<MT, BM, BN, WM, WN, true, UpdEpiT<BM / WM / 32>>;
     egg_status st = ensure_dynamic_lds(c, (const void*)kern, (size_t)lds, "gemm smem attr");
     if (st != EGG_OK) return st;
     KernelScope ks(c, name);
@@ -324,7 +349,7 @@ egg_status launch_update(eggroll_ctx* c, const StreamKey& ka, const StreamKey& k
 
     Operand P{(const char*)c->pack_a.p, 16, (int64_t)s.d_out * 16, s.d_out};
     Operand Q{(const char*)(b_panel ? B_cache : c->pack_b.p), 16, (int64_t)s.d_in * 16, s.d_in};
-    UpdEpi::Args ea{G, W, fnorm, s.d_out, s.d_in, scale, lr, accumulate, w_dtype == EGG_BF16 ? 1 : 0};
+    UpdArgs ea{G, W, fnorm, s.d_out, s.d_in, scale, lr, accumulate, w_dtype == EGG_BF16 ? 1 : 0};
     if (bf) {
         const int64_t big_tiles = ((s.d_out + 255) / 256) * (int64_t)((s.d_in + 255) / 256);
         if (big_tiles >= 192) return launch_upd_gemm<MmaF16, 256, 256, 2, 4>(c, "update_gemm_f16", P, Q, (int)kgroups, ea);
