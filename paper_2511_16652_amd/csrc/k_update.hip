@@ -57,6 +57,50 @@ __global__ __launch_bounds__(256) void pack_kernel(const void* __restrict__ src,
     const int64_t K = members * rank;
     const float finv = fitness ? fnorm[1] : 1.f;
     float v[EPC];
+    if constexpr (BF16) {
+        // rank 2, 4 or 8: the 8 values are 8 / rank members x rank contiguous bf16; one load per member, issued
+        // unconditionally from clamped addresses (members past the end count with factor 0)
+        if (rank == 2 || rank == 4 || rank == 8) {
+            uint32_t w[4];
+            float fs[4];
+            bool in[4];  // the member of word h exists
+            if (rank == 8) {
+                const int64_t i = kg, ic = min(i, members - 1);
+                const u32x4 t = *(const u32x4*)((const uint16_t*)src + (ic * d + col) * 8);
+                w[0] = t[0]; w[1] = t[1]; w[2] = t[2]; w[3] = t[3];
+                fs[0] = fs[1] = fs[2] = fs[3] = fitness ? fitness[ic] * finv : 1.f;
+                in[0] = in[1] = in[2] = in[3] = i < members;
+            } else if (rank == 4) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int64_t i = kg * 2 + h, ic = min(i, members - 1);
+                    const uint2 t = *(const uint2*)((const uint16_t*)src + (ic * d + col) * 4);
+                    w[2 * h] = t.x; w[2 * h + 1] = t.y;
+                    fs[2 * h] = fs[2 * h + 1] = fitness ? fitness[ic] * finv : 1.f;
+                    in[2 * h] = in[2 * h + 1] = i < members;
+                }
+            } else {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const int64_t i = kg * 4 + h, ic = min(i, members - 1);
+                    w[h] = *(const uint32_t*)((const uint16_t*)src + (ic * d + col) * 2);
+                    fs[h] = fitness ? fitness[ic] * finv : 1.f;
+                    in[h] = i < members;
+                }
+            }
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            u32x4 o;
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                h2 p;
+                p[0] = (_Float16)(in[h] ? bf16_lo(w[h]) * fs[h] : 0.f);  // round to nearest even; past the last member: +0
+                p[1] = (_Float16)(in[h] ? bf16_hi(w[h]) * fs[h] : 0.f);
+                o[h] = __builtin_bit_cast(uint32_t, p);
+            }
+            ((u32x4*)out)[gid] = o;
+            return;
+        }
+    }
 #pragma unroll
     for (int e = 0; e < EPC; ++e) {
         const int64_t kappa = kg * EPC + e;
