@@ -28,15 +28,20 @@ __global__ __launch_bounds__(256) void pack_i8_kernel(const int8_t* __restrict__
     const int64_t kg = gid / cgroups;
     const int col0 = (int)(gid - kg * cgroups) * 16;
     u32x4 x[16];  // [member] -> 16 column bytes, already multiplied by the member's fitness
+    // all 16 loads (and the 16 fitness bytes) go out before the first use: unconditional, from clamped member numbers --
+    // a load under "if (i < members)" is a branch and gets a full wait of its own
+    int fit[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int64_t i = kg * 16 + e, ic = min(i, members - 1);
+        x[e] = *(const u32x4*)(src + ic * d + col0);
+        fit[e] = F ? (int)F[ic] : 1;
+    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int64_t i = kg * 16 + e;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        int f = 0;
-        if (i < members) {
-            v = *(const u32x4*)(src + i * d + col0);
-            f = F ? (int)F[i] : 1;
-        }
+        const u32x4 v = x[e];
+        const int f = i < members ? fit[e] : 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             // bytewise negation without a carry between bytes: -b = (b ^ 0xFF) + 1 (no byte is -128)
