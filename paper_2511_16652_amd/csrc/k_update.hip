@@ -150,15 +150,21 @@ __global__ __launch_bounds__(256) void pack_r1_kernel(const void* __restrict__ s
     const int col0 = (int)(gid - kg * cgroups) * EPC;
     const float finv = fitness ? fnorm[1] : 1.f;
     float x[EPC][EPC];  // [member][column]
+    // every load of the thread goes out before the first use (unconditional, from clamped member numbers; members past
+    // the end count with factor 0, written as +0)
+    u32x4 raw[EPC];
+    float fsv[EPC];
 #pragma unroll
     for (int e = 0; e < EPC; ++e) {
-        const int64_t i = kg * EPC + e;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        float fs = 0.f;
-        if (i < members) {
-            v = *(const u32x4*)((const char*)src + (i * d + col0) * (BF16 ? 2 : 4));
-            fs = fitness ? fitness[i] * finv : 1.f;
-        }
+        const int64_t ic = min(kg * EPC + e, members - 1);
+        raw[e] = *(const u32x4*)((const char*)src + (ic * d + col0) * (BF16 ? 2 : 4));
+        fsv[e] = fitness ? fitness[ic] * finv : 1.f;
+    }
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+        const bool in = kg * EPC + e < members;
+        const u32x4 v = in ? raw[e] : u32x4{0u, 0u, 0u, 0u};
+        const float fs = in ? fsv[e] : 0.f;
         if constexpr (BF16) {
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
